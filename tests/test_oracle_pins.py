@@ -1,0 +1,433 @@
+"""CPU-only pins of the oracle: closed forms, invariants, library routines on special
+cases and brute force, chosen so that a plausible slip in the oracle (dropped term,
+wrong sign or index, transposed operand, wrong KL direction, wrong scale) fails one.
+The paper prints no worked numeric example, so there is no paper fixture to compare with."""
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.special as sp
+
+import oracle
+from oracle import BF16, CONF_PROB, CONF_THRESH, F32, FP8_E4M3, KL_PROB, KL_THRESH, TRUST
+from paper_2604_05250_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ storage decode
+def test_e4m3_decode_all_codes_closed_form_and_library():
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    lib_vals = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        got = oracle.decode_e4m3(c)
+        if e == 15 and m == 7:
+            assert math.isnan(got) and math.isnan(lib_vals[c])
+            continue
+        want = (m / 8.0) * 2.0 ** -6 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
+        want = -want if s else want
+        assert got == want == lib_vals[c], c
+    # hand-known values of the OCP format
+    assert oracle.decode_e4m3(0x7E) == 448.0 and oracle.decode_e4m3(0xFE) == -448.0
+    assert oracle.decode_e4m3(0x38) == 1.0 and oracle.decode_e4m3(0xC0) == -2.0
+    assert oracle.decode_e4m3(0x01) == 2.0 ** -9 and oracle.decode_e4m3(0x08) == 2.0 ** -6
+
+
+def test_bf16_decode_matches_library():
+    import torch
+    rng = np.random.default_rng(1)
+    bits = rng.integers(0, 0x7F80, size=2000).astype(np.uint16)
+    bits[::2] |= 0x8000
+    lib_vals = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([oracle.decode_bf16(int(b)) for b in bits])
+    assert np.array_equal(got, lib_vals)
+    assert oracle.decode_bf16(0x3F80) == 1.0 and oracle.decode_bf16(0xC000) == -2.0
+
+
+def test_workload_encoders_match_library_and_roundtrip():
+    import torch
+    rng = np.random.default_rng(2)
+    x = (rng.standard_normal(20000) * 3).astype(np.float32)
+    x[:8] = [0.0, -0.0, 1.0, -1.0, 1.00390625, 1.01171875, 3.3895314e38, 1e-40]
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(wl.f32_to_bf16_bits(x), want)
+    assert np.array_equal(wl.bf16_bits_to_f32(want), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
+    # fp8: all finite codes survive decode -> encode; random values match torch's RNE conversion
+    finite = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    vals = np.array([oracle.decode_e4m3(int(c)) for c in finite], dtype=np.float32)
+    enc = wl.f32_to_e4m3_bits(vals)
+    assert np.array_equal(enc & 0x7F, finite & 0x7F)
+    assert np.array_equal(enc[vals != 0], finite[vals != 0])
+    y = (rng.standard_normal(20000) * 100).astype(np.float32).clip(-448, 448)
+    y[:6] = [448.0, -448.0, 2.0 ** -10, 3 * 2.0 ** -10, 0.0155, 17.0]   # ties and subnormals
+    want8 = torch.from_numpy(y).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got8 = wl.f32_to_e4m3_bits(y)
+    nz = y != 0
+    assert np.array_equal(got8[nz], want8[nz])
+    assert wl.f32_to_e4m3_bits(np.array([1e6, -1e6], np.float32)).tolist() == [0x7E, 0xFE]   # saturates
+
+
+# ------------------------------------------------------------------ counter RNG
+def test_philox_known_answers():
+    n = 0
+    for line in open(os.path.join(GOLD, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        w = [int(t, 16) for t in line.split()]
+        assert oracle.philox4x32_10(w[0:4], w[4:6]) == w[6:10]
+        n += 1
+    assert n == 3
+
+
+def test_row_uniform_properties():
+    u0 = oracle.row_uniform(0, 0)
+    assert u0 == (0x6627e8d5 >> 8) / 2.0 ** 24          # first word of the all-zero known answer
+    us = np.array([oracle.row_uniform(7, i) for i in range(20000)])
+    assert (us >= 0).all() and (us < 1).all()
+    assert np.array_equal(us * 2 ** 24, np.floor(us * 2 ** 24))       # 24-bit grid
+    assert abs(us.mean() - 0.5) < 4 * (1 / math.sqrt(12 * 20000))
+    assert oracle.row_uniform(7, 5) == us[5] and oracle.row_uniform(8, 5) != us[5]
+    # high counter / key words are used
+    assert oracle.row_uniform(7, 5 + 2 ** 32) != us[5]
+    assert oracle.row_uniform(7 + 2 ** 32, 5) != us[5]
+
+
+# ------------------------------------------------------------------ softmax / confidence / argmax
+def _scores(ld, lv, dtype=F32, rows=None):
+    return oracle.verify_scores(None if ld is None else np.asarray(ld, np.float32),
+                                np.asarray(lv, np.float32), dtype, rows)
+
+
+def test_confidence_closed_forms():
+    V = 37
+    flat = np.zeros((1, V), np.float32)
+    kl, conf, tok = _scores(None, flat)
+    assert conf[0] == pytest.approx(1.0 / V, rel=1e-14) and tok[0] == 0 and math.isnan(kl[0])
+    for delta in (0.5, 3.0, 20.0):
+        lv = np.full((1, V), 1.25, np.float32)
+        lv[0, 11] += delta
+        _, conf, tok = _scores(None, lv)
+        assert conf[0] == pytest.approx(math.exp(delta) / (math.exp(delta) + V - 1), rel=1e-13)
+        assert tok[0] == 11
+    # overflow safety and shift invariance
+    rng = np.random.default_rng(3)
+    base = rng.standard_normal((4, 50)).astype(np.float32)
+    _, c0, t0 = _scores(None, base)
+    for shift in (80.0, -80.0, 1000.0):
+        _, c1, t1 = _scores(None, base + np.float32(shift))
+        assert np.all(np.isfinite(c1)) and np.array_equal(t0, t1)
+        assert np.allclose(c1, c0, rtol=1e-4)            # fp32 storage of shifted logits loses low bits
+    assert ((c0 > 0) & (c0 <= 1)).all()
+    # against the library softmax
+    assert np.allclose(c0, sp.softmax(base.astype(np.float64), axis=1).max(axis=1), rtol=1e-13)
+
+
+def test_argmax_lowest_index_on_ties():
+    lv = np.zeros((3, 16), np.float32)
+    lv[0, [5, 9, 12]] = 2.0
+    lv[1, :] = -1.0
+    lv[2, [15, 0]] = 7.0
+    _, _, tok = _scores(None, lv)
+    assert tok.tolist() == [5, 0, 0]
+    # bf16 storage: distinct fp32 values that collapse to one bf16 value tie
+    vals = np.array([[1.0, 1.001, 1.002, 0.5]], np.float32)
+    bits = wl.f32_to_bf16_bits(vals)
+    _, _, tok = oracle.verify_scores(None, bits, BF16)
+    assert tok[0] == 0
+
+
+def test_kl_closed_forms_and_direction():
+    # two-token vocabulary: Bernoulli KL, and it is KL(drafter || verifier), not the reverse
+    a, b = 1.3, -0.4          # drafter logit gap, verifier logit gap
+    ld = np.array([[a, 0.0]], np.float32)
+    lv = np.array([[b, 0.0]], np.float32)
+    p = 1 / (1 + math.exp(-float(np.float32(a))))
+    q = 1 / (1 + math.exp(-float(np.float32(b))))
+    want = p * math.log(p / q) + (1 - p) * math.log((1 - p) / (1 - q))
+    rev = q * math.log(q / p) + (1 - q) * math.log((1 - q) / (1 - p))
+    kl, _, _ = _scores(ld, lv)
+    assert kl[0] == pytest.approx(want, rel=1e-12)
+    assert abs(want - rev) > 1e-2                       # the test can tell the directions apart
+    # uniform drafter vs peaked verifier: KL = -log V - mean(log p_V)
+    V = 64
+    ld = np.zeros((1, V), np.float32)
+    lv = np.zeros((1, V), np.float32)
+    lv[0, 3] = 5.0
+    lse = math.log(math.exp(5.0) + V - 1)
+    want = -math.log(V) - ((5.0 - lse) + (V - 1) * (0.0 - lse)) / V
+    kl, _, _ = _scores(ld, lv)
+    assert kl[0] == pytest.approx(want, rel=1e-12)
+    # peaked drafter vs uniform verifier: KL = log V - H(p_D)
+    kl2, _, _ = _scores(lv, ld)
+    pd = sp.softmax(lv[0].astype(np.float64))
+    assert kl2[0] == pytest.approx(math.log(V) + float((pd * np.log(pd)).sum()), rel=1e-12)
+
+
+def test_kl_invariants_and_library():
+    rng = np.random.default_rng(4)
+    ld = (rng.standard_normal((16, 301)) * 2).astype(np.float32)
+    lv = (ld + rng.standard_normal((16, 301)).astype(np.float32) * 0.5).astype(np.float32)
+    kl, conf, tok = _scores(ld, lv)
+    assert (kl >= 0).all()
+    # natural log, library formulation
+    pd = sp.softmax(ld.astype(np.float64), axis=1)
+    pv = sp.softmax(lv.astype(np.float64), axis=1)
+    assert np.allclose(kl, sp.rel_entr(pd, pv).sum(axis=1), rtol=1e-11)
+    assert np.array_equal(tok, lv.argmax(axis=1))
+    # KL(p || p) = 0 exactly
+    kl0, _, _ = _scores(ld, ld)
+    assert np.array_equal(kl0, np.zeros(16))
+    # per-row constants leave KL unchanged (values chosen exactly representable after the shift)
+    ldq = np.round(ld * 64) / 64
+    lvq = np.round(lv * 64) / 64
+    k1, _, _ = _scores(ldq, lvq)
+    k2, _, _ = _scores(ldq + np.float32(8.0), lvq - np.float32(16.0))
+    assert np.allclose(k1, k2, rtol=1e-11)
+    # probabilities are normalised: sum_x exp(log p) = 1 is what makes KL >= 0 tight; check through
+    # the identity KL = sum p_D log p_D - sum p_D l_V + lse_V evaluated with library routines
+    alt = (pd * np.log(pd)).sum(1) - (pd * lv).sum(1) + sp.logsumexp(lv.astype(np.float64), axis=1)
+    assert np.allclose(kl, alt, rtol=1e-10)
+    # zero drafter probability contributes nothing (exp underflow), no NaN
+    ld3 = np.array([[0.0, -2000.0, 0.0]], np.float32)
+    lv3 = np.array([[0.0, 0.0, 0.0]], np.float32)
+    k3, _, _ = _scores(ld3, lv3)
+    assert k3[0] == pytest.approx(math.log(3) - math.log(2), rel=1e-12)
+
+
+def test_kl_small_perturbation_regime():
+    # verifier = drafter + sigma*eps with a diffuse drafter: KL ~ sigma^2 / 2 (coarse)
+    cfg = wl.CONFIGS[1]
+    inp = wl.verify_inputs(cfg, seed=0)
+    kl, conf, _ = oracle.verify_scores(inp["logits_d"], inp["logits_v"], F32)
+    assert 0.08 < kl.mean() < 0.18
+    assert (conf < 0.9).all()
+
+
+def test_rows_subset_equals_full():
+    cfg = wl.CONFIGS[1]
+    inp = wl.verify_inputs(cfg, seed=0)
+    full = oracle.verify_scores(inp["logits_d"], inp["logits_v"], F32)
+    sub = oracle.verify_scores(inp["logits_d"], inp["logits_v"], F32, rows=[5, 0, 63])
+    for f, s in zip(full, sub):
+        assert np.array_equal(f[[5, 0, 63]], s)
+
+
+# ------------------------------------------------------------------ remask rules
+def test_trust_changes_nothing_and_reports_verifier_argmax():
+    cfg = wl.CONFIGS[1]
+    inp = wl.verify_inputs(cfg, seed=0)
+    mask = (np.arange(cfg.P) % 3 == 0).astype(np.uint8)
+    out = oracle.verify_remask(None, inp["logits_v"], mask, TRUST, 0.0, 0, cfg.B, cfg.G, F32)
+    assert np.array_equal(out["out_mask"], mask)
+    assert np.array_equal(out["out_tokens"], inp["logits_v"].argmax(axis=1))
+    assert np.allclose(out["out_scores"], sp.softmax(inp["logits_v"].astype(np.float64), axis=1).max(1), rtol=1e-6)
+
+
+def test_threshold_rules_strict_monotone_and_eligibility():
+    score = np.array([0.1, 0.3, 0.30000001, 0.5, 0.3, 0.9], np.float32)
+    mask = np.array([0, 0, 0, 0, 1, 1], np.uint8)
+    tau = np.float32(0.3)
+    om, _ = oracle.remask_decide(score, mask, KL_THRESH, tau, 0, 1, 6)
+    # strictly greater; equality keeps; masked rows stay masked whatever their score
+    assert om.tolist() == [0, 0, int(np.float32(0.30000001) > tau), 1, 1, 1]
+    oc, _ = oracle.remask_decide(score, mask, CONF_THRESH, tau, 0, 1, 6)
+    assert oc.tolist() == [1, 0, 0, 0, 1, 1]
+    for mode, lo_all in ((KL_THRESH, True), (CONF_THRESH, False)):
+        a, _ = oracle.remask_decide(score, mask, mode, -np.inf, 0, 1, 6)
+        b, _ = oracle.remask_decide(score, mask, mode, np.inf, 0, 1, 6)
+        all_elig, none_elig = np.ones(6, np.uint8), mask
+        assert np.array_equal(a, all_elig if lo_all else none_elig)
+        assert np.array_equal(b, none_elig if lo_all else all_elig)
+    prev = None
+    for t in np.linspace(0, 1, 21):
+        cur, _ = oracle.remask_decide(score, mask, KL_THRESH, t, 0, 1, 6)
+        if prev is not None:
+            assert (cur <= prev).all()                  # raising tau never remasks more
+        prev = cur
+
+
+def test_probabilistic_rules():
+    B, G = 3, 200
+    rng = np.random.default_rng(5)
+    kl = rng.random(B * G).astype(np.float32)
+    mask = (rng.random(B * G) < 0.25).astype(np.uint8)
+    om, prob = oracle.remask_decide(kl, mask, KL_PROB, 0.0, 11, B, G)
+    p = prob.reshape(B, G)
+    assert np.allclose(p.sum(axis=1), 1.0, rtol=1e-12)              # Eq. 6 normalises per sequence
+    elig = mask.reshape(B, G) == 0
+    want_p = np.where(elig, kl.reshape(B, G).astype(np.float64), 0)
+    want_p = want_p / want_p.sum(axis=1, keepdims=True)
+    assert np.allclose(p, want_p, rtol=1e-12)
+    u = np.array([oracle.row_uniform(11, i) for i in range(B * G)])
+    assert np.array_equal(om, ((mask != 0) | ((mask == 0) & (u < prob))).astype(np.uint8))
+    # all-zero divergences or no eligible rows: nothing is remasked
+    z, _ = oracle.remask_decide(np.zeros(B * G, np.float32), mask, KL_PROB, 0.0, 11, B, G)
+    assert np.array_equal(z, mask)
+    allm = np.ones(B * G, np.uint8)
+    z, _ = oracle.remask_decide(kl, allm, KL_PROB, 0.0, 11, B, G)
+    assert np.array_equal(z, allm)
+    # confidence: probability 1 - c; c = 1 never remasks, c = 0 always does
+    conf = np.concatenate([np.ones(100), np.zeros(100), np.full(400, 0.25)]).astype(np.float32)
+    m0 = np.zeros(600, np.uint8)
+    oc, pc = oracle.remask_decide(conf, m0, CONF_PROB, 0.0, 3, 1, 600)
+    assert oc[:100].sum() == 0 and oc[100:200].sum() == 100
+    assert np.allclose(pc, 1 - conf.astype(np.float64))
+    # empirical rate over many seeds, binomial 5-sigma bound
+    hits = sum(int(oracle.remask_decide(conf, m0, CONF_PROB, 0.0, s, 1, 600)[0][200:].sum()) for s in range(40))
+    n = 40 * 400
+    assert abs(hits / n - 0.75) < 5 * math.sqrt(0.75 * 0.25 / n)
+    # the seed matters only in the probabilistic modes
+    a, _ = oracle.remask_decide(kl, mask, KL_THRESH, 0.5, 1, B, G)
+    b, _ = oracle.remask_decide(kl, mask, KL_THRESH, 0.5, 2, B, G)
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ attention
+def _rand_qkv(rng, B, H, Hkv, N, d, Nq=None):
+    Nq = N if Nq is None else Nq
+    Q = rng.standard_normal((B, H, Nq, d)).astype(np.float32)
+    K = rng.standard_normal((B, Hkv, N, d)).astype(np.float32)
+    V = rng.standard_normal((B, Hkv, N, d)).astype(np.float32)
+    return Q, K, V
+
+
+def _numpy_attention(Q, K, V):
+    """Independent formulation: einsum + library softmax, fp64, MHA only."""
+    Q, K, V = (t.astype(np.float64) for t in (Q, K, V))
+    S = np.einsum("bhid,bhjd->bhij", Q, K) / math.sqrt(Q.shape[-1])
+    return np.einsum("bhij,bhjd->bhid", sp.softmax(S, axis=-1), V)
+
+
+def test_attention_brute_force_against_library_formulation():
+    rng = np.random.default_rng(6)
+    Q, K, V = _rand_qkv(rng, 2, 3, 3, 19, 8)
+    O = oracle.bidir_attention(Q, K, V, F32, F32)
+    assert np.allclose(O, _numpy_attention(Q, K, V), rtol=1e-12, atol=1e-14)
+    # non-square operands catch a transposed contraction: Nq != N through the block entry
+    Qb = rng.standard_normal((2, 3, 5, 8)).astype(np.float32)
+    Ob = oracle.block_attention_cached(Qb, K, V, 7, F32, F32)
+    assert np.allclose(Ob, _numpy_attention(Qb, K, V), rtol=1e-12, atol=1e-14)
+
+
+def test_attention_closed_forms():
+    rng = np.random.default_rng(7)
+    B, H, N, d = 1, 2, 33, 16
+    Q, K, V = _rand_qkv(rng, B, H, H, N, d)
+    # identical keys: uniform weights, O = mean(V)
+    Kc = np.broadcast_to(K[:, :, :1, :], K.shape).copy()
+    O = oracle.bidir_attention(Q, Kc, V, F32, F32)
+    assert np.allclose(O, V.astype(np.float64).mean(axis=2, keepdims=True), rtol=1e-12, atol=1e-14)
+    # N = 1: O = V
+    O1 = oracle.bidir_attention(Q[:, :, :1], K[:, :, :1], V[:, :, :1], F32, F32)
+    assert np.array_equal(O1, V[:, :, :1].astype(np.float64))
+    # two keys: weight of key 0 is sigmoid((q.k0 - q.k1)/sqrt(d)) -- pins the 1/sqrt(d_k) scale
+    q = rng.standard_normal((1, 1, 1, d)).astype(np.float32)
+    k2 = rng.standard_normal((1, 1, 2, d)).astype(np.float32)
+    v2 = rng.standard_normal((1, 1, 2, d)).astype(np.float32)
+    gap = float((q[0, 0, 0].astype(np.float64) * (k2[0, 0, 0].astype(np.float64) - k2[0, 0, 1])).sum()) / math.sqrt(d)
+    w0 = 1 / (1 + math.exp(-gap))
+    O2 = oracle.block_attention_cached(q, k2, v2, 0, F32, F32)     # one query, two keys
+    assert np.allclose(O2[0, 0, 0], w0 * v2[0, 0, 0].astype(np.float64) + (1 - w0) * v2[0, 0, 1].astype(np.float64), rtol=1e-12)
+    # a dominant key wins
+    Kd = K.copy()
+    Kd[0, 0, 5] = Q[0, 0, 3] * 50
+    Od = oracle.bidir_attention(Q, Kd, V, F32, F32)
+    assert np.allclose(Od[0, 0, 3], V[0, 0, 5], atol=1e-9)
+    # bidirectional: jointly permuting (K, V) rows changes nothing (no causal mask, no position)
+    perm = rng.permutation(N)
+    O = oracle.bidir_attention(Q, K, V, F32, F32)
+    Op = oracle.bidir_attention(Q, K[:, :, perm], V[:, :, perm], F32, F32)
+    assert np.allclose(O, Op, rtol=1e-11, atol=1e-13)
+    # every query sees the last key (a causal mask would hide it from query 0)
+    Vl = V.copy()
+    Vl[0, 0, N - 1] += 100.0
+    assert not np.allclose(oracle.bidir_attention(Q, K, Vl, F32, F32)[0, 0, 0], O[0, 0, 0])
+
+
+def test_attention_gqa_storage_types_and_scales():
+    rng = np.random.default_rng(8)
+    B, H, Hkv, N, d = 2, 4, 2, 21, 16
+    Q, K, V = _rand_qkv(rng, B, H, Hkv, N, d)
+    O = oracle.bidir_attention(Q, K, V, F32, F32)
+    # consecutive query heads share a kv head
+    Krep, Vrep = np.repeat(K, H // Hkv, axis=1), np.repeat(V, H // Hkv, axis=1)
+    assert np.allclose(O, _numpy_attention(Q, Krep, Vrep), rtol=1e-12, atol=1e-14)
+    # bf16 storage = the same computation on the rounded values
+    Qb, Kb, Vb = (wl.f32_to_bf16_bits(t) for t in (Q, K, V))
+    Ob = oracle.bidir_attention(Qb, Kb, Vb, BF16, BF16)
+    Oq = _numpy_attention(wl.bf16_bits_to_f32(Qb), np.repeat(wl.bf16_bits_to_f32(Kb), 2, 1),
+                          np.repeat(wl.bf16_bits_to_f32(Vb), 2, 1))
+    assert np.allclose(Ob, Oq, rtol=1e-12, atol=1e-14)
+    # fp8 codes with per-(batch, head) scales: real value = scale * decoded code
+    qs = (rng.random((B, H)) + 0.5).astype(np.float32) / 64
+    ks = (rng.random((B, Hkv)) + 0.5).astype(np.float32) / 64
+    Q8 = wl.f32_to_e4m3_bits(Q / qs[:, :, None, None])
+    K8 = wl.f32_to_e4m3_bits(K / ks[:, :, None, None])
+    table = np.array([oracle.decode_e4m3(c) for c in range(256)])
+    Qr = table[Q8] * qs[:, :, None, None].astype(np.float64)
+    Kr = table[K8] * ks[:, :, None, None].astype(np.float64)
+    O8 = oracle.bidir_attention(Q8, K8, Vb, FP8_E4M3, BF16, q_scale=qs, k_scale=ks)
+    S = np.einsum("bhid,bhjd->bhij", Qr, np.repeat(Kr, 2, 1)) / math.sqrt(d)
+    want = np.einsum("bhij,bhjd->bhid", sp.softmax(S, -1), np.repeat(wl.bf16_bits_to_f32(Vb).astype(np.float64), 2, 1))
+    assert np.allclose(O8, want, rtol=1e-12, atol=1e-14)
+    # sampled rows equal the full tensor's rows
+    rows = [(1, 3, 20), (0, 0, 0), (1, 2, 7)]
+    Os = oracle.bidir_attention(Q8, K8, Vb, FP8_E4M3, BF16, q_scale=qs, k_scale=ks, rows=rows)
+    for r, (b, h, i) in enumerate(rows):
+        assert np.array_equal(Os[r], O8[b, h, i])
+
+
+def test_block_attention_cache_semantics():
+    rng = np.random.default_rng(9)
+    B, H, Hkv, N, d, bl, bs = 2, 4, 2, 40, 16, 8, 24
+    Q, K, V = _rand_qkv(rng, B, H, Hkv, N, d)
+    full = oracle.bidir_attention(Q, K, V, F32, F32)
+    Qblk = np.ascontiguousarray(Q[:, :, bs:bs + bl])
+    # cache == current K/V: block output equals the same rows of full attention, bit for bit
+    O_in_place = oracle.block_attention_cached(Qblk, K, V, bs, F32, F32)
+    assert np.array_equal(O_in_place, full[:, :, bs:bs + bl])
+    Kblk = np.ascontiguousarray(K[:, :, bs:bs + bl]); Vblk = np.ascontiguousarray(V[:, :, bs:bs + bl])
+    # stale rows inside the block range of the cache are ignored when fresh block rows are given
+    Kst, Vst = K.copy(), V.copy()
+    Kst[:, :, bs:bs + bl] = 9.0
+    Vst[:, :, bs:bs + bl] = -9.0
+    O_fresh = oracle.block_attention_cached(Qblk, Kst, Vst, bs, F32, F32, Kblk=Kblk, Vblk=Vblk)
+    assert np.array_equal(O_fresh, full[:, :, bs:bs + bl])
+    # ... and used when they are not given
+    O_stale = oracle.block_attention_cached(Qblk, Kst, Vst, bs, F32, F32)
+    assert not np.allclose(O_stale, O_fresh)
+    # a cached row outside the block matters (prefix and suffix are both attended: DualCache)
+    for j in (0, N - 1):
+        Vp = V.copy()
+        Vp[:, :, j] += 3.0
+        assert not np.allclose(oracle.block_attention_cached(Qblk, K, Vp, bs, F32, F32), O_in_place)
+    # first and last block positions are legal; out-of-range blocks are rejected
+    oracle.block_attention_cached(Qblk, K, V, 0, F32, F32)
+    oracle.block_attention_cached(Qblk, K, V, N - bl, F32, F32)
+    with pytest.raises(ValueError):
+        oracle.block_attention_cached(Qblk, K, V, N - bl + 1, F32, F32)
+
+
+def test_workload_shapes_and_determinism():
+    cfg = wl.CONFIGS[1]
+    a = wl.attention_inputs(cfg, 0); b = wl.attention_inputs(cfg, 0); c = wl.attention_inputs(cfg, 1)
+    assert a["Q"].shape == (1, 4, 128, 64) and a["K"].shape == (1, 4, 128, 64)
+    assert np.array_equal(a["Q"], b["Q"]) and not np.array_equal(a["Q"], c["Q"])
+    v = wl.verify_inputs(cfg, 0)
+    assert v["logits_d"].shape == (64, 1024) and v["mask"].sum() == 0
+    assert np.array_equal(wl.verify_inputs(cfg, 0, rows=40)["logits_v"], v["logits_v"][:40])
+    assert abs(float(v["logits_d"].std()) - 2.0) < 0.05
+    assert abs(float((v["logits_v"] - v["logits_d"]).std()) - 0.5) < 0.02
+    assert [wl.block_start(cfg, k) for k in range(4)] == [64, 80, 96, 112]
+    c5 = wl.custom_config(B=2, H=4, Hkv=2, N=64, prompt=32, G=32, d=64, qk_dtype=FP8_E4M3, bl=16)
+    a5 = wl.attention_inputs(c5, 0)
+    assert a5["Q"].dtype == np.uint8 and a5["q_scale"].shape == (2, 4) and a5["k_scale"].shape == (2, 2)
+    assert (a5["Q"] & 0x7F).max() == 0x7E                 # amax maps to 448
+    kc = wl.cache_inputs(c5, 0)
+    blk = wl.block_inputs(c5, 0, 1, k_scale=kc["k_scale"])
+    assert blk["Kblk"].shape == (2, 2, 16, 64) and blk["block_start"] == 48
+    m3 = wl.verify_inputs(wl.custom_config(B=4, G=500, V=8, decoded_frac=0.3), 0)["mask"]
+    assert 0.6 < m3.mean() < 0.8                          # ~70 % still masked
