@@ -1,0 +1,167 @@
+/*
+ * dd.h -- C ABI of the DualDiffusion draft-then-verify hot path on MI355X (gfx950).
+ *
+ * One draft-then-verify cycle (Alg. 1) is K drafter unmasking steps followed by one
+ * verifier pass and a verification rule.  This library provides the three operations
+ * that dominate it:
+ *
+ *   dd_bidir_attention         the verifier's attention over ALL positions -- the
+ *                              O(N^2)-per-step cost Sec. 1 and Sec. 2.2 name as the
+ *                              bottleneck of masked diffusion models;
+ *   dd_block_attention_cached  the drafter's attention: only the active block's
+ *                              queries, keys/values of the other positions read from
+ *                              a block-wise approximate KV cache (Sec. 2.3, Sec. 3.1);
+ *   dd_verify_remask           the verification rule of Sec. 3.2 over the vocabulary:
+ *                              verifier confidence (Eq. 7) and argmax, KL(drafter ||
+ *                              verifier) (Eq. 5), and the Trust (Eq. 4) / KL-threshold /
+ *                              KL-probabilistic (Eq. 6) / confidence-threshold /
+ *                              confidence-probabilistic remask decision.
+ *
+ * Common rules
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or synchronises.  Work is enqueued on `stream` (a hipStream_t
+ *     passed as void*; NULL = the default stream).  Inputs are never written; outputs
+ *     are fully overwritten; identical inputs give bit-identical outputs.
+ *   - `workspace` is device memory of at least dd_*_workspace_bytes(...) bytes (same
+ *     shape arguments), 256-byte aligned, contents undefined on entry and exit.  It may
+ *     be NULL when the query function returns 0.  Calls that share a workspace must be
+ *     ordered on one stream.
+ *   - All tensors are dense, row-major, contiguous, base pointers 16-byte aligned.
+ *   - Return value: DD_OK, or a negative dd_status.  Arguments are validated on the
+ *     host before any GPU call; on error nothing is launched and no output is touched.
+ */
+#ifndef DD_H
+#define DD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DD_OK = 0,
+    DD_ERR_NULL = -1,       /* a required pointer is NULL */
+    DD_ERR_SHAPE = -2,      /* a size is out of range or inconsistent */
+    DD_ERR_DTYPE = -3,      /* unsupported element type / combination */
+    DD_ERR_MODE = -4,       /* unknown remask mode */
+    DD_ERR_WORKSPACE = -5,  /* workspace NULL / too small / misaligned */
+    DD_ERR_ALIGN = -6,      /* a pointer or row pitch is not 16-byte aligned */
+    DD_ERR_LAUNCH = -7      /* the HIP runtime refused a launch */
+} dd_status;
+
+typedef enum {
+    DD_F32 = 0,        /* IEEE binary32 */
+    DD_BF16 = 1,       /* upper 16 bits of binary32 */
+    DD_FP8_E4M3 = 2    /* OCP e4m3 (bias 7, max 448, no infinities); Q and K only */
+} dd_dtype;
+
+typedef enum {
+    DD_TRUST = 0,        /* Eq. 4: keep the drafter's sequence, remask nothing */
+    DD_KL_THRESH = 1,    /* remask i iff KL_i > threshold                      (Sec. 3.2.2) */
+    DD_CONF_THRESH = 2,  /* remask i iff c_V,i < threshold                     (Sec. 3.2.3) */
+    DD_KL_PROB = 3,      /* remask i with probability KL_i / sum_j KL_j (Eq. 6) */
+    DD_CONF_PROB = 4     /* remask i with probability 1 - c_V,i                (Sec. 3.2.3) */
+} dd_mode;
+
+/* Human-readable text for a dd_status (static storage; never NULL). */
+const char *dd_strerror(int status);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int dd_version(void);
+
+/*
+ * Verifier attention (Sec. 2.2; Alg. 1, verification phase):
+ *     O[b,h,i,:] = sum_j softmax_j( Q[b,h,i,:] . K[b,g,j,:] / sqrt(d) ) V[b,g,j,:],   j = 0..N-1
+ * i.e. the softmax(Q K^T / sqrt(d_k)) V of Eq. 3 with the key range being every position
+ * (bidirectional: no causal or padding mask).  Query head h reads kv head g = h*Hkv/H
+ * (consecutive groups; Hkv == H is plain multi-head attention).
+ *
+ *   Q  [B,H,N,d]    qk_dtype          K [B,Hkv,N,d]  qk_dtype
+ *   V  [B,Hkv,N,d]  v_dtype           O [B,H,N,d]    v_dtype   (written)
+ *   q_scale [B*H], k_scale [B*Hkv]  fp32 per-(batch,head) multipliers of the decoded
+ *       values (must be > 0); required for DD_FP8_E4M3, optional (NULL = 1) otherwise.
+ * Supported: (qk_dtype, v_dtype) in {(F32,F32), (BF16,BF16), (FP8_E4M3,BF16)};
+ *            d in {64, 128}; H % Hkv == 0; B, H, N >= 1; B*H*N*d < 2^40.
+ * Arithmetic: F32 path in fp32 throughout; BF16/FP8 paths multiply on the matrix cores
+ *            with fp32 accumulation, fp32 online softmax, probabilities rounded to bf16
+ *            before the PV product.
+ * Workspace: none needed (dd_bidir_attention_workspace_bytes returns 0).
+ */
+int dd_bidir_attention(const void *Q, const void *K, const void *V, void *O,
+                       int B, int H, int Hkv, int N, int d,
+                       dd_dtype qk_dtype, dd_dtype v_dtype,
+                       const float *q_scale, const float *k_scale,
+                       void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_bidir_attention_workspace_bytes(int B, int H, int Hkv, int N, int d,
+                                          dd_dtype qk_dtype, dd_dtype v_dtype);
+
+/*
+ * Drafter attention over a block-wise approximate KV cache (Sec. 2.3: keys/values of the
+ * other blocks are cached and reused across the denoising steps inside a block; prefix
+ * and suffix are both cached).  Same formula as above, but only for the block_len queries
+ * of the active block; key/value row j is
+ *     Kblk/Vblk[b,g,j-block_start,:]  if Kblk != NULL and block_start <= j < block_start+block_len
+ *     Kc/Vc[b,g,j,:]                  otherwise (whatever the cache holds, stale or not).
+ * With Kblk == Vblk == NULL the caller has already refreshed the block's rows in the cache.
+ *
+ *   Qblk [B,H,block_len,d] qk_dtype     Kc [B,Hkv,N,d] qk_dtype    Vc [B,Hkv,N,d] v_dtype
+ *   Kblk [B,Hkv,block_len,d] qk_dtype   Vblk [B,Hkv,block_len,d] v_dtype  (both or neither)
+ *   O    [B,H,block_len,d] v_dtype  (written)
+ *   k_scale applies to cache rows and block rows alike.
+ * Requires 0 <= block_start, 1 <= block_len, block_start + block_len <= N;
+ *          dtypes / d / heads as for dd_bidir_attention.
+ * The key range is split over several workgroups whose partial (max, sum, unnormalised
+ * output) states live in `workspace` and are merged by a second kernel.
+ */
+int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                              int block_start, int block_len,
+                              const void *Kblk, const void *Vblk,
+                              int B, int H, int Hkv, int N, int d,
+                              dd_dtype qk_dtype, dd_dtype v_dtype,
+                              const float *q_scale, const float *k_scale,
+                              void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                 dd_dtype qk_dtype, dd_dtype v_dtype);
+
+/*
+ * Verification rule of Sec. 3.2 for P = B*G positions (G verified positions per sequence),
+ * softmax at temperature 1 over the whole vocabulary, natural logarithm:
+ *     c_V,i  = max_x p_V(x | i)                     (Eq. 7)      t_V,i = lowest x attaining it
+ *     KL_i   = sum_x p_D(x|i) (log p_D(x|i) - log p_V(x|i))      (Eq. 5)
+ *     score_i = KL_i in the KL modes, c_V,i otherwise
+ *     eligible_i = (mask[i] == 0)      -- the rules are stated for decoded positions only
+ *     remask_i = eligible_i and
+ *         DD_TRUST        false
+ *         DD_KL_THRESH    score_i >  threshold       (strict; compared in fp32)
+ *         DD_CONF_THRESH  score_i <  threshold       (strict; compared in fp32)
+ *         DD_KL_PROB      u_i < max(score_i,0) / sum_{j eligible, same sequence} max(score_j,0)
+ *                         (an empty or zero sum remasks nothing)
+ *         DD_CONF_PROB    u_i < 1 - score_i
+ *     u_i = top 24 bits of word 0 of Philox-4x32-10(counter = (i_lo, i_hi, 0, 0),
+ *           key = (seed_lo, seed_hi)) times 2^-24, i = global row index b*G+g.
+ *
+ *   logits_d [P,V] logit_dtype  drafter logits; read only in the KL modes (may be NULL otherwise)
+ *   logits_v [P,V] logit_dtype  verifier logits
+ *   mask     [P] u8             1 = position still holds [MASK], 0 = decoded
+ *   out_mask   [P] u8   = mask[i] | remask_i
+ *   out_tokens [P] i32  = t_V,i            (every row, eligible or not, every mode)
+ *   out_scores [P] f32  = score_i          (every row)
+ * logit_dtype in {DD_F32, DD_BF16}; V >= 1 with V * sizeof(element) a multiple of 16;
+ * B, G >= 0 (P == 0 is a no-op returning DD_OK); V < 2^31, P < 2^31.
+ * `seed` is ignored by DD_TRUST and the threshold modes.
+ * Each logit is read from memory exactly once (single pass; rows are split across
+ * workgroups and their partial states merged in `workspace`).
+ */
+int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                     dd_mode mode, float threshold, uint64_t seed,
+                     uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                     int B, int G, int V, dd_dtype logit_dtype,
+                     void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DD_H */

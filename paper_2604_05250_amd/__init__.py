@@ -1,0 +1,194 @@
+"""MI355X-native hot path of one DualDiffusion draft-then-verify step.
+
+Thin ctypes binding over the C ABI in ``include/dd.h`` (``libdd.so``, hand-written
+gfx950 HIP kernels).  The functions here have the C entry points' names and only
+marshal arguments: torch tensors supply device memory and the current stream, every
+step of the computation runs in the library's kernels.  There is no CPU fallback:
+if the library cannot be loaded, importing the binding's functions raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+F32, BF16, FP8_E4M3 = 0, 1, 2
+TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB = 0, 1, 2, 3, 4
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdd.so")
+_lib = None
+
+
+class DDError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {lib().dd_strerror(status).decode()} (status {status})")
+
+
+def lib():
+    """The loaded C-ABI library (built on first use only when no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_library
+        build_library(force=True)
+    L = C.CDLL(LIB_PATH)
+    vp, i, sz = C.c_void_p, C.c_int, C.c_size_t
+    L.dd_strerror.restype = C.c_char_p
+    L.dd_strerror.argtypes = [i]
+    L.dd_version.restype = i
+    L.dd_bidir_attention.restype = i
+    L.dd_bidir_attention.argtypes = [vp, vp, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
+    L.dd_bidir_attention_workspace_bytes.restype = sz
+    L.dd_bidir_attention_workspace_bytes.argtypes = [i, i, i, i, i, i, i]
+    L.dd_block_attention_cached.restype = i
+    L.dd_block_attention_cached.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
+    L.dd_block_attention_cached_workspace_bytes.restype = sz
+    L.dd_block_attention_cached_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.dd_verify_remask.restype = i
+    L.dd_verify_remask.argtypes = [vp, vp, vp, i, C.c_float, C.c_uint64, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dd_verify_remask_workspace_bytes.restype = sz
+    L.dd_verify_remask_workspace_bytes.argtypes = [i, i, i, i]
+    _lib = L
+    return L
+
+
+EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attention_workspace_bytes",
+           "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
+           "dd_verify_remask", "dd_verify_remask_workspace_bytes")
+
+
+# ---------------------------------------------------------------- marshalling helpers
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_tag(t, what: str) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        return BF16
+    if t.dtype in (torch.uint8, torch.float8_e4m3fn):
+        return FP8_E4M3
+    raise TypeError(f"{what}: unsupported tensor dtype {t.dtype}")
+
+
+def _dev(t, what: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{what}: must live in GPU memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return _torch().cuda.current_stream().cuda_stream
+
+
+_ws_cache = {}
+
+
+def _workspace(nbytes: int, device):
+    """A per-device scratch tensor (device memory only; the library never allocates)."""
+    if nbytes == 0:
+        return None, 0
+    torch = _torch()
+    key = str(device)
+    cur = _ws_cache.get(key)
+    if cur is None or cur.numel() < nbytes:
+        cur = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
+        _ws_cache[key] = cur
+    return cur, cur.numel()
+
+
+# ---------------------------------------------------------------- entry points
+def dd_bidir_attention_workspace_bytes(B, H, Hkv, N, d, qk_dtype, v_dtype) -> int:
+    return lib().dd_bidir_attention_workspace_bytes(B, H, Hkv, N, d, qk_dtype, v_dtype)
+
+
+def dd_bidir_attention(Q, K, V, O=None, q_scale=None, k_scale=None, qk_dtype: Optional[int] = None,
+                       v_dtype: Optional[int] = None):
+    """Verifier attention over all positions.  Q [B,H,N,d], K,V [B,Hkv,N,d] -> O [B,H,N,d] (V's type)."""
+    torch = _torch()
+    B, H, N, d = Q.shape
+    Hkv = K.shape[1]
+    if tuple(K.shape) != (B, Hkv, N, d) or tuple(V.shape) != (B, Hkv, N, d):
+        raise ValueError("K/V shape must be [B,Hkv,N,d] matching Q")
+    qk = _dtype_tag(Q, "Q") if qk_dtype is None else qk_dtype
+    vd = _dtype_tag(V, "V") if v_dtype is None else v_dtype
+    if O is None:
+        O = torch.empty((B, H, N, d), dtype=V.dtype, device=V.device)
+    ws, wsn = _workspace(dd_bidir_attention_workspace_bytes(B, H, Hkv, N, d, qk, vd), Q.device)
+    rc = lib().dd_bidir_attention(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), B, H, Hkv, N, d, qk, vd,
+                                  _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"), _dev(ws, "workspace"), wsn,
+                                  _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_bidir_attention")
+    return O
+
+
+def dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype) -> int:
+    return lib().dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype)
+
+
+def dd_block_attention_cached(Qblk, Kc, Vc, block_start: int, O=None, Kblk=None, Vblk=None, q_scale=None,
+                              k_scale=None, qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None):
+    """Drafter attention: the active block's queries over cached K/V.
+    Qblk [B,H,bl,d], Kc,Vc [B,Hkv,N,d], optional Kblk,Vblk [B,Hkv,bl,d] -> O [B,H,bl,d]."""
+    torch = _torch()
+    B, H, bl, d = Qblk.shape
+    _, Hkv, N, _ = Kc.shape
+    if tuple(Kc.shape) != (B, Hkv, N, d) or tuple(Vc.shape) != (B, Hkv, N, d):
+        raise ValueError("Kc/Vc shape must be [B,Hkv,N,d]")
+    if Kblk is not None and (tuple(Kblk.shape) != (B, Hkv, bl, d) or tuple(Vblk.shape) != (B, Hkv, bl, d)):
+        raise ValueError("Kblk/Vblk shape must be [B,Hkv,block_len,d]")
+    qk = _dtype_tag(Qblk, "Qblk") if qk_dtype is None else qk_dtype
+    vd = _dtype_tag(Vc, "Vc") if v_dtype is None else v_dtype
+    if O is None:
+        O = torch.empty((B, H, bl, d), dtype=Vc.dtype, device=Vc.device)
+    ws, wsn = _workspace(dd_block_attention_cached_workspace_bytes(bl, B, H, Hkv, N, d, qk, vd), Qblk.device)
+    rc = lib().dd_block_attention_cached(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
+                                         int(block_start), bl, _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"),
+                                         B, H, Hkv, N, d, qk, vd, _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
+                                         _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_block_attention_cached")
+    return O
+
+
+def dd_verify_remask_workspace_bytes(B, G, V, logit_dtype) -> int:
+    return lib().dd_verify_remask_workspace_bytes(B, G, V, logit_dtype)
+
+
+def dd_verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed: int, B: int, G: int,
+                     out_mask=None, out_tokens=None, out_scores=None, logit_dtype: Optional[int] = None):
+    """Verification rule over the vocabulary.  logits [B*G, V]; mask [B*G] u8 (1 = still masked).
+    Returns (out_mask u8, out_tokens i32, out_scores f32)."""
+    torch = _torch()
+    P, V = logits_v.shape
+    if P != B * G:
+        raise ValueError("logits_v must have B*G rows")
+    if logits_d is not None and tuple(logits_d.shape) != (P, V):
+        raise ValueError("logits_d shape must match logits_v")
+    dt = _dtype_tag(logits_v, "logits_v") if logit_dtype is None else logit_dtype
+    dev = logits_v.device
+    if out_mask is None:
+        out_mask = torch.empty(P, dtype=torch.uint8, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty(P, dtype=torch.int32, device=dev)
+    if out_scores is None:
+        out_scores = torch.empty(P, dtype=torch.float32, device=dev)
+    ws, wsn = _workspace(dd_verify_remask_workspace_bytes(B, G, V, dt), dev)
+    rc = lib().dd_verify_remask(_dev(logits_d, "logits_d"), _dev(logits_v, "logits_v"), _dev(mask, "mask"),
+                                int(mode), float(threshold), int(seed) & (2 ** 64 - 1),
+                                _dev(out_mask, "out_mask"), _dev(out_tokens, "out_tokens"),
+                                _dev(out_scores, "out_scores"), B, G, V, dt, _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_verify_remask")
+    return out_mask, out_tokens, out_scores

@@ -1,0 +1,169 @@
+// C ABI of the library: argument validation (host only, before any GPU call) and dispatch
+// to the kernels.  See include/dd.h for the contract of every entry point.
+#include "../../include/dd.h"
+#include "dd_internal.h"
+
+namespace {
+
+inline bool misaligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int check_attention_common(int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                           const float *q_scale, const float *k_scale)
+{
+    if (B < 1 || H < 1 || Hkv < 1 || N < 1) return DD_ERR_SHAPE;
+    if (H % Hkv != 0) return DD_ERR_SHAPE;
+    if (d != 64 && d != 128) return DD_ERR_SHAPE;
+    if ((double)B * H * N * d >= 1099511627776.0) return DD_ERR_SHAPE;
+    const bool ok = (qk_dtype == DD_F32 && v_dtype == DD_F32) || (qk_dtype == DD_BF16 && v_dtype == DD_BF16) ||
+                    (qk_dtype == DD_FP8_E4M3 && v_dtype == DD_BF16);
+    if (!ok) return DD_ERR_DTYPE;
+    if (qk_dtype == DD_FP8_E4M3 && (!q_scale || !k_scale)) return DD_ERR_NULL;
+    return DD_OK;
+}
+
+int check_workspace(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return DD_OK;
+    if (!ws || have < need) return DD_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return DD_ERR_WORKSPACE;
+    return DD_OK;
+}
+
+}  // namespace
+
+namespace dd {
+
+int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
+{
+    (void)d;
+    const int group = H / Hkv;
+    const long base = (long)B * Hkv * ((group * block_len + 127) / 128);
+    long s = (1024 + base - 1) / base;
+    const long max_s = N / 128 > 1 ? N / 128 : 1;   // at least 128 keys per split
+    if (s > max_s) s = max_s;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+size_t attn_partial_bytes(int B, int H, int Nq, int d, int splits)
+{
+    if (splits <= 1) return 0;
+    return (size_t)B * H * Nq * (size_t)splits * (size_t)(d + 2) * sizeof(float);
+}
+
+}  // namespace dd
+
+extern "C" {
+
+const char *dd_strerror(int status)
+{
+    switch (status) {
+    case DD_OK: return "ok";
+    case DD_ERR_NULL: return "a required pointer is NULL";
+    case DD_ERR_SHAPE: return "a size is out of range or inconsistent";
+    case DD_ERR_DTYPE: return "unsupported element type or combination";
+    case DD_ERR_MODE: return "unknown remask mode";
+    case DD_ERR_WORKSPACE: return "workspace is NULL, too small or not 256-byte aligned";
+    case DD_ERR_ALIGN: return "a pointer or row pitch is not 16-byte aligned";
+    case DD_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    default: return "unknown status";
+    }
+}
+
+int dd_version(void) { return 100; }
+
+size_t dd_bidir_attention_workspace_bytes(int, int, int, int, int, dd_dtype, dd_dtype) { return 0; }
+
+int dd_bidir_attention(const void *Q, const void *K, const void *V, void *O,
+                       int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                       const float *q_scale, const float *k_scale,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    if (!Q || !K || !V || !O) return DD_ERR_NULL;
+    const int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale);
+    if (rc != DD_OK) return rc;
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O)) return DD_ERR_ALIGN;
+    dd::AttnArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.Kblk = nullptr; a.Vblk = nullptr; a.O = O;
+    a.q_scale = q_scale; a.k_scale = k_scale;
+    a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = N; a.N = N; a.d = d;
+    a.block_start = 0; a.block_len = 0;
+    a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
+    a.splits = 1; a.workspace = nullptr;
+    const hipError_t e = (qk_dtype == DD_F32) ? dd::launch_attention_f32(a, static_cast<hipStream_t>(stream))
+                                              : dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                 dd_dtype qk_dtype, dd_dtype v_dtype)
+{
+    if (check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, (const float *)16, (const float *)16) != DD_OK) return 0;
+    if (block_len < 1 || block_len > N) return 0;
+    return dd::attn_partial_bytes(B, H, block_len, d, dd::attn_block_splits(block_len, B, H, Hkv, N, d));
+}
+
+int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                              int block_start, int block_len, const void *Kblk, const void *Vblk,
+                              int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                              const float *q_scale, const float *k_scale,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!Qblk || !Kc || !Vc || !O) return DD_ERR_NULL;
+    if ((Kblk == nullptr) != (Vblk == nullptr)) return DD_ERR_NULL;
+    int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale);
+    if (rc != DD_OK) return rc;
+    if (block_start < 0 || block_len < 1 || (long)block_start + block_len > N) return DD_ERR_SHAPE;
+    if (misaligned16(Qblk) || misaligned16(Kc) || misaligned16(Vc) || misaligned16(O) ||
+        misaligned16(Kblk) || misaligned16(Vblk))
+        return DD_ERR_ALIGN;
+    const int splits = dd::attn_block_splits(block_len, B, H, Hkv, N, d);
+    rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));
+    if (rc != DD_OK) return rc;
+    dd::AttnArgs a{};
+    a.Q = Qblk; a.K = Kc; a.V = Vc; a.Kblk = Kblk; a.Vblk = Vblk; a.O = O;
+    a.q_scale = q_scale; a.k_scale = k_scale;
+    a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = block_len; a.N = N; a.d = d;
+    a.block_start = block_start; a.block_len = block_len;
+    a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
+    a.splits = splits; a.workspace = workspace;
+    const hipError_t e = (qk_dtype == DD_F32) ? dd::launch_attention_f32(a, static_cast<hipStream_t>(stream))
+                                              : dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)
+{
+    if (B < 0 || G < 0 || V < 1 || (logit_dtype != DD_F32 && logit_dtype != DD_BF16)) return 0;
+    if ((double)B * G >= 2147483648.0) return 0;
+    return dd::verify_workspace_bytes(B * G, V, logit_dtype == DD_BF16 ? 2 : 4);
+}
+
+int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                     dd_mode mode, float threshold, uint64_t seed,
+                     uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                     int B, int G, int V, dd_dtype logit_dtype,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (mode < DD_TRUST || mode > DD_CONF_PROB) return DD_ERR_MODE;
+    if (logit_dtype != DD_F32 && logit_dtype != DD_BF16) return DD_ERR_DTYPE;
+    if (B < 0 || G < 0 || V < 1) return DD_ERR_SHAPE;
+    if ((double)B * G >= 2147483648.0) return DD_ERR_SHAPE;
+    const int eb = logit_dtype == DD_BF16 ? 2 : 4;
+    if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
+    if (B == 0 || G == 0) return DD_OK;
+    const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB);
+    if (!logits_v || !mask || !out_mask || !out_tokens || !out_scores) return DD_ERR_NULL;
+    if (kl && !logits_d) return DD_ERR_NULL;
+    if (misaligned16(logits_v) || (kl && misaligned16(logits_d))) return DD_ERR_ALIGN;
+    const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(B * G, V, eb));
+    if (rc != DD_OK) return rc;
+    const hipError_t e = dd::launch_verify(kl ? logits_d : nullptr, logits_v, mask, (int)mode, threshold, seed,
+                                           out_mask, out_tokens, out_scores, B, G, V, logit_dtype == DD_BF16,
+                                           workspace, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Internal launch interfaces between the C-ABI layer (dd_api.hip) and the kernels.
+// Everything here takes validated arguments; shapes were checked by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dd {
+
+// ---- verification (verify.hip) -------------------------------------------------
+// Number of workgroups one logit row is split over, and workspace size.
+int verify_splits(int P, int V, int elem_bytes);
+size_t verify_workspace_bytes(int P, int V, int elem_bytes);
+hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                         int mode, float threshold, uint64_t seed,
+                         uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream);
+
+// ---- attention (attention_mfma.hip, attention_f32.hip) -------------------------
+// One description serves the verifier's full attention and the drafter's block attention:
+// for every (batch, kv head) the `group * Nq` query rows of the heads sharing that kv head
+// attend keys [0, N); key row j is taken from (Kblk, Vblk) when Kblk != nullptr and
+// block_start <= j < block_start + block_len, else from (K, V).
+struct AttnArgs {
+    const void *Q;       // [B, H, Nq, d]
+    const void *K;       // [B, Hkv, N, d]
+    const void *V;       // [B, Hkv, N, d]
+    const void *Kblk;    // [B, Hkv, block_len, d] or nullptr
+    const void *Vblk;
+    void *O;             // [B, H, Nq, d]
+    const float *q_scale;  // [B*H] or nullptr
+    const float *k_scale;  // [B*Hkv] or nullptr
+    int B, H, Hkv, Nq, N, d;
+    int block_start, block_len;
+    int qk_dtype, v_dtype;   // dd_dtype values
+    int splits;              // key-range splits (1 = write O directly)
+    void *workspace;         // partial states when splits > 1
+};
+
+int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d);
+size_t attn_partial_bytes(int B, int H, int Nq, int d, int splits);
+hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream);   // bf16 / fp8 inputs
+hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t stream);    // fp32 inputs
+hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream);
+
+}  // namespace dd

@@ -1,0 +1,427 @@
+// Verification pass over the vocabulary (Sec. 3.2): one streaming read of the verifier
+// logits (and, in the KL modes, the drafter logits) produces per position the verifier
+// confidence c_V = max_x p_V(x) (Eq. 7), its argmax, and KL(p_D || p_V) (Eq. 5); a small
+// finishing kernel applies the remask rule (Eq. 4, the KL / confidence thresholds, Eq. 6,
+// and the 1 - c_V rule).
+//
+// HBM-bound design: every logit is loaded exactly once with 16-byte coalesced loads.
+// A row is split over `S` workgroups.  Each wave keeps wave-uniform references (the
+// running verifier and drafter maxima) so the per-element work
+// is one fma + one exp2 + one add per logit, and the argmax / rescale logic runs only
+// when some lane of the wave sees a new maximum (a few times per row).  Partial states
+//     (ref_D, sum e^{l_D-ref_D}, sum e^{l_D-ref_D}(l_D-l_V), max l_V, sum e^{l_V-max}, argmax)
+// are merged in a fixed order (lanes -> waves -> splits), so results are run-to-run
+// identical; the last merge and the log / divide are done in fp64.
+#include "dd_internal.h"
+
+#include <limits.h>
+#include <math.h>
+
+namespace dd {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+constexpr int kUnroll = 4;
+constexpr float kLog2e = 1.44269504088896340736f;
+constexpr float kNegInf = -INFINITY;
+// The drafter reference is raised when a logit exceeds it by more than this.  Zero keeps it
+// equal to the running maximum, exactly as on the verifier side, so identical drafter and
+// verifier rows go through identical arithmetic and give KL = 0 exactly.
+constexpr float kLazyMargin = 0.0f;
+
+struct __align__(32) VerifyPartial {
+    float ref_d, s_d, a;   // drafter reference, sum e^{l_D-ref}, sum e^{l_D-ref} (l_D - l_V)
+    float best_v, s_v;     // verifier maximum, sum e^{l_V-best}
+    int idx;               // lowest index attaining best_v
+    int pad0, pad1;
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// streaming 16-byte load: every logit is read once, so it need not displace cached lines
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 stream_load16(const uint4 *p)
+{
+    const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return make_uint4(w.x, w.y, w.z, w.w);
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_min(int v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// e^{ref - m} with the convention that an empty state (ref = -inf) weighs nothing
+__device__ __forceinline__ float rescale_factor(float ref, float m)
+{
+    return ref == kNegInf ? 0.0f : fast_exp2((ref - m) * kLog2e);
+}
+
+template <bool BF16> struct VecTraits;
+template <> struct VecTraits<true> {
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float (&x)[8])
+    {
+        const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(w[i] << 16);
+            x[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+template <> struct VecTraits<false> {
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ void unpack(const uint4 &r, float (&x)[4])
+    {
+        x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+        x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
+    }
+};
+
+struct LaneState {
+    float ref_d = kNegInf, s_d = 0.f, a = 0.f;   // ref_d is wave-uniform
+    float best_v = kNegInf, s_v = 0.f;           // best_v, idx_v are wave-uniform
+    int idx_v = INT_MAX;
+};
+
+// Fold one 16-byte vector of verifier logits (and the matching drafter vector) into the state.
+// Must be called by all lanes of a wave together; `valid` masks lanes past the row chunk's end.
+template <bool BF16, bool KL>
+__device__ __forceinline__ void consume(const uint4 &rv, const uint4 &rd, bool valid, int elem_base, LaneState &st)
+{
+    constexpr int E = VecTraits<BF16>::kElems;
+    float xv[E], xd[E];
+    VecTraits<BF16>::unpack(rv, xv);
+    float bmax = xv[0];
+#pragma unroll
+    for (int e = 1; e < E; ++e) bmax = fmaxf(bmax, xv[e]);
+    if (!valid) bmax = kNegInf;
+
+    if (__any(bmax > st.best_v)) {
+        // rare: a new verifier maximum appears in this wave
+        const float wmax = wave_max(bmax);
+        int cand = INT_MAX;
+        if (valid && bmax == wmax) {
+#pragma unroll
+            for (int e = E - 1; e >= 0; --e)
+                if (xv[e] == wmax) cand = elem_base + e;
+        }
+        const int widx = wave_min(cand);
+        st.s_v *= rescale_factor(st.best_v, wmax);
+        st.best_v = wmax;
+        st.idx_v = widx;
+    }
+    if (KL) {
+        VecTraits<BF16>::unpack(rd, xd);
+        float dmax = xd[0];
+#pragma unroll
+        for (int e = 1; e < E; ++e) dmax = fmaxf(dmax, xd[e]);
+        if (!valid) dmax = kNegInf;
+        if (__any(dmax > st.ref_d + kLazyMargin)) {
+            const float wmax = wave_max(dmax);
+            const float c = rescale_factor(st.ref_d, wmax);
+            st.s_d *= c;
+            st.a *= c;
+            st.ref_d = wmax;
+        }
+    }
+    if (valid) {
+        const float mv = st.best_v * kLog2e;
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc += fast_exp2(fmaf(xv[e], kLog2e, -mv));
+        st.s_v += acc;
+        if (KL) {
+            const float md = st.ref_d * kLog2e;
+            float accs = 0.f, acca = 0.f;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const float ed = fast_exp2(fmaf(xd[e], kLog2e, -md));
+                accs += ed;
+                acca = fmaf(ed, xd[e] - xv[e], acca);
+            }
+            st.s_d += accs;
+            st.a += acca;
+        }
+    }
+}
+
+struct WaveState {
+    float ref_d, s_d, a, best_v, s_v;
+    int idx;
+};
+
+// associative merge of two partial states (b comes after a in index order)
+__device__ __forceinline__ WaveState merge(const WaveState &x, const WaveState &y)
+{
+    WaveState r;
+    const float mv = fmaxf(x.best_v, y.best_v);
+    r.s_v = x.s_v * rescale_factor(x.best_v, mv) + y.s_v * rescale_factor(y.best_v, mv);
+    const bool take_y = (y.best_v > x.best_v) || (y.best_v == x.best_v && y.idx < x.idx);
+    r.best_v = mv;
+    r.idx = take_y ? y.idx : x.idx;
+    const float md = fmaxf(x.ref_d, y.ref_d);
+    const float cx = rescale_factor(x.ref_d, md), cy = rescale_factor(y.ref_d, md);
+    r.ref_d = md;
+    r.s_d = x.s_d * cx + y.s_d * cy;
+    r.a = x.a * cx + y.a * cy;
+    return r;
+}
+
+// grid: P * S workgroups; workgroup (row, split) reduces vectors [split*chunk, (split+1)*chunk) of its row
+template <bool BF16, bool KL>
+__global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *__restrict__ logits_d,
+                                                                  const uint4 *__restrict__ logits_v,
+                                                                  int nvec, int S, int chunk,
+                                                                  VerifyPartial *__restrict__ part)
+{
+    constexpr int E = VecTraits<BF16>::kElems;
+    const int row = blockIdx.x / S;
+    const int split = blockIdx.x - row * S;
+    const int tid = threadIdx.x;
+    const size_t rbase = (size_t)row * (size_t)nvec;
+    const uint4 *pv = logits_v + rbase;
+    const uint4 *pd = KL ? logits_d + rbase : nullptr;
+    const int vbeg = split * chunk;
+    const int vend = min(nvec, vbeg + chunk);
+
+    LaneState st;
+    int base = vbeg;
+    // full iterations: kUnroll independent 16-byte loads per matrix in flight per lane
+    for (; base + kThreads * kUnroll <= vend; base += kThreads * kUnroll) {
+        uint4 rv[kUnroll], rd[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int idx = base + u * kThreads + tid;
+            rv[u] = stream_load16(pv + idx);
+            if (KL) rd[u] = stream_load16(pd + idx);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            consume<BF16, KL>(rv[u], rd[u], true, (base + u * kThreads + tid) * E, st);
+    }
+    // ragged remainder of the chunk
+    if (base < vend) {
+        uint4 rv[kUnroll], rd[kUnroll];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const int idx = base + u * kThreads + tid;
+            ok[u] = idx < vend;
+            rv[u] = make_uint4(0, 0, 0, 0);
+            rd[u] = make_uint4(0, 0, 0, 0);
+            if (ok[u]) {
+                rv[u] = stream_load16(pv + idx);
+                if (KL) rd[u] = stream_load16(pd + idx);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            consume<BF16, KL>(rv[u], rd[u], ok[u], (base + u * kThreads + tid) * E, st);
+    }
+
+    // lanes -> wave (references are already wave-uniform), waves -> workgroup
+    __shared__ WaveState ws[kWaves];
+    WaveState w;
+    w.ref_d = st.ref_d;
+    w.s_d = wave_sum(st.s_d);
+    w.a = wave_sum(st.a);
+    w.best_v = st.best_v;
+    w.s_v = wave_sum(st.s_v);
+    w.idx = st.idx_v;
+    if ((tid & 63) == 0) ws[tid >> 6] = w;
+    __syncthreads();
+    if (tid == 0) {
+        WaveState r = ws[0];
+#pragma unroll
+        for (int i = 1; i < kWaves; ++i) r = merge(r, ws[i]);
+        VerifyPartial p;
+        p.ref_d = r.ref_d; p.s_d = r.s_d; p.a = r.a;
+        p.best_v = r.best_v; p.s_v = r.s_v; p.idx = r.idx;
+        p.pad0 = 0; p.pad1 = 0;
+        part[(size_t)row * S + split] = p;
+    }
+}
+
+// Philox-4x32 with ten rounds (Salmon et al., SC'11): counter-based, so the uniform of a
+// row depends only on (seed, row index) and not on the launch geometry.
+__device__ __forceinline__ unsigned philox_word0(uint64_t seed, uint64_t row)
+{
+    unsigned c0 = (unsigned)row, c1 = (unsigned)(row >> 32), c2 = 0u, c3 = 0u;
+    unsigned k0 = (unsigned)seed, k1 = (unsigned)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const unsigned hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const unsigned hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const unsigned n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+__device__ __forceinline__ double row_uniform(uint64_t seed, uint64_t row)
+{
+    return (double)(philox_word0(seed, row) >> 8) * (1.0 / 16777216.0);
+}
+
+// one thread per row: merge the S partials in fp64, finish the scores, apply the rule
+__global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartial *__restrict__ part, int S, int P,
+                                                              const uint8_t *__restrict__ mask, int mode,
+                                                              float threshold, uint64_t seed, int kl_mode,
+                                                              uint8_t *__restrict__ out_mask,
+                                                              int32_t *__restrict__ out_tokens,
+                                                              float *__restrict__ out_scores)
+{
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= P) return;
+    const VerifyPartial *p = part + (size_t)row * S;
+    float mv = kNegInf, md = kNegInf;
+    int idx = INT_MAX;
+    for (int s = 0; s < S; ++s) {
+        const float b = p[s].best_v;
+        if (b > mv || (b == mv && p[s].idx < idx)) {
+            mv = b;
+            idx = p[s].idx;
+        }
+        md = fmaxf(md, p[s].ref_d);
+    }
+    double sv = 0.0, sd = 0.0, a = 0.0;
+    for (int s = 0; s < S; ++s) {
+        if (p[s].best_v != kNegInf) sv += (double)p[s].s_v * exp((double)p[s].best_v - (double)mv);
+        if (kl_mode && p[s].ref_d != kNegInf) {
+            const double c = exp((double)p[s].ref_d - (double)md);
+            sd += (double)p[s].s_d * c;
+            a += (double)p[s].a * c;
+        }
+    }
+    double score;
+    if (kl_mode)
+        score = a / sd - ((double)md + log(sd)) + ((double)mv + log(sv));   // E_D[l_D - l_V] - lse_D + lse_V
+    else
+        score = 1.0 / sv;                                                   // e^{max - lse_V}
+    const float s32 = (float)score;
+    out_scores[row] = s32;
+    out_tokens[row] = idx;
+    const uint8_t m = mask[row];
+    bool remask = false;
+    switch (mode) {
+    case 1: remask = s32 > threshold; break;                                // KL threshold
+    case 2: remask = s32 < threshold; break;                                // confidence threshold
+    case 4: remask = row_uniform(seed, (uint64_t)row) < 1.0 - (double)s32; break;
+    default: break;                                                         // trust; KL-prob decided later
+    }
+    out_mask[row] = (uint8_t)((m != 0) || remask);
+}
+
+// Eq. 6: one workgroup per sequence sums the divergences of its eligible rows, then draws
+__global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restrict__ scores,
+                                                            const uint8_t *__restrict__ mask, int G, uint64_t seed,
+                                                            uint8_t *__restrict__ out_mask)
+{
+    __shared__ double red[256];
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const size_t base = (size_t)b * G;
+    double local = 0.0;
+    for (int g = tid; g < G; g += 256) {
+        const float s = scores[base + g];
+        if (mask[base + g] == 0 && s > 0.0f) local += (double)s;
+    }
+    red[tid] = local;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    const double total = red[0];
+    for (int g = tid; g < G; g += 256) {
+        const size_t i = base + g;
+        const float s = scores[i];
+        const double k = s > 0.0f ? (double)s : 0.0;
+        const double p = total > 0.0 ? k / total : 0.0;
+        const bool remask = mask[i] == 0 && row_uniform(seed, (uint64_t)i) < p;
+        out_mask[i] = (uint8_t)(mask[i] != 0 || remask);
+    }
+}
+
+int env_int(const char *name, int dflt)
+{
+    const char *v = getenv(name);
+    return v && *v ? atoi(v) : dflt;
+}
+
+}  // namespace
+
+int verify_splits(int P, int V, int elem_bytes)
+{
+    if (P <= 0) return 1;
+    const long nvec = (long)V * elem_bytes / 16;
+    static const int forced = env_int("DD_TUNE_VERIFY_SPLITS", 0);
+    static const int target = env_int("DD_TUNE_VERIFY_TARGET_WGS", 2048);
+    long s = forced > 0 ? forced : (target + P - 1) / P;
+    const long max_s = nvec / (2L * kThreads * kUnroll);   // at least two full iterations per workgroup
+    if (s > max_s) s = max_s;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+size_t verify_workspace_bytes(int P, int V, int elem_bytes)
+{
+    if (P <= 0) return 0;
+    return (size_t)P * (size_t)verify_splits(P, V, elem_bytes) * sizeof(VerifyPartial);
+}
+
+hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                         int mode, float threshold, uint64_t seed,
+                         uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream)
+{
+    const int P = B * G;
+    if (P == 0) return hipSuccess;
+    const int eb = logit_is_bf16 ? 2 : 4;
+    const int nvec = (int)((long)V * eb / 16);
+    const int S = verify_splits(P, V, eb);
+    const int chunk = (nvec + S - 1) / S;
+    const bool kl = (mode == 1 || mode == 3);
+    VerifyPartial *part = static_cast<VerifyPartial *>(workspace);
+    const uint4 *ld = static_cast<const uint4 *>(logits_d);
+    const uint4 *lv = static_cast<const uint4 *>(logits_v);
+    const dim3 grid((unsigned)((long)P * S)), block(kThreads);
+    if (logit_is_bf16) {
+        if (kl) hipLaunchKernelGGL((verify_partial_kernel<true, true>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+        else    hipLaunchKernelGGL((verify_partial_kernel<true, false>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+    } else {
+        if (kl) hipLaunchKernelGGL((verify_partial_kernel<false, true>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+        else    hipLaunchKernelGGL((verify_partial_kernel<false, false>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), 0, stream,
+                       part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (mode == 3) {
+        hipLaunchKernelGGL(verify_klprob_kernel, dim3(B), dim3(256), 0, stream, out_scores, mask, G, seed, out_mask);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+}  // namespace dd

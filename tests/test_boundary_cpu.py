@@ -1,0 +1,87 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, and rejects bad arguments on the host before any GPU call (no compute here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2604_05250_amd as dd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert set(names) == set(dd.EXPORTS)
+    L = dd.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert L.dd_version() >= 100
+    assert L.dd_strerror(0) == b"ok"
+    for code in range(-7, 0):
+        assert L.dd_strerror(code) not in (b"ok", b"unknown status")
+    assert L.dd_strerror(-99) == b"unknown status"
+
+
+FAKE = 0x1000   # a non-NULL, 16-byte aligned address that is never dereferenced: every call below fails validation first
+
+
+def test_attention_argument_validation():
+    L = dd.lib()
+    ok_args = dict(B=1, H=4, Hkv=2, N=64, d=128, qk=dd.BF16, v=dd.BF16)
+
+    def call(Q=FAKE, K=FAKE, V=FAKE, O=FAKE, qs=None, ks=None, **kw):
+        a = dict(ok_args); a.update(kw)
+        return L.dd_bidir_attention(Q, K, V, O, a["B"], a["H"], a["Hkv"], a["N"], a["d"], a["qk"], a["v"], qs, ks,
+                                    None, 0, None)
+    assert call(Q=None) == -1 and call(O=None) == -1
+    assert call(B=0) == -2 and call(N=0) == -2 and call(H=3) == -2 and call(d=96) == -2
+    assert call(qk=dd.BF16, v=dd.F32) == -3 and call(qk=dd.FP8_E4M3, v=dd.FP8_E4M3) == -3 and call(qk=7) == -3
+    assert call(qk=dd.FP8_E4M3, v=dd.BF16) == -1          # fp8 needs both scales
+    assert call(Q=FAKE + 4) == -6
+
+    def blk(bs=0, bl=16, Kblk=None, Vblk=None, ws=None, wsn=0, **kw):
+        a = dict(ok_args); a.update(kw)
+        return L.dd_block_attention_cached(FAKE, FAKE, FAKE, FAKE, bs, bl, Kblk, Vblk, a["B"], a["H"], a["Hkv"],
+                                           a["N"], a["d"], a["qk"], a["v"], None, None, ws, wsn, None)
+    assert blk(bs=-1) == -2 and blk(bs=60, bl=16) == -2 and blk(bl=0) == -2
+    assert blk(Kblk=FAKE) == -1                            # Kblk and Vblk come together
+    # workspace: needed once the key range is split
+    need = L.dd_block_attention_cached_workspace_bytes(64, 1, 32, 32, 4096, 128, dd.BF16, dd.BF16)
+    assert need > 0
+    big = dict(B=1, H=32, Hkv=32, N=4096)
+    assert blk(bs=0, bl=64, **big) == -5
+    assert blk(bs=0, bl=64, ws=FAKE, wsn=need - 1, **big) == -5
+    assert blk(bs=0, bl=64, ws=FAKE + 16, wsn=need, **big) == -5      # 256-byte alignment
+
+
+def test_verify_argument_validation():
+    L = dd.lib()
+
+    def call(ld=FAKE, lv=FAKE, mask=FAKE, mode=dd.KL_THRESH, om=FAKE, ot=FAKE, osc=FAKE, B=2, G=8, V=1024,
+             dt=dd.BF16, ws=None, wsn=0):
+        return L.dd_verify_remask(ld, lv, mask, mode, C.c_float(0.3), 0, om, ot, osc, B, G, V, dt, ws, wsn, None)
+    assert call(mode=5) == -4 and call(mode=-1) == -4
+    assert call(dt=dd.FP8_E4M3) == -3
+    assert call(B=-1) == -2 and call(V=0) == -2
+    assert call(V=1001) == -6                              # row pitch not a multiple of 16 bytes
+    assert call(lv=None) == -1 and call(ld=None) == -1 and call(om=None) == -1
+    assert call(ld=None, mode=dd.TRUST) == -5              # drafter logits optional outside the KL modes; workspace is not
+    assert call(B=0) == 0 and call(G=0) == 0               # empty input is a no-op
+    need = L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)
+    assert need >= 16 * 32
+    assert call(ws=FAKE, wsn=need - 1) == -5
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    q = torch.zeros(1, 1, 4, 64)
+    with pytest.raises(ValueError):
+        dd.dd_bidir_attention(q, q, q, O=q)

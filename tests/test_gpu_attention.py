@@ -1,0 +1,200 @@
+"""GPU parity of dd_bidir_attention and dd_block_attention_cached against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2604_05250_amd as dd
+from paper_2604_05250_amd import workloads as wl
+from _util import assert_attention_close, attn_errors, out_to_f64, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_bidir(inp, cfg):
+    import torch
+    O = dd.dd_bidir_attention(to_dev(inp["Q"]), to_dev(inp["K"]), to_dev(inp["V"]),
+                              q_scale=to_dev(inp["q_scale"]), k_scale=to_dev(inp["k_scale"]),
+                              qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+    torch.cuda.synchronize()
+    return out_to_f64(O, cfg.v_dtype)
+
+
+def gpu_block(cfg, Qblk, Kc, Vc, bs, Kblk=None, Vblk=None, q_scale=None, k_scale=None):
+    import torch
+    O = dd.dd_block_attention_cached(to_dev(Qblk), to_dev(Kc), to_dev(Vc), bs, Kblk=to_dev(Kblk), Vblk=to_dev(Vblk),
+                                     q_scale=to_dev(q_scale), k_scale=to_dev(k_scale),
+                                     qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+    torch.cuda.synchronize()
+    return out_to_f64(O, cfg.v_dtype)
+
+
+def sample_rows(rng, B, H, Nq, n):
+    """(b, h, i) rows: corners, tile boundaries and random positions."""
+    fixed = [(0, 0, 0), (B - 1, H - 1, Nq - 1), (0, H - 1, min(127, Nq - 1)), (B - 1, 0, min(128, Nq - 1)),
+             (0, 0, Nq // 2), (B // 2, H // 2, min(31, Nq - 1)), (B // 2, H // 2, min(32, Nq - 1))]
+    rnd = list(zip(rng.integers(0, B, n).tolist(), rng.integers(0, H, n).tolist(), rng.integers(0, Nq, n).tolist()))
+    return sorted(set(fixed + rnd))
+
+
+# ------------------------------------------------------------------ full attention
+def test_cfg1_fp32_full():
+    cfg = wl.CONFIGS[1]
+    inp = wl.attention_inputs(cfg, 0)
+    got = gpu_bidir(inp, cfg)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], cfg.qk_dtype, cfg.v_dtype)
+    assert_attention_close(got, ref, cfg.qk_dtype, "cfg1 bidir")
+
+
+SMALL = [
+    # (B, H, Hkv, N, d, qk_dtype): ragged N, one wave / partial tiles, GQA, both head dims
+    (1, 2, 2, 1, 64, wl.BF16), (1, 2, 2, 33, 128, wl.BF16), (2, 4, 2, 200, 128, wl.BF16), (1, 3, 1, 77, 64, wl.BF16),
+    (1, 2, 2, 320, 64, wl.BF16), (2, 8, 2, 130, 128, wl.FP8_E4M3), (1, 4, 4, 96, 64, wl.FP8_E4M3),
+    (1, 2, 1, 257, 128, wl.F32), (2, 4, 4, 50, 64, wl.F32), (1, 1, 1, 640, 128, wl.BF16),
+]
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,qk", SMALL)
+def test_bidir_small_shapes(B, H, Hkv, N, d, qk):
+    vd = wl.F32 if qk == wl.F32 else wl.BF16
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=vd, prompt=0, G=N, bl=min(16, N))
+    inp = wl.attention_inputs(cfg, seed=N)
+    got = gpu_bidir(inp, cfg)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], qk, vd, inp["q_scale"], inp["k_scale"])
+    assert_attention_close(got, ref, qk, f"bidir {B}x{H}/{Hkv}x{N}x{d} dtype {qk}")
+
+
+def test_bidir_closed_forms_on_gpu():
+    # identical keys -> mean(V); a dominant key -> that V row; both readings of the cfg2 input scale
+    cfg = wl.custom_config(B=1, H=2, Hkv=2, N=192, d=128, prompt=0, G=192)
+    inp = wl.attention_inputs(cfg, 1)
+    K1 = np.broadcast_to(inp["K"][:, :, :1], inp["K"].shape).copy()
+    got = gpu_bidir(dict(inp, K=K1), cfg)
+    meanV = wl.bf16_bits_to_f32(inp["V"]).astype(np.float64).mean(axis=2, keepdims=True)
+    assert np.abs(got - meanV).max() < 2e-3
+    small = wl.custom_config(B=1, H=2, Hkv=2, N=192, d=128, prompt=0, G=192, qk_prescale=1.0 / np.sqrt(128.0))
+    inp2 = wl.attention_inputs(small, 1)
+    got2 = gpu_bidir(inp2, small)
+    ref2 = oracle.bidir_attention(inp2["Q"], inp2["K"], inp2["V"], wl.BF16, wl.BF16)
+    assert_attention_close(got2, ref2, wl.BF16, "prescaled inputs")
+    assert np.abs(got2 - wl.bf16_bits_to_f32(inp2["V"]).astype(np.float64).mean(axis=2, keepdims=True)).max() < 0.05
+
+
+def test_bidir_is_deterministic():
+    cfg = wl.custom_config(B=2, H=4, Hkv=4, N=300, d=128, prompt=0, G=300)
+    inp = wl.attention_inputs(cfg, 4)
+    assert np.array_equal(gpu_bidir(inp, cfg), gpu_bidir(inp, cfg))
+
+
+def _bidir_full_size(cfg_id, n_rows, full=False):
+    cfg = wl.CONFIGS[cfg_id]
+    inp = wl.attention_inputs(cfg, 0)
+    got = gpu_bidir(inp, cfg)
+    assert np.isfinite(got).all()
+    if full:
+        ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], cfg.qk_dtype, cfg.v_dtype, inp["q_scale"], inp["k_scale"])
+        assert_attention_close(got, ref, cfg.qk_dtype, f"cfg{cfg_id} bidir (all rows)")
+        return
+    rows = sample_rows(np.random.default_rng(cfg_id), cfg.B, cfg.H, cfg.N, n_rows)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], cfg.qk_dtype, cfg.v_dtype, inp["q_scale"], inp["k_scale"],
+                                 rows=rows)
+    sel = np.stack([got[b, h, i] for b, h, i in rows])
+    assert_attention_close(sel, ref, cfg.qk_dtype, f"cfg{cfg_id} bidir ({len(rows)} sampled rows)")
+
+
+def test_cfg2_bidir_full_size():
+    _bidir_full_size(2, 0, full=True)
+
+
+def test_cfg3_bidir_full_size():
+    _bidir_full_size(3, 384)
+
+
+def test_cfg4_bidir_full_size():
+    _bidir_full_size(4, 256)
+
+
+def test_cfg5_bidir_full_size():
+    _bidir_full_size(5, 256)
+
+
+# ------------------------------------------------------------------ block attention over the cache
+def _block_case(cfg, seed, step, full_rows=True, n_rows=256):
+    cache = wl.cache_inputs(cfg, seed)
+    blk = wl.block_inputs(cfg, seed, step, k_scale=cache["k_scale"])
+    bs = blk["block_start"]
+    got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, blk["Kblk"], blk["Vblk"], blk["q_scale"], cache["k_scale"])
+    if full_rows:
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, cfg.qk_dtype, cfg.v_dtype,
+                                            blk["Kblk"], blk["Vblk"], blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, cfg.qk_dtype, f"{cfg.name} block step {step}")
+    else:
+        rows = sample_rows(np.random.default_rng(seed + step), cfg.B, cfg.H, cfg.bl, n_rows)
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, cfg.qk_dtype, cfg.v_dtype,
+                                            blk["Kblk"], blk["Vblk"], blk["q_scale"], cache["k_scale"], rows=rows)
+        sel = np.stack([got[b, h, i] for b, h, i in rows])
+        assert_attention_close(sel, ref, cfg.qk_dtype, f"{cfg.name} block step {step} (sampled)")
+
+
+def test_cfg1_block_all_steps():
+    cfg = wl.CONFIGS[1]
+    for step in range(cfg.K):
+        _block_case(cfg, 0, step)
+
+
+def test_cfg2_block_all_steps():
+    cfg = wl.CONFIGS[2]
+    for step in range(cfg.K):
+        _block_case(cfg, 0, step)
+
+
+@pytest.mark.parametrize("cfg_id", [3, 4, 5])
+def test_large_block_first_and_last_step(cfg_id):
+    cfg = wl.CONFIGS[cfg_id]
+    for step in (0, cfg.K - 1):
+        _block_case(cfg, 0, step, full_rows=False, n_rows=192)
+
+
+BLOCK_SMALL = [
+    # (B, H, Hkv, N, d, bl, block_start, qk): first / last / unaligned blocks, ragged N, GQA, one query
+    (1, 2, 2, 100, 64, 16, 0, wl.BF16), (1, 2, 2, 100, 64, 16, 84, wl.BF16), (2, 4, 2, 333, 128, 32, 101, wl.BF16),
+    (1, 8, 2, 1000, 128, 64, 936, wl.FP8_E4M3), (1, 2, 1, 150, 64, 1, 77, wl.BF16), (1, 4, 4, 128, 64, 16, 64, wl.F32),
+    (2, 2, 1, 600, 128, 48, 200, wl.F32), (1, 16, 2, 2048, 128, 64, 1024, wl.BF16), (1, 1, 1, 64, 128, 64, 0, wl.BF16),
+]
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", BLOCK_SMALL)
+def test_block_small_shapes(B, H, Hkv, N, d, bl, bs, qk):
+    vd = wl.F32 if qk == wl.F32 else wl.BF16
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=vd, bl=bl, prompt=0, G=N)
+    cache = wl.cache_inputs(cfg, seed=bs)
+    blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+    for fresh in (True, False):
+        Kb, Vb = (blk["Kblk"], blk["Vblk"]) if fresh else (None, None)
+        got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, Kb, Vb, blk["q_scale"], cache["k_scale"])
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, qk, vd, Kb, Vb,
+                                            blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, qk, f"block {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} fresh={fresh}")
+
+
+def test_block_equals_rows_of_full_attention_when_cache_is_current():
+    cfg = wl.custom_config(B=2, H=4, Hkv=2, N=512, d=128, bl=64, prompt=256, G=256)
+    inp = wl.attention_inputs(cfg, 6)
+    full = gpu_bidir(inp, cfg)
+    for bs in (0, 256, 448):
+        Qblk = np.ascontiguousarray(inp["Q"][:, :, bs:bs + cfg.bl])
+        got = gpu_block(cfg, Qblk, inp["K"], inp["V"], bs)
+        mx, rl = attn_errors(got, full[:, :, bs:bs + cfg.bl])
+        assert mx <= 2e-2 and rl <= 5e-3, (bs, mx, rl)       # two tilings of the same sum: equal up to bf16 rounding
+        ref = oracle.block_attention_cached(Qblk, inp["K"], inp["V"], bs, wl.BF16, wl.BF16)
+        assert_attention_close(got, ref, wl.BF16, f"block@{bs} vs oracle")
+
+
+def test_errors_raise_through_the_binding():
+    import torch
+    q = torch.zeros((1, 2, 16, 64), dtype=torch.bfloat16, device="cuda:0")
+    kv = torch.zeros((1, 2, 64, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(dd.DDError):
+        dd.dd_block_attention_cached(q, kv, kv, 60)           # block runs past N
+    q96 = torch.zeros((1, 2, 16, 96), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(dd.DDError):
+        dd.dd_bidir_attention(q96, q96, q96)

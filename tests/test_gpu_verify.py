@@ -1,0 +1,207 @@
+"""GPU parity of dd_verify_remask against the CPU oracle (through the C ABI)."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2604_05250_amd as dd
+from paper_2604_05250_amd import workloads as wl
+from _util import assert_scores_close, remask_exempt, to_dev
+
+pytestmark = pytest.mark.gpu
+
+ALL_MODES = ((wl.TRUST, 0.0), (wl.KL_THRESH, 0.5), (wl.CONF_THRESH, 0.9), (wl.KL_PROB, 0.0), (wl.CONF_PROB, 0.0))
+
+
+def run_gpu(inp, mode, tau, seed, B, G, dtype, with_drafter=True):
+    ld = to_dev(inp["logits_d"]) if with_drafter else None
+    om, ot, osc = dd.dd_verify_remask(ld, to_dev(inp["logits_v"]), to_dev(inp["mask"]), mode, tau, seed, B, G,
+                                      logit_dtype=dtype)
+    import torch
+    torch.cuda.synchronize()
+    return om.cpu().numpy(), ot.cpu().numpy(), osc.cpu().numpy()
+
+
+def check_against_oracle(inp, mode, tau, seed, B, G, dtype, what):
+    kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB)
+    om, ot, osc = run_gpu(inp, mode, tau, seed, B, G, dtype, with_drafter=kl_mode)
+    ora = oracle.verify_remask(inp["logits_d"] if kl_mode else None, inp["logits_v"], inp["mask"], mode, tau, seed,
+                               B, G, dtype)
+    assert np.array_equal(ot, ora["out_tokens"]), f"{what}: argmax tokens differ"
+    assert_scores_close(osc, ora["score64"], what)
+    exempt = remask_exempt(ora, mode, tau, seed)
+    if mode == wl.KL_PROB:
+        # the GPU's probability uses its own fp32 scores; rows where the draw is within their
+        # propagated error of the probability are exempt as well
+        exempt |= np.abs(np.array([oracle.row_uniform(seed, i) for i in range(B * G)]) - ora["prob"]) <= 2e-3 * ora["prob"] + 1e-5
+    diff = (om != ora["out_mask"]) & ~exempt
+    assert not diff.any(), f"{what}: remask decisions differ at rows {np.nonzero(diff)[0][:8]}"
+    assert np.array_equal(om[inp["mask"] != 0], np.ones(int((inp["mask"] != 0).sum()), np.uint8))
+    return om, ot, osc, ora
+
+
+@pytest.mark.parametrize("mode,tau", ALL_MODES)
+def test_cfg1_all_modes(mode, tau):
+    cfg = wl.CONFIGS[1]
+    inp = wl.verify_inputs(cfg, seed=0)
+    om, ot, osc, ora = check_against_oracle(inp, mode, tau, 0, cfg.B, cfg.G, cfg.logit_dtype, f"cfg1 mode {mode}")
+    if mode == wl.TRUST:
+        assert np.array_equal(om, inp["mask"])
+        assert np.array_equal(ot, inp["logits_v"].argmax(axis=1))
+
+
+@pytest.mark.parametrize("mode", [wl.KL_THRESH, wl.CONF_THRESH, wl.KL_PROB, wl.CONF_PROB])
+def test_median_threshold_exercises_both_branches(mode):
+    cfg = wl.custom_config(B=3, G=50, V=4096, logit_dtype=wl.BF16, sigma_d=3.0, sigma_n=1.0, decoded_frac=0.6)
+    inp = wl.verify_inputs(cfg, seed=3)
+    kl, conf, _ = oracle.verify_scores(inp["logits_d"], inp["logits_v"], wl.BF16)
+    tau = float(np.median(kl if mode in (wl.KL_THRESH, wl.KL_PROB) else conf))
+    om, _, _, ora = check_against_oracle(inp, mode, tau, 12345, cfg.B, cfg.G, wl.BF16, f"median mode {mode}")
+    elig = inp["mask"] == 0
+    if mode in (wl.KL_THRESH, wl.CONF_THRESH):
+        frac = om[elig].mean()
+        assert 0.3 < frac < 0.7
+
+
+@pytest.mark.parametrize("V,dtype", [(8, wl.BF16), (1000, wl.BF16), (4, wl.F32), (1028, wl.F32), (8200, wl.BF16),
+                                     (40000, wl.BF16), (126464, wl.BF16)])
+def test_ragged_vocab_and_row_splits(V, dtype):
+    # small P with a large V makes the library split every row over several workgroups
+    cfg = wl.custom_config(B=2, G=5, V=V, logit_dtype=dtype, sigma_d=3.0, sigma_n=1.0)
+    inp = wl.verify_inputs(cfg, seed=5)
+    for mode, tau in ((wl.KL_THRESH, 0.4), (wl.CONF_THRESH, 0.01)):
+        check_against_oracle(inp, mode, tau, 0, cfg.B, cfg.G, dtype, f"V={V} dtype={dtype} mode={mode}")
+
+
+def test_degenerate_rows():
+    V = 2048
+    rng = np.random.default_rng(0)
+    rows = []
+    base = (rng.standard_normal(V) * 3).astype(np.float32)
+    r_tie = base.copy(); r_tie[[1500, 7, 900]] = 20.0                  # exact ties: lowest index wins
+    r_flat = np.zeros(V, np.float32)                                   # uniform: c = 1/V, token 0
+    r_hot = base.copy(); r_hot[1234] = 60.0                            # near one-hot: c -> 1
+    r_big = base + np.float32(1000.0)                                  # large magnitude: no overflow
+    r_neg = base - np.float32(80.0)
+    r_last = base.copy(); r_last[V - 1] = 30.0                         # maximum in the last vector
+    lv = np.stack([r_tie, r_flat, r_hot, r_big, r_neg, r_last, base, base])
+    ld = np.stack([base, r_flat, base, base + np.float32(1000.0), r_neg, base, base, r_hot])
+    for dtype in (wl.F32, wl.BF16):
+        inp = {"logits_d": ld if dtype == wl.F32 else wl.f32_to_bf16_bits(ld),
+               "logits_v": lv if dtype == wl.F32 else wl.f32_to_bf16_bits(lv),
+               "mask": np.zeros(8, np.uint8)}
+        om, ot, osc, ora = check_against_oracle(inp, wl.KL_THRESH, 0.3, 0, 1, 8, dtype, f"degenerate dtype {dtype}")
+        assert ot[0] == 7 and ot[1] == 0 and ot[2] == 1234 and ot[5] == V - 1
+        assert osc[6] == 0.0 and osc[1] == 0.0                         # KL(p || p) = 0 exactly
+        _, _, conf, _ = check_against_oracle(inp, wl.CONF_THRESH, 0.5, 0, 1, 8, dtype, "degenerate conf")
+        assert abs(conf[1] - 1.0 / V) < 1e-9 and conf[2] > 0.999
+
+
+def test_mask_extremes_and_threshold_equality():
+    cfg = wl.custom_config(B=2, G=16, V=512, logit_dtype=wl.F32)
+    inp = wl.verify_inputs(cfg, seed=9)
+    P = cfg.P
+    for m in (np.ones(P, np.uint8), np.zeros(P, np.uint8)):
+        inp2 = dict(inp, mask=m)
+        for mode, tau in ALL_MODES:
+            om, _, _, _ = check_against_oracle(inp2, mode, tau, 4, cfg.B, cfg.G, wl.F32, "mask extremes")
+            if m[0] == 1:
+                assert om.all()
+    # a score exactly equal to the threshold keeps the token (strict inequalities)
+    _, _, osc = run_gpu(inp, wl.KL_THRESH, 0.0, 0, cfg.B, cfg.G, wl.F32)
+    tau = float(osc[3])
+    om, _, osc2 = run_gpu(inp, wl.KL_THRESH, tau, 0, cfg.B, cfg.G, wl.F32)
+    assert osc2[3] == osc[3] and om[3] == 0
+    assert np.array_equal(om, (osc2 > np.float32(tau)).astype(np.uint8))
+    _, _, conf = run_gpu(inp, wl.CONF_THRESH, 0.0, 0, cfg.B, cfg.G, wl.F32, with_drafter=False)
+    om, _, conf2 = run_gpu(inp, wl.CONF_THRESH, float(conf[5]), 0, cfg.B, cfg.G, wl.F32, with_drafter=False)
+    assert om[5] == 0 and np.array_equal(om, (conf2 < conf[5]).astype(np.uint8))
+    # +-inf thresholds
+    om, _, _ = run_gpu(inp, wl.KL_THRESH, float("inf"), 0, cfg.B, cfg.G, wl.F32)
+    assert not om.any()
+    om, _, _ = run_gpu(inp, wl.KL_THRESH, float("-inf"), 0, cfg.B, cfg.G, wl.F32)
+    assert om.all()
+
+
+def test_empty_input_and_determinism():
+    import torch
+    e8 = torch.empty(0, dtype=torch.uint8, device="cuda:0")
+    lv = torch.empty((0, 1024), dtype=torch.float32, device="cuda:0")
+    om, ot, osc = dd.dd_verify_remask(lv, lv, e8, wl.KL_THRESH, 0.3, 0, 0, 16)
+    assert om.numel() == 0
+    cfg = wl.custom_config(B=2, G=20, V=32768, logit_dtype=wl.BF16)
+    inp = wl.verify_inputs(cfg, seed=2)
+    a = run_gpu(inp, wl.KL_PROB, 0.0, 77, cfg.B, cfg.G, wl.BF16)
+    b = run_gpu(inp, wl.KL_PROB, 0.0, 77, cfg.B, cfg.G, wl.BF16)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    c = run_gpu(inp, wl.KL_PROB, 0.0, 78, cfg.B, cfg.G, wl.BF16)
+    assert np.array_equal(a[2], c[2])          # the seed changes draws, not scores
+
+
+def test_probabilistic_rate_matches_probability():
+    # many rows with a known confidence: remask frequency ~ 1 - c
+    V, P = 16, 4096
+    lv = np.zeros((P, V), np.float32)
+    lv[:, 0] = np.log(3.0 * (V - 1))           # c = 0.75
+    inp = {"logits_d": lv, "logits_v": lv, "mask": np.zeros(P, np.uint8)}
+    om, _, osc = run_gpu(inp, wl.CONF_PROB, 0.0, 5, 1, P, wl.F32, with_drafter=False)
+    assert abs(float(osc[0]) - 0.75) < 1e-6
+    assert abs(om.mean() - 0.25) < 5 * np.sqrt(0.25 * 0.75 / P)
+    u = np.array([oracle.row_uniform(5, i) for i in range(P)])
+    want = (u < 1.0 - osc.astype(np.float64)).astype(np.uint8)
+    assert np.array_equal(om, want)
+
+
+# ------------------------------------------------------------------ benchmark configurations, full size
+def _full_size(cfg_id, n_sample, seed=0):
+    cfg = wl.CONFIGS[cfg_id]
+    inp = wl.verify_inputs(cfg, seed=seed)
+    rng = np.random.default_rng(100 + cfg_id)
+    rows = np.unique(np.concatenate([[0, cfg.P - 1, cfg.G - 1, cfg.G % cfg.P], rng.integers(0, cfg.P, n_sample)]))
+    import torch
+    ld = to_dev(inp["logits_d"]); lv = to_dev(inp["logits_v"]); mk = to_dev(inp["mask"])
+    for mode, tau in cfg.modes:
+        kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB)
+        om, ot, osc = dd.dd_verify_remask(ld if kl_mode else None, lv, mk, mode, tau, seed, cfg.B, cfg.G,
+                                          logit_dtype=cfg.logit_dtype)
+        torch.cuda.synchronize()
+        om, ot, osc = om.cpu().numpy(), ot.cpu().numpy(), osc.cpu().numpy()
+        kl, conf, tok = oracle.verify_scores(inp["logits_d"] if kl_mode else None, inp["logits_v"], cfg.logit_dtype,
+                                             rows=rows)
+        score = kl if kl_mode else conf
+        assert np.array_equal(ot[rows], tok), f"cfg{cfg_id} mode {mode}: tokens"
+        assert_scores_close(osc[rows], score, f"cfg{cfg_id} mode {mode}")
+        # decisions on the sampled rows against the oracle's rule ...
+        ora_mask, _ = oracle.remask_decide(score.astype(np.float32), inp["mask"][rows], mode, tau, seed, 1, len(rows))
+        exempt = np.abs(score - tau) <= 1e-5 * max(1.0, abs(tau))
+        assert np.array_equal(om[rows][~exempt], ora_mask[~exempt])
+        # ... and on every row as a property of the library's own scores
+        elig = inp["mask"] == 0
+        if mode == wl.TRUST:
+            want = inp["mask"]
+        elif mode == wl.KL_THRESH:
+            want = ((inp["mask"] != 0) | (elig & (osc > np.float32(tau)))).astype(np.uint8)
+        else:
+            want = ((inp["mask"] != 0) | (elig & (osc < np.float32(tau)))).astype(np.uint8)
+        assert np.array_equal(om, want)
+        assert ((ot >= 0) & (ot < cfg.V)).all() and np.isfinite(osc).all()
+        if kl_mode:
+            assert (osc > -1e-5).all()
+        else:
+            assert ((osc > 0) & (osc <= 1.0 + 1e-6)).all()
+
+
+def test_cfg2_full_size():
+    _full_size(2, 256)       # every row
+
+
+def test_cfg3_full_size():
+    _full_size(3, 96)
+
+
+def test_cfg4_full_size():
+    _full_size(4, 128)
+
+
+def test_cfg5_full_size():
+    _full_size(5, 64)
