@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of one DualDiffusion draft-then-verify step on one MI355X.
+
+A step = K drafter block-attention calls over the cached K/V, one verifier full
+bidirectional attention, one verification pass over the vocabulary (Alg. 1, one cycle),
+on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line:
+  value        = verifier attention TFLOP/s (4*B*H*N^2*d FLOP per call / its measured time)
+  ms_per_step  = wall time of the whole step (events around all kernels of the step)
+  roofline     = the attention kernel against the dense bf16 MFMA peak
+  roofline_verify = the verification kernels against the HBM peak
+  cpu_baseline = the fp64 CPU oracle timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "verifier attn TFLOP/s (% MFMA peak); verify GB/s (% HBM); draft+verify step ms"
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
+LLC_ROTATE_BYTES = 600e6      # rotate input sets until their total exceeds 2x the 256 MB last-level cache
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2604_05250_amd as dd
+    from paper_2604_05250_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    mode, tau = cfg.modes[-1]
+    kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB)
+
+    def up(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            a = a.view(np.int16)
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    # ---- seeded inputs, generated on the host (the oracle reads the same arrays), resident in HBM before timing
+    att = wl.attention_inputs(cfg, args.seed)
+    cache = wl.cache_inputs(cfg, args.seed)
+    ver = wl.verify_inputs(cfg, args.seed)
+    blocks = [wl.block_inputs(cfg, args.seed, k, k_scale=cache["k_scale"]) for k in range(cfg.K)]
+
+    eb_qk, eb_v, eb_l = wl.elem_bytes(cfg.qk_dtype), wl.elem_bytes(cfg.v_dtype), wl.elem_bytes(cfg.logit_dtype)
+    q_elems = cfg.B * cfg.H * cfg.N * cfg.d
+    kv_elems = cfg.B * cfg.Hkv * cfg.N * cfg.d
+    attn_bytes = q_elems * eb_qk + kv_elems * eb_qk + kv_elems * eb_v + q_elems * eb_v          # Q + K + V + O once
+    verify_bytes = (2 if kl_mode else 1) * cfg.P * cfg.V * eb_l                               # logits read once
+    blk_rows = cfg.B * cfg.H * cfg.bl * cfg.d
+    block_bytes = kv_elems * (eb_qk + eb_v) + blk_rows * (eb_qk + eb_v)                       # cache + Qblk + O
+    set_bytes = attn_bytes + verify_bytes + kv_elems * (eb_qk + eb_v)
+    n_sets = max(1, min(8, math.ceil(LLC_ROTATE_BYTES / set_bytes)))
+
+    sets = []
+    for _ in range(n_sets):
+        sets.append({
+            "Q": up(att["Q"]), "K": up(att["K"]), "V": up(att["V"]),
+            "Kc": up(cache["Kc"]), "Vc": up(cache["Vc"]),
+            "ld": up(ver["logits_d"]) if kl_mode else None, "lv": up(ver["logits_v"]),
+        })
+    qs, ks = up(att["q_scale"]), up(att["k_scale"])
+    kcs = up(cache["k_scale"])
+    mask = up(ver["mask"])
+    blk_dev = [{"Q": up(b["Qblk"]), "K": up(b["Kblk"]), "V": up(b["Vblk"]), "qs": up(b["q_scale"]),
+                "bs": b["block_start"]} for b in blocks]
+    o_dtype = sets[0]["V"].dtype
+    O = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=o_dtype, device=dev)
+    Oblk = torch.empty((cfg.B, cfg.H, cfg.bl, cfg.d), dtype=o_dtype, device=dev)
+    out_mask = torch.empty(cfg.P, dtype=torch.uint8, device=dev)
+    out_tok = torch.empty(cfg.P, dtype=torch.int32, device=dev)
+    out_sc = torch.empty(cfg.P, dtype=torch.float32, device=dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(i, rec=None):
+        s = sets[i % n_sets]
+        marks = [ev() for _ in range(4)] if rec is not None else None
+        if marks: marks[0].record()
+        for b in blk_dev:
+            dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], O=Oblk, Kblk=b["K"], Vblk=b["V"],
+                                         q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+        if marks: marks[1].record()
+        dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
+                              qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+        if marks: marks[2].record()
+        dd.dd_verify_remask(s["ld"], s["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
+                            out_mask=out_mask, out_tokens=out_tok, out_scores=out_sc, logit_dtype=cfg.logit_dtype)
+        if marks:
+            marks[3].record()
+            rec.append(marks)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    rec = []
+    t_begin, t_end = ev(), ev()
+    wall0 = time.perf_counter()
+    t_begin.record()
+    for i in range(args.steps):
+        step(args.warmup + i, rec)
+    t_end.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    total_ms = t_begin.elapsed_time(t_end)
+    ms_per_step = total_ms / args.steps
+    t_block = sum(m[0].elapsed_time(m[1]) for m in rec) / len(rec)         # K calls
+    t_attn = sum(m[1].elapsed_time(m[2]) for m in rec) / len(rec)
+    t_ver = sum(m[2].elapsed_time(m[3]) for m in rec) / len(rec)
+    assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
+
+    attn_flops = 4.0 * cfg.B * cfg.H * cfg.N * cfg.N * cfg.d
+    attn_tflops = attn_flops / (t_attn * 1e-3) / 1e12
+    ver_gbps = verify_bytes / (t_ver * 1e-3) / 1e9
+    blk_gbps = block_bytes / (t_block / cfg.K * 1e-3) / 1e9
+
+    out = {
+        "metric": METRIC, "value": round(attn_tflops, 3), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {wl.F32: "f32", wl.BF16: "bf16", wl.FP8_E4M3: "fp8_e4m3(QK)+bf16(V)"}[cfg.qk_dtype],
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
+                               f"drafter block_len={cfg.bl} x K={cfg.K} steps, verify P={cfg.P} x V={cfg.V} "
+                               f"mode={wl.MODE_NAMES[mode]} tau={tau}",
+                   "baseline_config_index": args.config - 1, "input_sets_rotated": n_sets, "seed": args.seed},
+        "verify_GBps": round(ver_gbps, 1),
+        "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
+                          "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
+        "block_attention_GBps": round(blk_gbps, 1),
+        "roofline": {"kernel": "attn_mfma_kernel (dd_bidir_attention)", "bound": "mfma",
+                     "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "roofline_verify": {"kernel": "verify_partial_kernel + verify_finalize_kernel (dd_verify_remask)",
+                            "bound": "hbm", "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                            "frac": round(ver_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+                            "algorithmic_bytes": verify_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        att_host = att
+        rng = np.random.default_rng(args.seed)
+
+        def rows(n):
+            return np.stack([rng.integers(0, cfg.B, n), rng.integers(0, cfg.H, n), rng.integers(0, cfg.N, n)], axis=1)
+
+        def run_attn(n):
+            t0 = time.perf_counter()
+            oracle.bidir_attention(att_host["Q"], att_host["K"], att_host["V"], cfg.qk_dtype, cfg.v_dtype,
+                                   att_host["q_scale"], att_host["k_scale"], rows=rows(n))
+            return time.perf_counter() - t0
+        n0 = 64
+        t0 = run_attn(n0)
+        n = int(min(max(n0, args.cpu_seconds / max(t0 / n0, 1e-9)), cfg.B * cfg.H * cfg.N))
+        t = run_attn(n)
+        cpu_tflops = n * 4.0 * cfg.N * cfg.d / t / 1e12
+        out["cpu_baseline"] = {"value": float(f"{cpu_tflops:.3e}"), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"fp64 oracle attention on {n} random (b,h,i) query rows of this workload "
+                                         f"({t:.1f} s); rate = rows*4*N*d FLOP / time"}
+
+        def run_ver(n):
+            r = rng.integers(0, cfg.P, n)
+            t0 = time.perf_counter()
+            oracle.verify_scores(ver["logits_d"] if kl_mode else None, ver["logits_v"], cfg.logit_dtype, rows=r)
+            return time.perf_counter() - t0
+        n0 = 32
+        t0 = run_ver(n0)
+        n = int(min(max(n0, args.cpu_seconds / max(t0 / n0, 1e-9)), 4 * cfg.P))
+        t = run_ver(n)
+        out["cpu_baseline_verify"] = {"value": round(n * (2 if kl_mode else 1) * cfg.V * eb_l / t / 1e9, 4),
+                                      "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+                                      "sample": f"fp64 oracle verify scores on {n} logit rows ({t:.1f} s)"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

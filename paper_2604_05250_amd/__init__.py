@@ -34,6 +34,10 @@ def lib():
     if not os.path.exists(LIB_PATH):
         from .build import build_library
         build_library(force=True)
+    # torch ships its own copy of the HIP runtime (same soname).  It has to be mapped first so
+    # that this library binds to that copy: streams and device pointers handed over by torch
+    # are only valid inside the runtime instance that created them.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i, sz = C.c_void_p, C.c_int, C.c_size_t
     L.dd_strerror.restype = C.c_char_p

@@ -150,9 +150,8 @@ hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t stream)
     fill_kernel_args(a, k, rows_per_wg, TKF);
     const long blocks = (long)a.B * a.Hkv * k.row_tiles * k.splits;
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
-    if (a.d == 128) hipLaunchKernelGGL((attn_f32_kernel<128>), grid, block, 0, stream, k);
-    else            hipLaunchKernelGGL((attn_f32_kernel<64>), grid, block, 0, stream, k);
-    hipError_t e = hipGetLastError();
+    const hipError_t e = a.d == 128 ? launch(attn_f32_kernel<128>, grid, block, stream, k)
+                                    : launch(attn_f32_kernel<64>, grid, block, stream, k);
     if (e != hipSuccess || k.splits == 1) return e;
     AttnArgs c = a;
     c.splits = k.splits;

@@ -355,14 +355,14 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     const long blocks = (long)a.B * a.Hkv * k.row_tiles * k.splits;
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     const bool fp8 = a.qk_dtype == 2;
+    hipError_t e;
     if (a.d == 128) {
-        if (fp8) hipLaunchKernelGGL((attn_mfma_kernel<128, true>), grid, block, 0, stream, k);
-        else     hipLaunchKernelGGL((attn_mfma_kernel<128, false>), grid, block, 0, stream, k);
+        if (fp8) e = launch(attn_mfma_kernel<128, true>, grid, block, stream, k);
+        else     e = launch(attn_mfma_kernel<128, false>, grid, block, stream, k);
     } else {
-        if (fp8) hipLaunchKernelGGL((attn_mfma_kernel<64, true>), grid, block, 0, stream, k);
-        else     hipLaunchKernelGGL((attn_mfma_kernel<64, false>), grid, block, 0, stream, k);
+        if (fp8) e = launch(attn_mfma_kernel<64, true>, grid, block, stream, k);
+        else     e = launch(attn_mfma_kernel<64, false>, grid, block, stream, k);
     }
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess || k.splits == 1) return e;
     AttnArgs c = a;
     c.splits = k.splits;
@@ -377,10 +377,8 @@ hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream)
     const long threads = rows * (a.d / 4);
     const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
     if (a.v_dtype == 1)
-        hipLaunchKernelGGL((attn_combine_kernel<true>), grid, block, 0, stream, po, pml, a.O, rows, a.splits, a.d);
-    else
-        hipLaunchKernelGGL((attn_combine_kernel<false>), grid, block, 0, stream, po, pml, a.O, rows, a.splits, a.d);
-    return hipGetLastError();
+        return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
+    return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
 }
 
 }  // namespace dd

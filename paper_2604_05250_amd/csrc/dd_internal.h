@@ -5,7 +5,26 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 namespace dd {
+
+// Launch through the runtime call that RETURNS the status of this launch, so that a stale
+// error left in the thread by an unrelated earlier runtime call is never reported as ours.
+template <typename... Params, size_t... I>
+inline hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                              std::tuple<Params...> &vals, std::index_sequence<I...>)
+{
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, 0, stream);
+}
+template <typename... Params, typename... Args>
+inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args)
+{
+    std::tuple<Params...> vals{args...};
+    return launch_impl(kernel, grid, block, stream, vals, std::index_sequence_for<Params...>{});
+}
 
 // ---- verification (verify.hip) -------------------------------------------------
 // Number of workgroups one logit row is split over, and workspace size.

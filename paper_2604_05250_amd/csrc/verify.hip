@@ -404,23 +404,20 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     const uint4 *ld = static_cast<const uint4 *>(logits_d);
     const uint4 *lv = static_cast<const uint4 *>(logits_v);
     const dim3 grid((unsigned)((long)P * S)), block(kThreads);
+    hipError_t e;
     if (logit_is_bf16) {
-        if (kl) hipLaunchKernelGGL((verify_partial_kernel<true, true>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
-        else    hipLaunchKernelGGL((verify_partial_kernel<true, false>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+        if (kl) e = launch(verify_partial_kernel<true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        else    e = launch(verify_partial_kernel<true, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
     } else {
-        if (kl) hipLaunchKernelGGL((verify_partial_kernel<false, true>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
-        else    hipLaunchKernelGGL((verify_partial_kernel<false, false>), grid, block, 0, stream, ld, lv, nvec, S, chunk, part);
+        if (kl) e = launch(verify_partial_kernel<false, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        else    e = launch(verify_partial_kernel<false, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
     }
-    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), 0, stream,
-                       part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
-    e = hipGetLastError();
+    e = launch(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), stream,
+               (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
     if (e != hipSuccess) return e;
-    if (mode == 3) {
-        hipLaunchKernelGGL(verify_klprob_kernel, dim3(B), dim3(256), 0, stream, out_scores, mask, G, seed, out_mask);
-        e = hipGetLastError();
-    }
+    if (mode == 3)
+        e = launch(verify_klprob_kernel, dim3(B), dim3(256), stream, (const float *)out_scores, mask, G, seed, out_mask);
     return e;
 }
 
