@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--parts", default="block,attention,verify",
+                    help="comma list of the step's parts to run (profiling a single kernel); default: the whole step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -106,19 +108,23 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
+    parts = set(args.parts.split(","))
+
     def step(i, rec=None):
         s = sets[i % n_sets]
         marks = [ev() for _ in range(4)] if rec is not None else None
         if marks: marks[0].record()
-        for b in blk_dev:
+        for b in (blk_dev if "block" in parts else ()):
             dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], O=Oblk, Kblk=b["K"], Vblk=b["V"],
                                          q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
         if marks: marks[1].record()
-        dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
-                              qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+        if "attention" in parts:
+            dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
+                                  qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
         if marks: marks[2].record()
-        dd.dd_verify_remask(s["ld"], s["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
-                            out_mask=out_mask, out_tokens=out_tok, out_scores=out_sc, logit_dtype=cfg.logit_dtype)
+        if "verify" in parts:
+            dd.dd_verify_remask(s["ld"], s["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
+                                out_mask=out_mask, out_tokens=out_tok, out_scores=out_sc, logit_dtype=cfg.logit_dtype)
         if marks:
             marks[3].record()
             rec.append(marks)
@@ -140,7 +146,9 @@ def main():
     t_block = sum(m[0].elapsed_time(m[1]) for m in rec) / len(rec)         # K calls
     t_attn = sum(m[1].elapsed_time(m[2]) for m in rec) / len(rec)
     t_ver = sum(m[2].elapsed_time(m[3]) for m in rec) / len(rec)
-    assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
+    if "verify" in parts:
+        assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
+    t_block, t_attn, t_ver = (max(t, 1e-9) for t in (t_block, t_attn, t_ver))
 
     attn_flops = 4.0 * cfg.B * cfg.H * cfg.N * cfg.N * cfg.d
     attn_tflops = attn_flops / (t_attn * 1e-3) / 1e12
@@ -156,7 +164,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
                                f"drafter block_len={cfg.bl} x K={cfg.K} steps, verify P={cfg.P} x V={cfg.V} "
                                f"mode={wl.MODE_NAMES[mode]} tau={tau}",
-                   "baseline_config_index": args.config - 1, "input_sets_rotated": n_sets, "seed": args.seed},
+                   "baseline_config_index": args.config - 1, "input_sets_rotated": n_sets, "seed": args.seed,
+                   "parts": sorted(parts)},
         "verify_GBps": round(ver_gbps, 1),
         "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},

@@ -20,6 +20,8 @@
 #include "attention_common.h"
 #include "dd_internal.h"
 
+#include <type_traits>
+
 namespace dd {
 namespace {
 
@@ -58,23 +60,63 @@ __device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint2 w)
                       pack_bf16_trunc(c.x, c.y), pack_bf16_trunc(d.x, d.y));
 }
 
-template <int D, bool FP8>
+// exchange between lane l and lane l^32 (one v_permlane32_swap), then combine
+__device__ __forceinline__ float half_swap_max(float x)
+{
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float half_swap_sum(float x)
+{
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
+// acc += p.lo + p.hi for a packed pair of bf16 (v_dot2c_f32_bf16 against (1, 1))
+__device__ __forceinline__ float add_bf16_pair(unsigned packed, float acc)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3F803F80u);
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), ones, acc, false);
+}
+
+// The running maximum used for exponentiation is raised only when a tile's maximum exceeds it
+// by more than this many powers of two; until then probabilities are at most 2^8, which bf16
+// and the fp32 accumulators hold without loss, and the 64 accumulator multiplies are skipped.
+constexpr float kRescaleSlack = 8.0f;
+
+// BLOCK = false: verifier attention (all rows of a head attend all keys, O written directly).
+// BLOCK = true : drafter block attention (key rows of the active block may come from the fresh
+//                block tensors, the key range may be split, partial states go to the workspace).
+template <int D, bool FP8, bool BLOCK>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKernelArgs a)
 {
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
     constexpr int KCH = TK * CH / kAttnThreads;      // K chunks staged per thread
+    constexpr int KROWS = kAttnThreads / CH;         // K rows covered by one pass of the workgroup
     constexpr int VTASKS = (TK / 8) * CH * 2;        // V transpose tasks per tile (4 keys x 8 dims)
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
+    constexpr int KELEM = FP8 ? 1 : 2;               // bytes per K element in memory
     static_assert(KCH >= 1 && VTASKS <= kAttnThreads, "tile does not fit the staging scheme");
 
-    __shared__ uint4 Ks[TK * CH];                    // [key][chunk ^ (key & 7)]
-    __shared__ uint4 Vt[D * (TK / 8)];               // [dim][keygroup ^ swz(dim)], 8 keys per 16 bytes
+    __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
+    __shared__ uint4 Vt[2][D * (TK / 8)];            // [dim][keygroup ^ swz(dim)], 8 keys per 16 bytes
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
 
+    // ---- which (batch, kv head, row tile, key split) this workgroup owns
     int bid = blockIdx.x;
+    if (!BLOCK) {
+        // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Remap so that the
+        // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD.
+        const int total = gridDim.x, per = total >> 3, rem = total & 7;
+        const int xcd = bid & 7, slot = bid >> 3;
+        bid = xcd * per + min(xcd, rem) + slot;
+    }
     const int sp = bid % a.splits; bid /= a.splits;
     const int rt = bid % a.row_tiles; bid /= a.row_tiles;
     const int kvh = bid % a.Hkv;
@@ -98,7 +140,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         else w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.Q) + off);
         qf[ks] = __builtin_bit_cast(bf16x8, w);
     }
-    float c = a.scale_log2;
+    float c = a.scale_log2;                          // scores are exponentiated as 2^(s*c)
     if (a.q_scale) c *= a.q_scale[b * a.H + head];
     if (a.k_scale) c *= a.k_scale[b * a.Hkv + kvh];
 
@@ -110,61 +152,73 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // ---- staging: global -> registers -> LDS
     uint4 kreg[KCH];
     uint4 vreg[4];
+    const int k_row0 = tid / CH, k_ch = tid % CH;                                  // K chunk i: row k_row0 + i*KROWS
     const int vt_dchunk = tid % CH, vt_e4 = (tid / CH) & 1, vt_g = tid / (2 * CH);   // V task of this thread
     // keys of task (g, e4): tile-local index (g/4)*32 + ((g/2)&1)*16 + 8*e4 + 4*(g&1) + e,  e = 0..3
     const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
+    const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
+    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)(D * 2) + vt_dchunk * 16;
 
-    auto src_row = [&](int j, const void *cache, const void *blk, int elem_bytes) -> const uint8_t * {
-        // row j of the key/value sequence: the fresh block tensor inside the active block, else the cache
-        if (blk != nullptr && j >= a.block_start && j < a.block_start + a.block_len)
-            return static_cast<const uint8_t *>(blk) +
-                   ((kv_head * a.block_len + (size_t)(j - a.block_start)) * D) * elem_bytes;
-        return static_cast<const uint8_t *>(cache) + ((kv_head * a.N + (size_t)j) * D) * elem_bytes;
+    // address of key row j's chunk for this thread; rows past the range are clamped to the last
+    // valid row (their scores are masked to -inf, their values multiply a zero probability)
+    auto k_src = [&](int j) -> const uint8_t * {
+        j = min(j, k_end - 1);
+        if (BLOCK && j >= a.block_start && j < a.block_start + a.block_len)
+            return static_cast<const uint8_t *>(a.Kblk) +
+                   (kv_head * a.block_len + (size_t)(j - a.block_start)) * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
+        return k_base + (size_t)j * (D * KELEM);
     };
-    auto load_tile = [&](int t) {
-        const int k0 = k_begin + t * TK;
+    auto v_src = [&](int j) -> const uint8_t * {
+        j = min(j, k_end - 1);
+        if (BLOCK && j >= a.block_start && j < a.block_start + a.block_len)
+            return static_cast<const uint8_t *>(a.Vblk) +
+                   (kv_head * a.block_len + (size_t)(j - a.block_start)) * (size_t)(D * 2) + vt_dchunk * 16;
+        return v_base + (size_t)j * (D * 2);
+    };
+    // K is staged in windows of 64 keys that are offset by half a tile against the V tiles:
+    // window w = keys [64w+32, 64w+96) relative to the range start.  A ring of 128 rows then always
+    // holds the two 32-key units the current stage multiplies while the next window is written.
+    const int nkeys = k_end - k_begin;
+    auto load_k = [&](int j0, int nch) {               // rows j0 + k_row0 + i*KROWS, i < nch
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
-            const int id = tid + i * kAttnThreads;
-            const int row = id / CH, ch = id % CH;
-            const int j = k0 + row;
-            uint4 w = make_uint4(0, 0, 0, 0);
-            if (j < k_end) {
+            if (i < nch) {
+                const uint8_t *p = k_src(k_begin + j0 + k_row0 + i * KROWS);
                 if (FP8) {
-                    const uint2 r = *reinterpret_cast<const uint2 *>(src_row(j, a.K, a.Kblk, 1) + ch * 8);
-                    w = make_uint4(r.x, r.y, 0, 0);
+                    const uint2 r = *reinterpret_cast<const uint2 *>(p);
+                    kreg[i] = make_uint4(r.x, r.y, 0, 0);
                 } else {
-                    w = *reinterpret_cast<const uint4 *>(src_row(j, a.K, a.Kblk, 2) + ch * 16);
+                    kreg[i] = *reinterpret_cast<const uint4 *>(p);
                 }
             }
-            kreg[i] = w;
         }
+    };
+    auto load_v = [&](int t) {
+        const int k0 = k_begin + t * TK;
         if (tid < VTASKS) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = k0 + vt_key0 + e;
-                uint4 w = make_uint4(0, 0, 0, 0);
-                if (j < k_end) w = *reinterpret_cast<const uint4 *>(src_row(j, a.V, a.Vblk, 2) + vt_dchunk * 16);
-                vreg[e] = w;
+            for (int e = 0; e < 4; ++e) vreg[e] = *reinterpret_cast<const uint4 *>(v_src(k0 + vt_key0 + e));
+        }
+    };
+    auto store_k = [&](int j0, int nch) {
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            if (i < nch) {
+                const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
+                uint4 w = kreg[i];
+                if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
+                Ks[row * CH + (k_ch ^ (row & 7))] = w;
             }
         }
     };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            const int id = tid + i * kAttnThreads;
-            const int row = id / CH, ch = id % CH;
-            uint4 w = kreg[i];
-            if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
-            Ks[row * CH + (ch ^ (row & 7))] = w;
-        }
+    auto store_v = [&](int buf) {
         if (tid < VTASKS) {
             // 4 keys x 8 dims -> 8 dims x 4 keys
             const unsigned r0[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
             const unsigned r1[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
             const unsigned r2[4] = {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w};
             const unsigned r3[4] = {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w};
-            uint2 *vt2 = reinterpret_cast<uint2 *>(Vt);
+            uint2 *vt2 = reinterpret_cast<uint2 *>(Vt[buf]);
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 // dims 2p (low halves) and 2p+1 (high halves)
@@ -183,91 +237,203 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     for (int i = 0; i < DC; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-    float m_run = -INFINITY;     // running max of raw scores (same in both lane halves)
+    float mc = -INFINITY;        // maximum in use, in log2 units (raw score * c); equal in both lane halves
     float l_run = 0.f;           // this lane half's share of the running sum
 
-    load_tile(0);
-    for (int t = 0; t < ntiles; ++t) {
-        __syncthreads();
-        store_tile();
-        __syncthreads();
-        if (t + 1 < ntiles) load_tile(t + 1);
-        if (!wave_active) continue;
+    // The softmax works on units of 32 keys x 32 queries (one accumulator block, 16 scores per
+    // lane); an LDS tile holds two units.
 
-        // S^T tiles: two 32-key x 32-query blocks
-        floatx16 s[2];
+    // matrix-core step ks (16 head dims) of S^T = K Q^T for the 32-key unit u (keys 32u .. 32u+31)
+    auto qk_step = [&](int u, int ks, floatx16 &s) {
+        const int krow = (u & 3) * 32 + l32;
+        const uint4 w = Ks[krow * CH + ((2 * ks + hh) ^ (krow & 7))];
+        floatx16 cin = s;
+        if (ks == 0) {
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s[sub][r] = 0.f;
-            const int krow = sub * 32 + l32;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const uint4 w = Ks[krow * CH + ((2 * ks + hh) ^ (krow & 7))];
-                s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), qf[ks], s[sub], 0, 0, 0);
-            }
+            for (int r = 0; r < 16; ++r) cin[r] = 0.f;
         }
-        // keys past the end of the range score -inf (only the last tile can be ragged)
-        const int k0 = k_begin + t * TK;
-        if (k0 + TK > k_end) {
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int kk = sub * 32 + 8 * (r >> 2) + 4 * hh + (r & 3);
-                    if (k0 + kk >= k_end) s[sub][r] = -INFINITY;
-                }
-        }
-        float tmax = s[0][0];
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, s[sub][r]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float m_new = fmaxf(m_run, tmax);
-        const float corr = fast_exp2((m_run - m_new) * c);   // first tile: exp2(-inf) = 0
-        m_run = m_new;
-        const float mc = m_new * c;
-        unsigned pk[2][2][4];     // [sub][16-key step][4 dwords = 8 bf16], already in B-operand order
-        float psum = 0.f;
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = fast_exp2(fmaf(s[sub][r], c, -mc));
-                const float p1 = fast_exp2(fmaf(s[sub][r + 1], c, -mc));
-                psum += p0 + p1;
-                pk[sub][r >> 3][(r & 7) >> 1] = pack_bf16_rne(p0, p1);
-            }
-        l_run = l_run * corr + psum;
-#pragma unroll
-        for (int i = 0; i < DC; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][r] *= corr;
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), qf[ks], cin, 0, 0, 0);
+    };
 
-        // O^T += V^T P^T
+    // keys past the end of the range score -inf (only the last tile can be ragged)
+    auto mask_tail = [&](int t, int sub, floatx16 &s) {
+        const int k0 = k_begin + t * TK + sub * 32;
+        if (k0 + 32 > k_end) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (k0 + 8 * (r >> 2) + 4 * hh + (r & 3) >= k_end) s[r] = -INFINITY;
+        }
+    };
+
+    // unit maximum; raise the maximum in use (and rescale the running state) only when needed
+    auto update_max = [&](const floatx16 &s) {
+        float tmax = s[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
+        const float tm = half_swap_max(tmax) * c;
+        if (__any(tm > mc + kRescaleSlack)) {        // always true on the first unit (mc = -inf)
+            const float mn = fmaxf(mc, tm);
+            const float corr = fast_exp2(mc - mn);
+            mc = mn;
+            l_run *= corr;
+#pragma unroll
+            for (int i = 0; i < DC; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][r] *= corr;
+        }
+    };
+
+    // probabilities of scores (2*step, 2*step+1) of a unit, packed to bf16 in B-operand order
+    auto exp_step = [&](int step, const floatx16 &s, unsigned (&pk)[2][4]) {
+        const int r = step * 2;
+#ifdef DDX_NOEXP
+        const float p0 = s[r], p1 = s[r + 1];
+#else
+        const float p0 = fast_exp2(fmaf(s[r], c, -mc));
+        const float p1 = fast_exp2(fmaf(s[r + 1], c, -mc));
+#endif
+        const unsigned w = pack_bf16_rne(p0, p1);
+        l_run += p0 + p1;     // plain adds: v_dot2c_f32_bf16 would serialise with the matrix cores
+        pk[r >> 3][(r & 7) >> 1] = w;
+    };
+
+    // O^T += V^T P^T for one unit
+    auto pv = [&](int buf, int sub, const unsigned (&pk)[2][4]) {   // buf = tile & 1, sub = unit within the tile
 #pragma unroll
         for (int i = 0; i < DC; ++i) {
             const int drow = i * 32 + l32;
             const int swz = (drow ^ (drow >> 3)) & 7;
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
+            for (int st = 0; st < 2; ++st) {
+                const int g = sub * 4 + st * 2 + hh;
+                const uint4 w = Vt[buf][drow * (TK / 8) + (g ^ swz)];
+                const uint4 pw = make_uint4(pk[st][0], pk[st][1], pk[st][2], pk[st][3]);
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w),
+                                                                 __builtin_bit_cast(bf16x8, pw), acc[i], 0, 0, 0);
+            }
+        }
+    };
+
+    // Softmax + PV of unit u (scores in s_cur) while, if have_next, the scores of unit u+1 are
+    // produced into s_nxt: the matrix-core steps are interleaved one by one with the exponentials,
+    // so the vector ALU work runs in the shadow of the matrix cores within the same wave.
+    // LDS fragment m of a unit's 16 matrix-core slots: slots 0..KS-1 are the K fragments of unit u+1,
+    // the following 2*DC are the V fragments of unit u (k-step major, 32-dim chunk minor)
+    auto frag = [&](int u, int m) -> uint4 {
+#ifdef DDX_NOLDSREAD
+        return make_uint4(u + m, l32, hh, 0x3f803f80u);
+#endif
+        if (m < KS) {
+            const int krow = ((u + 1) & 3) * 32 + l32;
+            return Ks[krow * CH + ((2 * m + hh) ^ (krow & 7))];
+        }
+        const int j = m - KS, st = j / DC, i = j % DC;
+        const int drow = i * 32 + l32;
+        const int g = (u & 1) * 4 + st * 2 + hh;
+        return Vt[(u >> 1) & 1][drow * (TK / 8) + (g ^ ((drow ^ (drow >> 3)) & 7))];
+    };
+    auto unit = [&](int u, floatx16 &s_cur, bool have_next, floatx16 &s_nxt) {
+        unsigned pk[2][4];
+#ifndef DDX_NOMAX
+        update_max(s_cur);
+#endif
+        if (have_next) {
+            constexpr int NSLOT = KS + 2 * DC;              // matrix-core slots of the unit
+            constexpr int PD = 3;                           // fragments requested this many slots ahead
+            uint4 fq[NSLOT];
 #pragma unroll
-                for (int st = 0; st < 2; ++st) {
-                    const int g = sub * 4 + st * 2 + hh;
-                    const uint4 w = Vt[drow * (TK / 8) + (g ^ swz)];
-                    const uint4 pw = make_uint4(pk[sub][st][0], pk[sub][st][1], pk[sub][st][2], pk[sub][st][3]);
-                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w),
-                                                                     __builtin_bit_cast(bf16x8, pw), acc[i], 0, 0, 0);
+            for (int m = 0; m < PD; ++m) fq[m] = frag(u, m);
+            constexpr int every = 8 / KS > 0 ? 8 / KS : 1;
+#pragma unroll
+            for (int step = 0; step < 8; ++step) {
+                if (step % every == 0) {
+                    const int m = step / every;
+                    if (m + PD < NSLOT) fq[m + PD] = frag(u, m + PD);
+                    floatx16 cin = s_nxt;
+                    if (m == 0) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) cin[r] = 0.f;
+                    }
+#ifndef DDX_NOQK
+                    s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fq[m]), qf[m], cin, 0, 0, 0);
+#else
+                    s_nxt[m] += __uint_as_float(fq[m].x);
+#endif
                 }
+                exp_step(step, s_cur, pk);
+            }
+#pragma unroll
+            for (int j = 0; j < 2 * DC; ++j) {
+                const int m = KS + j, st = j / DC, i = j % DC;
+                if (m + PD < NSLOT) fq[m + PD] = frag(u, m + PD);
+                const uint4 pw = make_uint4(pk[st][0], pk[st][1], pk[st][2], pk[st][3]);
+#ifndef DDX_NOPV
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fq[m]),
+                                                                 __builtin_bit_cast(bf16x8, pw), acc[i], 0, 0, 0);
+#else
+                acc[i][j] += __uint_as_float(fq[m].x ^ pw.x ^ pw.y ^ pw.z ^ pw.w);
+#endif
+            }
+        } else {
+#pragma unroll
+            for (int step = 0; step < 8; ++step) exp_step(step, s_cur, pk);
+            pv((u >> 1) & 1, u & 1, pk);
+        }
+    };
+
+    constexpr int UNIT0_CH = 32 / KROWS;               // chunks per thread to stage keys 0..31
+    load_k(0, UNIT0_CH);
+    load_v(0);
+    store_k(0, UNIT0_CH);
+    store_v(0);
+    if (32 < nkeys) {
+        load_k(32, KCH);                               // window 0: units 1 and 2
+        store_k(32, KCH);
+    }
+    __syncthreads();
+    floatx16 s_a, s_b;
+    if (wave_active) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qk_step(0, ks, s_a);
+    }
+    __syncthreads();   // unit 0's ring slot is rewritten at the end of stage 0: every wave must have read it
+    // Stage t: on entry units 2t .. 2t+2 of K and tile t of V are in LDS, s_a holds the scores of unit 2t.
+    for (int t = 0; t + 1 < ntiles; ++t) {
+        const bool more_k = TK * (t + 1) + 32 < nkeys;  // window t+1 = units 2t+3, 2t+4
+#ifndef DDX_NOSTAGE
+        if (more_k) load_k(TK * (t + 1) + 32, KCH);
+        load_v(t + 1);
+#endif
+        if (wave_active) {
+            unit(2 * t, s_a, true, s_b);
+            unit(2 * t + 1, s_b, true, s_a);
+        }
+#ifndef DDX_NOSTAGE
+        if (more_k) store_k(TK * (t + 1) + 32, KCH);   // overwrites units 2t-1, 2t: read one stage ago
+        store_v((t + 1) & 1);                          // overwrites V(t-1): read one stage ago
+#endif
+#ifndef DDX_NOBARRIER
+        __syncthreads();
+#endif
+    }
+    if (wave_active) {                                  // last tile: nothing to prefetch, possibly ragged
+        const int t = ntiles - 1;
+        const bool two_units = TK * t + 32 < nkeys;
+        mask_tail(t, 0, s_a);
+        if (two_units) {
+            unit(2 * t, s_a, true, s_b);
+            mask_tail(t, 1, s_b);
+            unit(2 * t + 1, s_b, false, s_a);
+        } else {
+            unit(2 * t, s_a, false, s_b);
         }
     }
 
     if (!wave_active) return;
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = half_swap_sum(l_run);
     if (!row_ok) return;
     // accumulator register r of chunk i holds dim 32*i + 8*(r/4) + 4*hh + (r%4) of this lane's query
-    if (a.splits == 1) {
+    if (!BLOCK || a.splits == 1) {
         const float inv = 1.0f / l_tot;
         uint16_t *o = static_cast<uint16_t *>(a.O) + orow * D;
 #pragma unroll
@@ -288,9 +454,349 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
                     make_float4(acc[i][4 * q4], acc[i][4 * q4 + 1], acc[i][4 * q4 + 2], acc[i][4 * q4 + 3]);
         if (hh == 0) {
             float *ml = a.part_ml + (orow * a.splits + sp) * 2;
-            ml[0] = m_run * c;
+            ml[0] = mc;
             ml[1] = l_tot;
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Verifier attention, wide-wave form: one wave owns 64 query rows (two 32-row blocks A and B) and is
+// alone on its SIMD (up to 512 registers), one workgroup = 4 waves = 256 query rows of one
+// (batch, kv head).  Every K fragment and every V fragment read from LDS now feeds two matrix-core
+// instructions (one per block), which halves the LDS bytes per FLOP: with 32 rows per wave each
+// MFMA needs its own 1 KB LDS read and the 128 B/clk LDS port saturates near 3/4 of the MFMA rate.
+// With a single wave per SIMD there is no other wave to overlap with, so the instruction stream
+// itself alternates matrix-core and vector work:
+//     phase 1   S(u+1) = K(u+1) Q^T   (MFMA)   interleaved with   P(u) = 2^(S(u) c - m)   (VALU)
+//     phase 2   O^T   += V(u)^T P(u)^T (MFMA)   interleaved with   row maxima of S(u+1)     (VALU)
+// for 32-key units u; the running maximum is raised (and the accumulators rescaled) in a rare
+// branch between units.
+template <int D, bool FP8>
+__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void attn_bidir64_kernel(const AttnKernelArgs a)
+{
+    constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
+    constexpr int KCH = TK * CH / kAttnThreads;      // K chunks staged per thread
+    constexpr int KROWS = kAttnThreads / CH;         // K rows covered by one pass of the workgroup
+    constexpr int VTASKS = (TK / 8) * CH * 2;        // V transpose tasks per tile (4 keys x 8 dims)
+    constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
+    constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
+    constexpr int KELEM = FP8 ? 1 : 2;               // bytes per K element in memory
+    constexpr int QB = 2;                            // 32-row query blocks per wave
+    constexpr int kRowsWave = 32 * QB, kRowsWG = 4 * kRowsWave;
+
+    __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
+    __shared__ uint4 Vt[2][D * (TK / 8)];            // [dim][keygroup ^ swz(dim)], 8 keys per 16 bytes
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hh = lane >> 5;
+
+    // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD (own L2 each)
+    int bid = blockIdx.x;
+    {
+        const int total = gridDim.x, per = total >> 3, rem = total & 7;
+        const int xcd = bid & 7, slot = bid >> 3;
+        bid = xcd * per + min(xcd, rem) + slot;
+    }
+    const int rt = bid % a.row_tiles; bid /= a.row_tiles;
+    const int kvh = bid % a.Hkv;
+    const int b = bid / a.Hkv;
+    const int rows_total = a.group * a.Nq;
+    const bool wave_active = rt * kRowsWG + wave * kRowsWave < rows_total;
+
+    bool row_ok[QB];
+    size_t orow[QB];
+    float c[QB];                                     // scores are exponentiated as 2^(s*c)
+    bf16x8 qf[QB][KS];                               // B operand of S^T = K Q^T
+#pragma unroll
+    for (int q = 0; q < QB; ++q) {
+        const int v = rt * kRowsWG + wave * kRowsWave + q * 32 + l32;
+        row_ok[q] = v < rows_total;
+        const int vv = row_ok[q] ? v : rows_total - 1;
+        const int head = kvh * a.group + vv / a.Nq;
+        orow[q] = ((size_t)b * a.H + head) * (size_t)a.Nq + vv % a.Nq;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const size_t off = orow[q] * D + ks * 16 + hh * 8;
+            uint4 w;
+            if (FP8) w = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(a.Q) + off));
+            else w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.Q) + off);
+            qf[q][ks] = __builtin_bit_cast(bf16x8, w);
+        }
+        c[q] = a.scale_log2;
+        if (a.q_scale) c[q] *= a.q_scale[b * a.H + head];
+        if (a.k_scale) c[q] *= a.k_scale[b * a.Hkv + kvh];
+    }
+
+    const int nkeys = a.N;
+    const int ntiles = (nkeys + TK - 1) / TK;
+    const int nunits = (nkeys + 31) / 32;
+    const size_t kv_head = (size_t)b * a.Hkv + kvh;
+
+    // ---- staging: global -> registers -> LDS (K in half-tile-offset windows, V per tile)
+    uint4 kreg[KCH];
+    uint4 vreg[4];
+    const int k_row0 = tid / CH, k_ch = tid % CH;
+    const int vt_dchunk = tid % CH, vt_e4 = (tid / CH) & 1, vt_g = tid / (2 * CH);
+    const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
+    const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
+    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)(D * 2) + vt_dchunk * 16;
+    auto load_k = [&](int j0, int nch) {               // rows j0 + k_row0 + i*KROWS, clamped into the sequence
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            if (i < nch) {
+                const uint8_t *p = k_base + (size_t)min(j0 + k_row0 + i * KROWS, nkeys - 1) * (D * KELEM);
+                if (FP8) {
+                    const uint2 r = *reinterpret_cast<const uint2 *>(p);
+                    kreg[i] = make_uint4(r.x, r.y, 0, 0);
+                } else {
+                    kreg[i] = *reinterpret_cast<const uint4 *>(p);
+                }
+            }
+        }
+    };
+    auto store_k = [&](int j0, int nch) {
+#pragma unroll
+        for (int i = 0; i < KCH; ++i) {
+            if (i < nch) {
+                const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
+                uint4 w = kreg[i];
+                if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
+                Ks[row * CH + (k_ch ^ (row & 7))] = w;
+            }
+        }
+    };
+    auto load_v = [&](int t) {
+        if (tid < VTASKS) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                vreg[e] = *reinterpret_cast<const uint4 *>(v_base + (size_t)min(t * TK + vt_key0 + e, nkeys - 1) * (D * 2));
+        }
+    };
+    auto store_v = [&](int buf) {
+        if (tid < VTASKS) {
+            const unsigned r0[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
+            const unsigned r1[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
+            const unsigned r2[4] = {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w};
+            const unsigned r3[4] = {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w};
+            uint2 *vt2 = reinterpret_cast<uint2 *>(Vt[buf]);
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint2 even = make_uint2((r0[p] & 0xFFFFu) | (r1[p] << 16), (r2[p] & 0xFFFFu) | (r3[p] << 16));
+                const uint2 odd = make_uint2((r0[p] >> 16) | (r1[p] & 0xFFFF0000u), (r2[p] >> 16) | (r3[p] & 0xFFFF0000u));
+                const int d0 = vt_dchunk * 8 + 2 * p, d1 = d0 + 1;
+                vt2[(d0 * (TK / 8) + (vt_g ^ ((d0 ^ (d0 >> 3)) & 7))) * 2 + vt_e4] = even;
+                vt2[(d1 * (TK / 8) + (vt_g ^ ((d1 ^ (d1 >> 3)) & 7))) * 2 + vt_e4] = odd;
+            }
+        }
+    };
+    // loads for the tile after stage t's (issued at the stage's first unit), stores + barrier at its second
+    auto stage_pre = [&](int t) {
+        if (t + 1 < ntiles) {
+            if (TK * (t + 1) + 32 < nkeys) load_k(TK * (t + 1) + 32, KCH);
+            load_v(t + 1);
+        }
+    };
+    auto stage_post = [&](int t) {
+        if (t + 1 < ntiles) {
+            if (TK * (t + 1) + 32 < nkeys) store_k(TK * (t + 1) + 32, KCH);
+            store_v((t + 1) & 1);
+        }
+        __syncthreads();
+    };
+
+    // ---- per-lane state of the two query blocks
+    floatx16 acc[QB][DC];
+#pragma unroll
+    for (int q = 0; q < QB; ++q)
+#pragma unroll
+        for (int i = 0; i < DC; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[q][i][r] = 0.f;
+    float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
+    float l_run[QB] = {0.f, 0.f};                    // this lane half's share of the running sums
+
+    // accumulator start of a score block: 0, or -inf for the keys of unit u at or past the end
+    auto score_init = [&](int u) {
+        floatx16 z;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) z[r] = (32 * u + 8 * (r >> 2) + 4 * hh + (r & 3) >= nkeys) ? -INFINITY : 0.f;
+        return z;
+    };
+    auto k_frag = [&](int u, int ks) {
+        const int krow = (u & 3) * 32 + l32;
+        return __builtin_bit_cast(bf16x8, Ks[krow * CH + ((2 * ks + hh) ^ (krow & 7))]);
+    };
+    auto v_frag = [&](int u, int i, int st) {
+        const int drow = i * 32 + l32;
+        const int g = (u & 1) * 4 + st * 2 + hh;
+        return __builtin_bit_cast(bf16x8, Vt[(u >> 1) & 1][drow * (TK / 8) + (g ^ ((drow ^ (drow >> 3)) & 7))]);
+    };
+    // S^T = K Q^T of unit u for both blocks: every K fragment feeds two matrix-core instructions
+    auto scores = [&](int u, floatx16 (&s)[QB], auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        floatx16 z;
+        if (MASKED) z = score_init(u);
+        else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) z[r] = 0.f;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 kf = k_frag(u, ks);
+#pragma unroll
+            for (int q = 0; q < QB; ++q)
+                s[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[q][ks], ks == 0 ? z : s[q], 0, 0, 0);
+        }
+    };
+    // Row maxima of a unit decide, without a branch, whether the maxima in use are raised; returns the
+    // factors 2^(old - new) (1 when nothing changes) that the running state must be multiplied by.
+    auto settle_max = [&](const floatx16 (&s)[QB], float (&corr)[QB]) -> bool {
+        float tm[QB];
+        bool need = false;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            float t = s[q][0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) t = fmaxf(t, s[q][r]);
+            tm[q] = half_swap_max(t) * c[q];
+            need = need || (tm[q] > mc[q] + kRescaleSlack);
+        }
+        const bool any_need = __any(need);                 // wave-uniform
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const float mn = any_need ? fmaxf(mc[q], tm[q]) : mc[q];
+            corr[q] = fast_exp2(mc[q] - mn);                // first unit: 2^(-inf) = 0
+            mc[q] = mn;
+        }
+        return any_need;
+    };
+    auto rescale = [&](const float (&corr)[QB]) {          // rare: the accumulators change units
+#pragma unroll
+        for (int q = 0; q < QB; ++q)
+#pragma unroll
+            for (int i = 0; i < DC; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[q][i][r] *= corr[q];
+    };
+    auto exp_step = [&](int q, int step, const floatx16 &s, unsigned (&pk)[2][4], float &lsum) {
+        const int r = step * 2;
+        const float p0 = fast_exp2(fmaf(s[r], c[q], -mc[q]));
+        const float p1 = fast_exp2(fmaf(s[r + 1], c[q], -mc[q]));
+        const unsigned w = pack_bf16_rne(p0, p1);
+        lsum += p0 + p1;      // plain adds: v_dot2c_f32_bf16 would serialise with the matrix cores
+        pk[r >> 3][(r & 7) >> 1] = w;
+    };
+    // O^T += V(u)^T P(u)^T, one k-step (16 keys) of one 32-dim chunk for both blocks
+    auto pv_step = [&](int u, int m, const unsigned (&pk)[QB][2][4]) {
+        const int st = m / DC, i = m % DC;
+        const bf16x8 vf = v_frag(u, i, st);
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const uint4 pw = make_uint4(pk[q][st][0], pk[q][st][1], pk[q][st][2], pk[q][st][3]);
+            acc[q][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pw), acc[q][i], 0, 0, 0);
+        }
+    };
+    // One pipeline step: scores and maxima of unit u, then the PV product of unit u-1 (matrix cores)
+    // interleaved with the exponentials of unit u (vector ALUs).  pk_prev / pk_next ping-pong.
+    auto step_unit = [&](int u, unsigned (&pk_prev)[QB][2][4], unsigned (&pk_next)[QB][2][4], auto masked_tag) {
+        floatx16 s[QB];
+        float corr[QB], lsum[QB] = {0.f, 0.f};
+        scores(u, s, masked_tag);
+        const bool changed = settle_max(s, corr);
+        constexpr int NPV = 2 * DC;                        // PV matrix steps (each feeds both blocks)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            constexpr int every = 16 / NPV;
+            if (e % every == 0) pv_step(u - 1, e / every, pk_prev);
+            exp_step(e & 1, e >> 1, s[e & 1], pk_next[e & 1], lsum[e & 1]);
+        }
+#pragma unroll
+        for (int q = 0; q < QB; ++q) l_run[q] = l_run[q] * corr[q] + lsum[q];
+        if (changed) rescale(corr);
+    };
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+
+    // ---- prologue: keys 0..31 (unit 0), window 0 (units 1, 2), V tile 0
+    constexpr int UNIT0_CH = 32 / KROWS;
+    load_k(0, UNIT0_CH);
+    load_v(0);
+    store_k(0, UNIT0_CH);
+    store_v(0);
+    if (32 < nkeys) {
+        load_k(32, KCH);
+        store_k(32, KCH);
+    }
+    __syncthreads();
+    unsigned pk_a[QB][2][4], pk_b[QB][2][4];
+    if (wave_active) {                                     // unit 0: scores, maxima, exponentials
+        floatx16 s[QB];
+        float corr[QB];
+        scores(0, s, T_{});
+        settle_max(s, corr);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) exp_step(e & 1, e >> 1, s[e & 1], pk_a[e & 1], l_run[e & 1]);
+    }
+    __syncthreads();   // unit 0's ring slot is rewritten at the end of stage 0: every wave must have read it
+
+    // ---- stage t = pipeline steps u = 2t+1, 2t+2: they read K units 2t+1, 2t+2 (window t) and V tile t.
+    // The main loop covers the stages whose steps are both before the last unit (which may be ragged).
+    const int nmain = nunits >= 3 ? (nunits - 1) / 2 - ((nunits - 1) % 2 == 0 ? 1 : 0) : 0;   // steps 1 .. 2*nmain
+    for (int t = 0; t < nmain; ++t) {
+        stage_pre(t);
+        if (wave_active) {
+            step_unit(2 * t + 1, pk_a, pk_b, F_{});
+            step_unit(2 * t + 2, pk_b, pk_a, F_{});
+        }
+        stage_post(t);
+    }
+    // ---- remaining steps: u = 2*nmain+1 .. nunits-1 (one or two), then the PV product of the last unit
+    {
+        const int u0 = 2 * nmain + 1;                      // pk_a holds unit u0 - 1
+        const int left = nunits - u0;                      // 0, 1 or 2
+        if (left == 2) {
+            stage_pre(nmain);
+            if (wave_active) {
+                step_unit(u0, pk_a, pk_b, F_{});
+                step_unit(u0 + 1, pk_b, pk_a, T_{});
+            }
+            stage_post(nmain);
+            if (wave_active) {
+#pragma unroll
+                for (int m = 0; m < 2 * DC; ++m) pv_step(u0 + 1, m, pk_a);
+            }
+        } else if (left == 1) {
+            if (wave_active) {
+                step_unit(u0, pk_a, pk_b, T_{});
+#pragma unroll
+                for (int m = 0; m < 2 * DC; ++m) pv_step(u0, m, pk_b);
+            }
+        } else {
+            if (wave_active) {
+#pragma unroll
+                for (int m = 0; m < 2 * DC; ++m) pv_step(u0 - 1, m, pk_a);
+            }
+        }
+    }
+
+    if (!wave_active) return;
+    // accumulator register r of chunk i holds dim 32*i + 8*(r/4) + 4*hh + (r%4) of the lane's query
+#pragma unroll
+    for (int q = 0; q < QB; ++q) {
+        const float l_tot = half_swap_sum(l_run[q]);
+        if (!row_ok[q]) continue;
+        const float inv = 1.0f / l_tot;
+        uint16_t *o = static_cast<uint16_t *>(a.O) + orow[q] * D;
+#pragma unroll
+        for (int i = 0; i < DC; ++i)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
+                                           pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
+                *reinterpret_cast<uint2 *>(o + i * 32 + q4 * 8 + hh * 4) = w;
+            }
     }
 }
 
@@ -351,18 +857,37 @@ void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int
 hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
 {
     AttnKernelArgs k;
+    const bool fp8 = a.qk_dtype == 2;
+    const bool blk = a.Nq != a.N || a.Kblk != nullptr || a.splits > 1;   // drafter form of the call
+#ifdef DDX_V3
+    if (!blk) {
+        // verifier form: 256 query rows per workgroup, 64 per wave
+        fill_kernel_args(a, k, 256, TK);
+        const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles)), block(kAttnThreads);
+        if (a.d == 128) return fp8 ? launch(attn_bidir64_kernel<128, true>, grid, block, stream, k)
+                                   : launch(attn_bidir64_kernel<128, false>, grid, block, stream, k);
+        return fp8 ? launch(attn_bidir64_kernel<64, true>, grid, block, stream, k)
+                   : launch(attn_bidir64_kernel<64, false>, grid, block, stream, k);
+    }
+#endif
     fill_kernel_args(a, k, kRowsPerWG, TK);
     const long blocks = (long)a.B * a.Hkv * k.row_tiles * k.splits;
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
-    const bool fp8 = a.qk_dtype == 2;
+    if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
-    if (a.d == 128) {
-        if (fp8) e = launch(attn_mfma_kernel<128, true>, grid, block, stream, k);
-        else     e = launch(attn_mfma_kernel<128, false>, grid, block, stream, k);
-    } else {
-        if (fp8) e = launch(attn_mfma_kernel<64, true>, grid, block, stream, k);
-        else     e = launch(attn_mfma_kernel<64, false>, grid, block, stream, k);
+#ifndef DDX_V3
+    if (!blk) {
+        if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)
+                                : launch(attn_mfma_kernel<128, false, false>, grid, block, stream, k);
+        else            e = fp8 ? launch(attn_mfma_kernel<64, true, false>, grid, block, stream, k)
+                                : launch(attn_mfma_kernel<64, false, false>, grid, block, stream, k);
+        return e;
     }
+#endif
+    if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, true>, grid, block, stream, k)
+                            : launch(attn_mfma_kernel<128, false, true>, grid, block, stream, k);
+    else            e = fp8 ? launch(attn_mfma_kernel<64, true, true>, grid, block, stream, k)
+                            : launch(attn_mfma_kernel<64, false, true>, grid, block, stream, k);
     if (e != hipSuccess || k.splits == 1) return e;
     AttnArgs c = a;
     c.splits = k.splits;
