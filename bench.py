@@ -27,6 +27,12 @@ METRIC = "verifier attn TFLOP/s (% MFMA peak); verify GB/s (% HBM); draft+verify
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 LLC_ROTATE_BYTES = 600e6      # rotate input sets until their total exceeds 2x the 256 MB last-level cache
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a 1 GiB copy (0.5 and 1.0); figures and commands: profiles/step_kernels_<workload>.md
+PROFILED_TRAFFIC_BYTES = {
+    "attention": {2: 16.98e6, 3: 268.6e6, 4: 134.4e6, 5: 503.5e6},
+    "verify": {2: 135.96e6, 3: 1039.4e6, 4: 261.3e6, 5: 2496.5e6},
+}
 
 
 def parse():
@@ -38,6 +44,9 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--parts", default="block,attention,verify",
                     help="comma list of the step's parts to run (profiling a single kernel); default: the whole step")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="after the timed steps, run one device-to-device copy of this many MiB (a kernel of known "
+                         "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -150,6 +159,14 @@ def main():
         assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
     t_block, t_attn, t_ver = (max(t, 1e-9) for t in (t_block, t_attn, t_ver))
 
+    if args.calib_copy_mb > 0:
+        src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+
     attn_flops = 4.0 * cfg.B * cfg.H * cfg.N * cfg.N * cfg.d
     attn_tflops = attn_flops / (t_attn * 1e-3) / 1e12
     ver_gbps = verify_bytes / (t_ver * 1e-3) / 1e9
@@ -172,10 +189,13 @@ def main():
         "block_attention_GBps": round(blk_gbps, 1),
         "roofline": {"kernel": "attn_mfma_kernel (dd_bidir_attention)", "bound": "mfma",
                      "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),
+                     "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
         "roofline_verify": {"kernel": "verify_partial_kernel + verify_finalize_kernel (dd_verify_remask)",
                             "bound": "hbm", "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                            "frac": round(ver_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+                            "frac": round(ver_gbps / PEAK_HBM_GBPS, 4),
+                            "traffic": PROFILED_TRAFFIC_BYTES["verify"].get(args.config),
                             "algorithmic_bytes": verify_bytes},
     }
 

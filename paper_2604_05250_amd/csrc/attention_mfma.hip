@@ -3,24 +3,29 @@
 // used by the verifier's full attention and, with a split key range, by the drafter's
 // block attention over the cached K/V (Sec. 2.3).
 //
-// Layout of the computation (one wave = 32 query rows, one workgroup = 4 waves):
-//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K tile (from LDS), B = Q (registers).
+// Layout of the computation (one wave = 32 query rows, one workgroup = 4 waves = 128 rows):
+//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K fragment (from LDS), B = Q (registers).
 //                 The 32x32 result puts one QUERY per lane column and 16 KEYS in the lane's
 //                 registers, so the softmax row reductions are in-register plus one
-//                 exchange between the two lane halves.
+//                 exchange between the two lane halves (v_permlane32_swap).
 //   O^T += V^T P^T  A = V^T (LDS, keys contiguous), B = P^T.  The accumulator layout of
 //                 S^T is exactly the B-operand layout of this product once the keys of a
 //                 16-key step are taken in the order the accumulator holds them, so the
 //                 probabilities never leave registers; V is transposed once per tile while
 //                 it is staged into LDS, in that same key order.
-//   The rescale factor of the online softmax is per query = per lane: a plain multiply.
-// K/V tiles are prefetched into registers while the previous tile is being multiplied, and
-// both LDS tiles are XOR-swizzled at 16-byte granularity so that the 16-byte operand reads
-// and the staging writes are bank-conflict free without padding.
+//   The rescale factor of the online softmax is per query = per lane: a plain multiply, and
+//   it is applied lazily (only when a unit's maximum exceeds the maximum in use by 2^8).
+// Pipeline: the softmax works on 32-key units.  While the exponentials of unit u run on the
+// vector ALUs, the matrix-core steps producing the scores of unit u+1 are issued in between
+// them; then the PV product of unit u follows.  K lives in a 128-row LDS ring whose 64-key
+// staging windows are offset by half a tile against the V tiles, so one barrier per 64 keys
+// suffices; the next window / tile is prefetched into registers during the current one.
+// Both LDS arrays are XOR-swizzled at 16-byte granularity: operand reads and staging writes
+// are bank-conflict free without padding.  Workgroups are renumbered so that those sharing
+// one (batch, kv head) run on the same XCD and hit its L2.
+// Row sums use plain adds: v_dot2c_f32_bf16 was measured to serialise with the MFMA pipe.
 #include "attention_common.h"
 #include "dd_internal.h"
-
-#include <type_traits>
 
 namespace dd {
 namespace {
@@ -72,14 +77,6 @@ __device__ __forceinline__ float half_swap_sum(float x)
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r.x) + __uint_as_float(r.y);
-}
-
-// acc += p.lo + p.hi for a packed pair of bf16 (v_dot2c_f32_bf16 against (1, 1))
-__device__ __forceinline__ float add_bf16_pair(unsigned packed, float acc)
-{
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3F803F80u);
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, packed), ones, acc, false);
 }
 
 // The running maximum used for exponentiation is raised only when a tile's maximum exceeds it
@@ -179,16 +176,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // window w = keys [64w+32, 64w+96) relative to the range start.  A ring of 128 rows then always
     // holds the two 32-key units the current stage multiplies while the next window is written.
     const int nkeys = k_end - k_begin;
-    auto load_k = [&](int j0, int nch) {               // rows j0 + k_row0 + i*KROWS, i < nch
+    auto load_k = [&](uint4 (&dst)[KCH], int j0, int nch) {   // rows j0 + k_row0 + i*KROWS, i < nch
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
             if (i < nch) {
                 const uint8_t *p = k_src(k_begin + j0 + k_row0 + i * KROWS);
                 if (FP8) {
                     const uint2 r = *reinterpret_cast<const uint2 *>(p);
-                    kreg[i] = make_uint4(r.x, r.y, 0, 0);
+                    dst[i] = make_uint4(r.x, r.y, 0, 0);
                 } else {
-                    kreg[i] = *reinterpret_cast<const uint4 *>(p);
+                    dst[i] = *reinterpret_cast<const uint4 *>(p);
                 }
             }
         }
@@ -200,12 +197,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             for (int e = 0; e < 4; ++e) vreg[e] = *reinterpret_cast<const uint4 *>(v_src(k0 + vt_key0 + e));
         }
     };
-    auto store_k = [&](int j0, int nch) {
+    auto store_k = [&](const uint4 (&src)[KCH], int j0, int nch) {
 #pragma unroll
         for (int i = 0; i < KCH; ++i) {
             if (i < nch) {
                 const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
-                uint4 w = kreg[i];
+                uint4 w = src[i];
                 if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
                 Ks[row * CH + (k_ch ^ (row & 7))] = w;
             }
@@ -286,12 +283,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // probabilities of scores (2*step, 2*step+1) of a unit, packed to bf16 in B-operand order
     auto exp_step = [&](int step, const floatx16 &s, unsigned (&pk)[2][4]) {
         const int r = step * 2;
-#ifdef DDX_NOEXP
-        const float p0 = s[r], p1 = s[r + 1];
-#else
         const float p0 = fast_exp2(fmaf(s[r], c, -mc));
         const float p1 = fast_exp2(fmaf(s[r + 1], c, -mc));
-#endif
         const unsigned w = pack_bf16_rne(p0, p1);
         l_run += p0 + p1;     // plain adds: v_dot2c_f32_bf16 would serialise with the matrix cores
         pk[r >> 3][(r & 7) >> 1] = w;
@@ -320,9 +313,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // LDS fragment m of a unit's 16 matrix-core slots: slots 0..KS-1 are the K fragments of unit u+1,
     // the following 2*DC are the V fragments of unit u (k-step major, 32-dim chunk minor)
     auto frag = [&](int u, int m) -> uint4 {
-#ifdef DDX_NOLDSREAD
-        return make_uint4(u + m, l32, hh, 0x3f803f80u);
-#endif
         if (m < KS) {
             const int krow = ((u + 1) & 3) * 32 + l32;
             return Ks[krow * CH + ((2 * m + hh) ^ (krow & 7))];
@@ -334,9 +324,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     };
     auto unit = [&](int u, floatx16 &s_cur, bool have_next, floatx16 &s_nxt) {
         unsigned pk[2][4];
-#ifndef DDX_NOMAX
         update_max(s_cur);
-#endif
         if (have_next) {
             constexpr int NSLOT = KS + 2 * DC;              // matrix-core slots of the unit
             constexpr int PD = 3;                           // fragments requested this many slots ahead
@@ -354,11 +342,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
 #pragma unroll
                         for (int r = 0; r < 16; ++r) cin[r] = 0.f;
                     }
-#ifndef DDX_NOQK
                     s_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fq[m]), qf[m], cin, 0, 0, 0);
-#else
-                    s_nxt[m] += __uint_as_float(fq[m].x);
-#endif
                 }
                 exp_step(step, s_cur, pk);
             }
@@ -367,12 +351,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
                 const int m = KS + j, st = j / DC, i = j % DC;
                 if (m + PD < NSLOT) fq[m + PD] = frag(u, m + PD);
                 const uint4 pw = make_uint4(pk[st][0], pk[st][1], pk[st][2], pk[st][3]);
-#ifndef DDX_NOPV
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fq[m]),
                                                                  __builtin_bit_cast(bf16x8, pw), acc[i], 0, 0, 0);
-#else
-                acc[i][j] += __uint_as_float(fq[m].x ^ pw.x ^ pw.y ^ pw.z ^ pw.w);
-#endif
             }
         } else {
 #pragma unroll
@@ -382,13 +362,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     };
 
     constexpr int UNIT0_CH = 32 / KROWS;               // chunks per thread to stage keys 0..31
-    load_k(0, UNIT0_CH);
-    load_v(0);
-    store_k(0, UNIT0_CH);
-    store_v(0);
-    if (32 < nkeys) {
-        load_k(32, KCH);                               // window 0: units 1 and 2
-        store_k(32, KCH);
+    {
+        // all prologue loads are in flight together: keys 0..31, window 0 (units 1 and 2), V tile 0
+        uint4 k0[KCH];
+        load_k(k0, 0, UNIT0_CH);
+        if (32 < nkeys) load_k(kreg, 32, KCH);
+        load_v(0);
+        store_k(k0, 0, UNIT0_CH);
+        if (32 < nkeys) store_k(kreg, 32, KCH);
+        store_v(0);
     }
     __syncthreads();
     floatx16 s_a, s_b;
@@ -400,21 +382,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // Stage t: on entry units 2t .. 2t+2 of K and tile t of V are in LDS, s_a holds the scores of unit 2t.
     for (int t = 0; t + 1 < ntiles; ++t) {
         const bool more_k = TK * (t + 1) + 32 < nkeys;  // window t+1 = units 2t+3, 2t+4
-#ifndef DDX_NOSTAGE
-        if (more_k) load_k(TK * (t + 1) + 32, KCH);
+        if (more_k) load_k(kreg, TK * (t + 1) + 32, KCH);
         load_v(t + 1);
-#endif
         if (wave_active) {
             unit(2 * t, s_a, true, s_b);
             unit(2 * t + 1, s_b, true, s_a);
         }
-#ifndef DDX_NOSTAGE
-        if (more_k) store_k(TK * (t + 1) + 32, KCH);   // overwrites units 2t-1, 2t: read one stage ago
+        if (more_k) store_k(kreg, TK * (t + 1) + 32, KCH);   // overwrites units 2t-1, 2t: read one stage ago
         store_v((t + 1) & 1);                          // overwrites V(t-1): read one stage ago
-#endif
-#ifndef DDX_NOBARRIER
         __syncthreads();
-#endif
     }
     if (wave_active) {                                  // last tile: nothing to prefetch, possibly ragged
         const int t = ntiles - 1;
@@ -457,346 +433,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             ml[0] = mc;
             ml[1] = l_tot;
         }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Verifier attention, wide-wave form: one wave owns 64 query rows (two 32-row blocks A and B) and is
-// alone on its SIMD (up to 512 registers), one workgroup = 4 waves = 256 query rows of one
-// (batch, kv head).  Every K fragment and every V fragment read from LDS now feeds two matrix-core
-// instructions (one per block), which halves the LDS bytes per FLOP: with 32 rows per wave each
-// MFMA needs its own 1 KB LDS read and the 128 B/clk LDS port saturates near 3/4 of the MFMA rate.
-// With a single wave per SIMD there is no other wave to overlap with, so the instruction stream
-// itself alternates matrix-core and vector work:
-//     phase 1   S(u+1) = K(u+1) Q^T   (MFMA)   interleaved with   P(u) = 2^(S(u) c - m)   (VALU)
-//     phase 2   O^T   += V(u)^T P(u)^T (MFMA)   interleaved with   row maxima of S(u+1)     (VALU)
-// for 32-key units u; the running maximum is raised (and the accumulators rescaled) in a rare
-// branch between units.
-template <int D, bool FP8>
-__global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void attn_bidir64_kernel(const AttnKernelArgs a)
-{
-    constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
-    constexpr int KCH = TK * CH / kAttnThreads;      // K chunks staged per thread
-    constexpr int KROWS = kAttnThreads / CH;         // K rows covered by one pass of the workgroup
-    constexpr int VTASKS = (TK / 8) * CH * 2;        // V transpose tasks per tile (4 keys x 8 dims)
-    constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
-    constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
-    constexpr int KELEM = FP8 ? 1 : 2;               // bytes per K element in memory
-    constexpr int QB = 2;                            // 32-row query blocks per wave
-    constexpr int kRowsWave = 32 * QB, kRowsWG = 4 * kRowsWave;
-
-    __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
-    __shared__ uint4 Vt[2][D * (TK / 8)];            // [dim][keygroup ^ swz(dim)], 8 keys per 16 bytes
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l32 = lane & 31, hh = lane >> 5;
-
-    // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD (own L2 each)
-    int bid = blockIdx.x;
-    {
-        const int total = gridDim.x, per = total >> 3, rem = total & 7;
-        const int xcd = bid & 7, slot = bid >> 3;
-        bid = xcd * per + min(xcd, rem) + slot;
-    }
-    const int rt = bid % a.row_tiles; bid /= a.row_tiles;
-    const int kvh = bid % a.Hkv;
-    const int b = bid / a.Hkv;
-    const int rows_total = a.group * a.Nq;
-    const bool wave_active = rt * kRowsWG + wave * kRowsWave < rows_total;
-
-    bool row_ok[QB];
-    size_t orow[QB];
-    float c[QB];                                     // scores are exponentiated as 2^(s*c)
-    bf16x8 qf[QB][KS];                               // B operand of S^T = K Q^T
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        const int v = rt * kRowsWG + wave * kRowsWave + q * 32 + l32;
-        row_ok[q] = v < rows_total;
-        const int vv = row_ok[q] ? v : rows_total - 1;
-        const int head = kvh * a.group + vv / a.Nq;
-        orow[q] = ((size_t)b * a.H + head) * (size_t)a.Nq + vv % a.Nq;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const size_t off = orow[q] * D + ks * 16 + hh * 8;
-            uint4 w;
-            if (FP8) w = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(a.Q) + off));
-            else w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.Q) + off);
-            qf[q][ks] = __builtin_bit_cast(bf16x8, w);
-        }
-        c[q] = a.scale_log2;
-        if (a.q_scale) c[q] *= a.q_scale[b * a.H + head];
-        if (a.k_scale) c[q] *= a.k_scale[b * a.Hkv + kvh];
-    }
-
-    const int nkeys = a.N;
-    const int ntiles = (nkeys + TK - 1) / TK;
-    const int nunits = (nkeys + 31) / 32;
-    const size_t kv_head = (size_t)b * a.Hkv + kvh;
-
-    // ---- staging: global -> registers -> LDS (K in half-tile-offset windows, V per tile)
-    uint4 kreg[KCH];
-    uint4 vreg[4];
-    const int k_row0 = tid / CH, k_ch = tid % CH;
-    const int vt_dchunk = tid % CH, vt_e4 = (tid / CH) & 1, vt_g = tid / (2 * CH);
-    const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
-    const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
-    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)(D * 2) + vt_dchunk * 16;
-    auto load_k = [&](int j0, int nch) {               // rows j0 + k_row0 + i*KROWS, clamped into the sequence
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            if (i < nch) {
-                const uint8_t *p = k_base + (size_t)min(j0 + k_row0 + i * KROWS, nkeys - 1) * (D * KELEM);
-                if (FP8) {
-                    const uint2 r = *reinterpret_cast<const uint2 *>(p);
-                    kreg[i] = make_uint4(r.x, r.y, 0, 0);
-                } else {
-                    kreg[i] = *reinterpret_cast<const uint4 *>(p);
-                }
-            }
-        }
-    };
-    auto store_k = [&](int j0, int nch) {
-#pragma unroll
-        for (int i = 0; i < KCH; ++i) {
-            if (i < nch) {
-                const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
-                uint4 w = kreg[i];
-                if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
-                Ks[row * CH + (k_ch ^ (row & 7))] = w;
-            }
-        }
-    };
-    auto load_v = [&](int t) {
-        if (tid < VTASKS) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                vreg[e] = *reinterpret_cast<const uint4 *>(v_base + (size_t)min(t * TK + vt_key0 + e, nkeys - 1) * (D * 2));
-        }
-    };
-    auto store_v = [&](int buf) {
-        if (tid < VTASKS) {
-            const unsigned r0[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
-            const unsigned r1[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
-            const unsigned r2[4] = {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w};
-            const unsigned r3[4] = {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w};
-            uint2 *vt2 = reinterpret_cast<uint2 *>(Vt[buf]);
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint2 even = make_uint2((r0[p] & 0xFFFFu) | (r1[p] << 16), (r2[p] & 0xFFFFu) | (r3[p] << 16));
-                const uint2 odd = make_uint2((r0[p] >> 16) | (r1[p] & 0xFFFF0000u), (r2[p] >> 16) | (r3[p] & 0xFFFF0000u));
-                const int d0 = vt_dchunk * 8 + 2 * p, d1 = d0 + 1;
-                vt2[(d0 * (TK / 8) + (vt_g ^ ((d0 ^ (d0 >> 3)) & 7))) * 2 + vt_e4] = even;
-                vt2[(d1 * (TK / 8) + (vt_g ^ ((d1 ^ (d1 >> 3)) & 7))) * 2 + vt_e4] = odd;
-            }
-        }
-    };
-    // loads for the tile after stage t's (issued at the stage's first unit), stores + barrier at its second
-    auto stage_pre = [&](int t) {
-        if (t + 1 < ntiles) {
-            if (TK * (t + 1) + 32 < nkeys) load_k(TK * (t + 1) + 32, KCH);
-            load_v(t + 1);
-        }
-    };
-    auto stage_post = [&](int t) {
-        if (t + 1 < ntiles) {
-            if (TK * (t + 1) + 32 < nkeys) store_k(TK * (t + 1) + 32, KCH);
-            store_v((t + 1) & 1);
-        }
-        __syncthreads();
-    };
-
-    // ---- per-lane state of the two query blocks
-    floatx16 acc[QB][DC];
-#pragma unroll
-    for (int q = 0; q < QB; ++q)
-#pragma unroll
-        for (int i = 0; i < DC; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[q][i][r] = 0.f;
-    float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
-    float l_run[QB] = {0.f, 0.f};                    // this lane half's share of the running sums
-
-    // accumulator start of a score block: 0, or -inf for the keys of unit u at or past the end
-    auto score_init = [&](int u) {
-        floatx16 z;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) z[r] = (32 * u + 8 * (r >> 2) + 4 * hh + (r & 3) >= nkeys) ? -INFINITY : 0.f;
-        return z;
-    };
-    auto k_frag = [&](int u, int ks) {
-        const int krow = (u & 3) * 32 + l32;
-        return __builtin_bit_cast(bf16x8, Ks[krow * CH + ((2 * ks + hh) ^ (krow & 7))]);
-    };
-    auto v_frag = [&](int u, int i, int st) {
-        const int drow = i * 32 + l32;
-        const int g = (u & 1) * 4 + st * 2 + hh;
-        return __builtin_bit_cast(bf16x8, Vt[(u >> 1) & 1][drow * (TK / 8) + (g ^ ((drow ^ (drow >> 3)) & 7))]);
-    };
-    // S^T = K Q^T of unit u for both blocks: every K fragment feeds two matrix-core instructions
-    auto scores = [&](int u, floatx16 (&s)[QB], auto masked_tag) {
-        constexpr bool MASKED = decltype(masked_tag)::value;
-        floatx16 z;
-        if (MASKED) z = score_init(u);
-        else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) z[r] = 0.f;
-        }
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 kf = k_frag(u, ks);
-#pragma unroll
-            for (int q = 0; q < QB; ++q)
-                s[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[q][ks], ks == 0 ? z : s[q], 0, 0, 0);
-        }
-    };
-    // Row maxima of a unit decide, without a branch, whether the maxima in use are raised; returns the
-    // factors 2^(old - new) (1 when nothing changes) that the running state must be multiplied by.
-    auto settle_max = [&](const floatx16 (&s)[QB], float (&corr)[QB]) -> bool {
-        float tm[QB];
-        bool need = false;
-#pragma unroll
-        for (int q = 0; q < QB; ++q) {
-            float t = s[q][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) t = fmaxf(t, s[q][r]);
-            tm[q] = half_swap_max(t) * c[q];
-            need = need || (tm[q] > mc[q] + kRescaleSlack);
-        }
-        const bool any_need = __any(need);                 // wave-uniform
-#pragma unroll
-        for (int q = 0; q < QB; ++q) {
-            const float mn = any_need ? fmaxf(mc[q], tm[q]) : mc[q];
-            corr[q] = fast_exp2(mc[q] - mn);                // first unit: 2^(-inf) = 0
-            mc[q] = mn;
-        }
-        return any_need;
-    };
-    auto rescale = [&](const float (&corr)[QB]) {          // rare: the accumulators change units
-#pragma unroll
-        for (int q = 0; q < QB; ++q)
-#pragma unroll
-            for (int i = 0; i < DC; ++i)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[q][i][r] *= corr[q];
-    };
-    auto exp_step = [&](int q, int step, const floatx16 &s, unsigned (&pk)[2][4], float &lsum) {
-        const int r = step * 2;
-        const float p0 = fast_exp2(fmaf(s[r], c[q], -mc[q]));
-        const float p1 = fast_exp2(fmaf(s[r + 1], c[q], -mc[q]));
-        const unsigned w = pack_bf16_rne(p0, p1);
-        lsum += p0 + p1;      // plain adds: v_dot2c_f32_bf16 would serialise with the matrix cores
-        pk[r >> 3][(r & 7) >> 1] = w;
-    };
-    // O^T += V(u)^T P(u)^T, one k-step (16 keys) of one 32-dim chunk for both blocks
-    auto pv_step = [&](int u, int m, const unsigned (&pk)[QB][2][4]) {
-        const int st = m / DC, i = m % DC;
-        const bf16x8 vf = v_frag(u, i, st);
-#pragma unroll
-        for (int q = 0; q < QB; ++q) {
-            const uint4 pw = make_uint4(pk[q][st][0], pk[q][st][1], pk[q][st][2], pk[q][st][3]);
-            acc[q][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, __builtin_bit_cast(bf16x8, pw), acc[q][i], 0, 0, 0);
-        }
-    };
-    // One pipeline step: scores and maxima of unit u, then the PV product of unit u-1 (matrix cores)
-    // interleaved with the exponentials of unit u (vector ALUs).  pk_prev / pk_next ping-pong.
-    auto step_unit = [&](int u, unsigned (&pk_prev)[QB][2][4], unsigned (&pk_next)[QB][2][4], auto masked_tag) {
-        floatx16 s[QB];
-        float corr[QB], lsum[QB] = {0.f, 0.f};
-        scores(u, s, masked_tag);
-        const bool changed = settle_max(s, corr);
-        constexpr int NPV = 2 * DC;                        // PV matrix steps (each feeds both blocks)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            constexpr int every = 16 / NPV;
-            if (e % every == 0) pv_step(u - 1, e / every, pk_prev);
-            exp_step(e & 1, e >> 1, s[e & 1], pk_next[e & 1], lsum[e & 1]);
-        }
-#pragma unroll
-        for (int q = 0; q < QB; ++q) l_run[q] = l_run[q] * corr[q] + lsum[q];
-        if (changed) rescale(corr);
-    };
-    using T_ = std::true_type;
-    using F_ = std::false_type;
-
-    // ---- prologue: keys 0..31 (unit 0), window 0 (units 1, 2), V tile 0
-    constexpr int UNIT0_CH = 32 / KROWS;
-    load_k(0, UNIT0_CH);
-    load_v(0);
-    store_k(0, UNIT0_CH);
-    store_v(0);
-    if (32 < nkeys) {
-        load_k(32, KCH);
-        store_k(32, KCH);
-    }
-    __syncthreads();
-    unsigned pk_a[QB][2][4], pk_b[QB][2][4];
-    if (wave_active) {                                     // unit 0: scores, maxima, exponentials
-        floatx16 s[QB];
-        float corr[QB];
-        scores(0, s, T_{});
-        settle_max(s, corr);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) exp_step(e & 1, e >> 1, s[e & 1], pk_a[e & 1], l_run[e & 1]);
-    }
-    __syncthreads();   // unit 0's ring slot is rewritten at the end of stage 0: every wave must have read it
-
-    // ---- stage t = pipeline steps u = 2t+1, 2t+2: they read K units 2t+1, 2t+2 (window t) and V tile t.
-    // The main loop covers the stages whose steps are both before the last unit (which may be ragged).
-    const int nmain = nunits >= 3 ? (nunits - 1) / 2 - ((nunits - 1) % 2 == 0 ? 1 : 0) : 0;   // steps 1 .. 2*nmain
-    for (int t = 0; t < nmain; ++t) {
-        stage_pre(t);
-        if (wave_active) {
-            step_unit(2 * t + 1, pk_a, pk_b, F_{});
-            step_unit(2 * t + 2, pk_b, pk_a, F_{});
-        }
-        stage_post(t);
-    }
-    // ---- remaining steps: u = 2*nmain+1 .. nunits-1 (one or two), then the PV product of the last unit
-    {
-        const int u0 = 2 * nmain + 1;                      // pk_a holds unit u0 - 1
-        const int left = nunits - u0;                      // 0, 1 or 2
-        if (left == 2) {
-            stage_pre(nmain);
-            if (wave_active) {
-                step_unit(u0, pk_a, pk_b, F_{});
-                step_unit(u0 + 1, pk_b, pk_a, T_{});
-            }
-            stage_post(nmain);
-            if (wave_active) {
-#pragma unroll
-                for (int m = 0; m < 2 * DC; ++m) pv_step(u0 + 1, m, pk_a);
-            }
-        } else if (left == 1) {
-            if (wave_active) {
-                step_unit(u0, pk_a, pk_b, T_{});
-#pragma unroll
-                for (int m = 0; m < 2 * DC; ++m) pv_step(u0, m, pk_b);
-            }
-        } else {
-            if (wave_active) {
-#pragma unroll
-                for (int m = 0; m < 2 * DC; ++m) pv_step(u0 - 1, m, pk_a);
-            }
-        }
-    }
-
-    if (!wave_active) return;
-    // accumulator register r of chunk i holds dim 32*i + 8*(r/4) + 4*hh + (r%4) of the lane's query
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        const float l_tot = half_swap_sum(l_run[q]);
-        if (!row_ok[q]) continue;
-        const float inv = 1.0f / l_tot;
-        uint16_t *o = static_cast<uint16_t *>(a.O) + orow[q] * D;
-#pragma unroll
-        for (int i = 0; i < DC; ++i)
-#pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
-                                           pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
-                *reinterpret_cast<uint2 *>(o + i * 32 + q4 * 8 + hh * 4) = w;
-            }
     }
 }
 
@@ -859,23 +495,11 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     AttnKernelArgs k;
     const bool fp8 = a.qk_dtype == 2;
     const bool blk = a.Nq != a.N || a.Kblk != nullptr || a.splits > 1;   // drafter form of the call
-#ifdef DDX_V3
-    if (!blk) {
-        // verifier form: 256 query rows per workgroup, 64 per wave
-        fill_kernel_args(a, k, 256, TK);
-        const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles)), block(kAttnThreads);
-        if (a.d == 128) return fp8 ? launch(attn_bidir64_kernel<128, true>, grid, block, stream, k)
-                                   : launch(attn_bidir64_kernel<128, false>, grid, block, stream, k);
-        return fp8 ? launch(attn_bidir64_kernel<64, true>, grid, block, stream, k)
-                   : launch(attn_bidir64_kernel<64, false>, grid, block, stream, k);
-    }
-#endif
     fill_kernel_args(a, k, kRowsPerWG, TK);
     const long blocks = (long)a.B * a.Hkv * k.row_tiles * k.splits;
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
-#ifndef DDX_V3
     if (!blk) {
         if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)
                                 : launch(attn_mfma_kernel<128, false, false>, grid, block, stream, k);
@@ -883,7 +507,6 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
                                 : launch(attn_mfma_kernel<64, false, false>, grid, block, stream, k);
         return e;
     }
-#endif
     if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, true>, grid, block, stream, k)
                             : launch(attn_mfma_kernel<128, false, true>, grid, block, stream, k);
     else            e = fp8 ? launch(attn_mfma_kernel<64, true, true>, grid, block, stream, k)
