@@ -21,8 +21,10 @@ namespace dd {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
-constexpr int kUnroll = 4;
+#ifndef DD_VERIFY_UNROLL
+#define DD_VERIFY_UNROLL 4
+#endif
+constexpr int kUnroll = DD_VERIFY_UNROLL;   // independent 16-byte loads per matrix in flight per lane
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kNegInf = -INFINITY;
 // The drafter reference is raised when a logit exceeds it by more than this.  Zero keeps it
@@ -184,45 +186,37 @@ __device__ __forceinline__ WaveState merge(const WaveState &x, const WaveState &
     return r;
 }
 
-// grid: P * S workgroups; workgroup (row, split) reduces vectors [split*chunk, (split+1)*chunk) of its row
-template <bool BF16, bool KL>
-__global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *__restrict__ logits_d,
-                                                                  const uint4 *__restrict__ logits_v,
-                                                                  int nvec, int S, int chunk,
-                                                                  VerifyPartial *__restrict__ part)
+// Reduce vectors [vbeg, vend) of one row with a workgroup of THREADS lanes.  Returns true on thread 0,
+// whose `out` then holds the merged state of the range (lanes -> waves -> workgroup, fixed order).
+template <bool BF16, bool KL, int THREADS>
+__device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const uint4 *__restrict__ pd,
+                                             int vbeg, int vend, WaveState &out)
 {
     constexpr int E = VecTraits<BF16>::kElems;
-    const int row = blockIdx.x / S;
-    const int split = blockIdx.x - row * S;
+    constexpr int NW = THREADS / 64;
     const int tid = threadIdx.x;
-    const size_t rbase = (size_t)row * (size_t)nvec;
-    const uint4 *pv = logits_v + rbase;
-    const uint4 *pd = KL ? logits_d + rbase : nullptr;
-    const int vbeg = split * chunk;
-    const int vend = min(nvec, vbeg + chunk);
-
     LaneState st;
     int base = vbeg;
     // full iterations: kUnroll independent 16-byte loads per matrix in flight per lane
-    for (; base + kThreads * kUnroll <= vend; base += kThreads * kUnroll) {
+    for (; base + THREADS * kUnroll <= vend; base += THREADS * kUnroll) {
         uint4 rv[kUnroll], rd[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int idx = base + u * kThreads + tid;
+            const int idx = base + u * THREADS + tid;
             rv[u] = stream_load16(pv + idx);
             if (KL) rd[u] = stream_load16(pd + idx);
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            consume<BF16, KL>(rv[u], rd[u], true, (base + u * kThreads + tid) * E, st);
+            consume<BF16, KL>(rv[u], rd[u], true, (base + u * THREADS + tid) * E, st);
     }
-    // ragged remainder of the chunk
+    // ragged remainder of the range
     if (base < vend) {
         uint4 rv[kUnroll], rd[kUnroll];
         bool ok[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int idx = base + u * kThreads + tid;
+            const int idx = base + u * THREADS + tid;
             ok[u] = idx < vend;
             rv[u] = make_uint4(0, 0, 0, 0);
             rd[u] = make_uint4(0, 0, 0, 0);
@@ -233,11 +227,11 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *_
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            consume<BF16, KL>(rv[u], rd[u], ok[u], (base + u * kThreads + tid) * E, st);
+            consume<BF16, KL>(rv[u], rd[u], ok[u], (base + u * THREADS + tid) * E, st);
     }
 
     // lanes -> wave (references are already wave-uniform), waves -> workgroup
-    __shared__ WaveState ws[kWaves];
+    __shared__ WaveState ws[NW];
     WaveState w;
     w.ref_d = st.ref_d;
     w.s_d = wave_sum(st.s_d);
@@ -247,10 +241,28 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *_
     w.idx = st.idx_v;
     if ((tid & 63) == 0) ws[tid >> 6] = w;
     __syncthreads();
-    if (tid == 0) {
-        WaveState r = ws[0];
+    if (tid != 0) return false;
+    WaveState r = ws[0];
 #pragma unroll
-        for (int i = 1; i < kWaves; ++i) r = merge(r, ws[i]);
+    for (int i = 1; i < NW; ++i) r = merge(r, ws[i]);
+    out = r;
+    return true;
+}
+
+// grid: P * S workgroups; workgroup (row, split) reduces vectors [split*chunk, (split+1)*chunk) of its row
+template <bool BF16, bool KL>
+__global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *__restrict__ logits_d,
+                                                                  const uint4 *__restrict__ logits_v,
+                                                                  int nvec, int S, int chunk,
+                                                                  VerifyPartial *__restrict__ part)
+{
+    const int row = blockIdx.x / S;
+    const int split = blockIdx.x - row * S;
+    const size_t rbase = (size_t)row * (size_t)nvec;
+    const int vbeg = split * chunk;
+    const int vend = min(nvec, vbeg + chunk);
+    WaveState r;
+    if (reduce_range<BF16, KL, kThreads>(logits_v + rbase, KL ? logits_d + rbase : nullptr, vbeg, vend, r)) {
         VerifyPartial p;
         p.ref_d = r.ref_d; p.s_d = r.s_d; p.a = r.a;
         p.best_v = r.best_v; p.s_v = r.s_v; p.idx = r.idx;
@@ -279,6 +291,28 @@ __device__ __forceinline__ unsigned philox_word0(uint64_t seed, uint64_t row)
 __device__ __forceinline__ double row_uniform(uint64_t seed, uint64_t row)
 {
     return (double)(philox_word0(seed, row) >> 8) * (1.0 / 16777216.0);
+}
+
+// Finish one row from its merged sums (fp64): score, token, remask rule.
+//   KL = E_D[l_D - l_V] - lse_D + lse_V = a/s_D - (m_D + ln s_D) + (m_V + ln s_V);   c_V = e^{max - lse_V} = 1/s_V
+__device__ __forceinline__ void finish_row(int row, double md, double sd, double a, double mv, double sv, int idx,
+                                           const uint8_t *__restrict__ mask, int mode, float threshold, uint64_t seed,
+                                           int kl_mode, uint8_t *__restrict__ out_mask,
+                                           int32_t *__restrict__ out_tokens, float *__restrict__ out_scores)
+{
+    const double score = kl_mode ? a / sd - (md + log(sd)) + (mv + log(sv)) : 1.0 / sv;
+    const float s32 = (float)score;
+    out_scores[row] = s32;
+    out_tokens[row] = idx;
+    const uint8_t m = mask[row];
+    bool remask = false;
+    switch (mode) {
+    case 1: remask = s32 > threshold; break;                                // KL threshold
+    case 2: remask = s32 < threshold; break;                                // confidence threshold
+    case 4: remask = row_uniform(seed, (uint64_t)row) < 1.0 - (double)s32; break;
+    default: break;                                                         // trust; KL-prob decided later
+    }
+    out_mask[row] = (uint8_t)((m != 0) || remask);
 }
 
 // one thread per row: merge the S partials in fp64, finish the scores, apply the rule
@@ -311,23 +345,26 @@ __global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartia
             a += (double)p[s].a * c;
         }
     }
-    double score;
-    if (kl_mode)
-        score = a / sd - ((double)md + log(sd)) + ((double)mv + log(sv));   // E_D[l_D - l_V] - lse_D + lse_V
-    else
-        score = 1.0 / sv;                                                   // e^{max - lse_V}
-    const float s32 = (float)score;
-    out_scores[row] = s32;
-    out_tokens[row] = idx;
-    const uint8_t m = mask[row];
-    bool remask = false;
-    switch (mode) {
-    case 1: remask = s32 > threshold; break;                                // KL threshold
-    case 2: remask = s32 < threshold; break;                                // confidence threshold
-    case 4: remask = row_uniform(seed, (uint64_t)row) < 1.0 - (double)s32; break;
-    default: break;                                                         // trust; KL-prob decided later
-    }
-    out_mask[row] = (uint8_t)((m != 0) || remask);
+    finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores);
+}
+
+// One workgroup per row: stream the whole row and finish it in the same kernel (no partial states,
+// no second launch).  Used whenever there are enough rows to fill the chip with such workgroups.
+template <bool BF16, bool KL, int THREADS>
+__global__ __launch_bounds__(THREADS) void verify_row_kernel(const uint4 *__restrict__ logits_d,
+                                                             const uint4 *__restrict__ logits_v, int nvec,
+                                                             const uint8_t *__restrict__ mask, int mode,
+                                                             float threshold, uint64_t seed,
+                                                             uint8_t *__restrict__ out_mask,
+                                                             int32_t *__restrict__ out_tokens,
+                                                             float *__restrict__ out_scores)
+{
+    const int row = blockIdx.x;
+    const size_t rbase = (size_t)row * (size_t)nvec;
+    WaveState r;
+    if (reduce_range<BF16, KL, THREADS>(logits_v + rbase, KL ? logits_d + rbase : nullptr, 0, nvec, r))
+        finish_row(row, (double)r.ref_d, (double)r.s_d, (double)r.a, (double)r.best_v, (double)r.s_v, r.idx,
+                   mask, mode, threshold, seed, KL ? 1 : 0, out_mask, out_tokens, out_scores);
 }
 
 // Eq. 6: one workgroup per sequence sums the divergences of its eligible rows, then draws
@@ -368,9 +405,20 @@ int env_int(const char *name, int dflt)
 
 }  // namespace
 
+// Rows are handled by one workgroup each (fused finish) once there are enough of them to occupy the
+// chip; the workgroup grows as the row count shrinks so that the bytes in flight stay about constant.
+int verify_fused_threads(int P)
+{
+    static const int min_rows = env_int("DD_TUNE_VERIFY_FUSED_MIN_ROWS", 192);
+    if (P < min_rows) return 0;          // too few rows: split them over several workgroups instead
+    static const int forced = env_int("DD_TUNE_VERIFY_THREADS", 0);
+    if (forced == 256 || forced == 512) return forced;
+    return P >= 2048 ? 256 : 512;        // measured: 512 lanes per row stream best for 256..1024 rows
+}
+
 int verify_splits(int P, int V, int elem_bytes)
 {
-    if (P <= 0) return 1;
+    if (P <= 0 || verify_fused_threads(P) != 0) return 1;
     const long nvec = (long)V * elem_bytes / 16;
     static const int forced = env_int("DD_TUNE_VERIFY_SPLITS", 0);
     static const int target = env_int("DD_TUNE_VERIFY_TARGET_WGS", 2048);
@@ -384,8 +432,20 @@ int verify_splits(int P, int V, int elem_bytes)
 
 size_t verify_workspace_bytes(int P, int V, int elem_bytes)
 {
-    if (P <= 0) return 0;
+    if (P <= 0 || verify_fused_threads(P) != 0) return 0;
     return (size_t)P * (size_t)verify_splits(P, V, elem_bytes) * sizeof(VerifyPartial);
+}
+
+template <bool BF16, bool KL>
+static hipError_t launch_row_kernel(int threads, dim3 grid, hipStream_t stream, const uint4 *ld, const uint4 *lv,
+                                    int nvec, const uint8_t *mask, int mode, float threshold, uint64_t seed,
+                                    uint8_t *out_mask, int32_t *out_tokens, float *out_scores)
+{
+    if (threads == 256)
+        return launch(verify_row_kernel<BF16, KL, 256>, grid, dim3(256), stream, ld, lv, nvec, mask, mode,
+                      threshold, seed, out_mask, out_tokens, out_scores);
+    return launch(verify_row_kernel<BF16, KL, 512>, grid, dim3(512), stream, ld, lv, nvec, mask, mode,
+                  threshold, seed, out_mask, out_tokens, out_scores);
 }
 
 hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
@@ -397,24 +457,35 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     if (P == 0) return hipSuccess;
     const int eb = logit_is_bf16 ? 2 : 4;
     const int nvec = (int)((long)V * eb / 16);
-    const int S = verify_splits(P, V, eb);
-    const int chunk = (nvec + S - 1) / S;
     const bool kl = (mode == 1 || mode == 3);
-    VerifyPartial *part = static_cast<VerifyPartial *>(workspace);
     const uint4 *ld = static_cast<const uint4 *>(logits_d);
     const uint4 *lv = static_cast<const uint4 *>(logits_v);
-    const dim3 grid((unsigned)((long)P * S)), block(kThreads);
     hipError_t e;
-    if (logit_is_bf16) {
-        if (kl) e = launch(verify_partial_kernel<true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
-        else    e = launch(verify_partial_kernel<true, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+    const int fused = verify_fused_threads(P);
+    if (fused != 0) {
+        const dim3 grid((unsigned)P);
+        if (logit_is_bf16)
+            e = kl ? launch_row_kernel<true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores)
+                   : launch_row_kernel<true, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores);
+        else
+            e = kl ? launch_row_kernel<false, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores)
+                   : launch_row_kernel<false, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores);
     } else {
-        if (kl) e = launch(verify_partial_kernel<false, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
-        else    e = launch(verify_partial_kernel<false, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        const int S = verify_splits(P, V, eb);
+        const int chunk = (nvec + S - 1) / S;
+        VerifyPartial *part = static_cast<VerifyPartial *>(workspace);
+        const dim3 grid((unsigned)((long)P * S)), block(kThreads);
+        if (logit_is_bf16) {
+            if (kl) e = launch(verify_partial_kernel<true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+            else    e = launch(verify_partial_kernel<true, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        } else {
+            if (kl) e = launch(verify_partial_kernel<false, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+            else    e = launch(verify_partial_kernel<false, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        }
+        if (e != hipSuccess) return e;
+        e = launch(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), stream,
+                   (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
     }
-    if (e != hipSuccess) return e;
-    e = launch(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), stream,
-               (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
     if (e != hipSuccess) return e;
     if (mode == 3)
         e = launch(verify_klprob_kernel, dim3(B), dim3(256), stream, (const float *)out_scores, mask, G, seed, out_mask);

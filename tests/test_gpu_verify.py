@@ -72,6 +72,17 @@ def test_ragged_vocab_and_row_splits(V, dtype):
         check_against_oracle(inp, mode, tau, 0, cfg.B, cfg.G, dtype, f"V={V} dtype={dtype} mode={mode}")
 
 
+@pytest.mark.parametrize("P,V,dtype", [(200, 1000, wl.BF16), (300, 33000, wl.BF16), (1100, 520, wl.F32),
+                                        (2100, 4104, wl.BF16), (192, 8, wl.BF16)])
+def test_one_workgroup_per_row_path(P, V, dtype):
+    # enough rows for the fused kernel (workgroup sizes 512 and 256), ragged vocabularies
+    cfg = wl.custom_config(B=4, G=P // 4, V=V, logit_dtype=dtype, sigma_d=3.0, sigma_n=1.0, decoded_frac=0.5)
+    assert dd.dd_verify_remask_workspace_bytes(cfg.B, cfg.G, V, dtype) == 0
+    inp = wl.verify_inputs(cfg, seed=P)
+    for mode, tau in ((wl.KL_THRESH, 0.45), (wl.CONF_THRESH, 0.02), (wl.KL_PROB, 0.0), (wl.TRUST, 0.0)):
+        check_against_oracle(inp, mode, tau, 9, cfg.B, cfg.G, dtype, f"fused P={P} V={V} mode={mode}")
+
+
 def test_degenerate_rows():
     V = 2048
     rng = np.random.default_rng(0)
