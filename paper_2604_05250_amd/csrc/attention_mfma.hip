@@ -500,6 +500,10 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
+    if (!blk && !fp8) {
+        static const char *wide = getenv("DD_TUNE_ATTN_WIDE");
+        if (wide && wide[0] == '1') return launch_attention_wide(a, stream);
+    }
     if (!blk) {
         if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)
                                 : launch(attn_mfma_kernel<128, false, false>, grid, block, stream, k);
