@@ -501,8 +501,13 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
     if (!blk && !fp8) {
-        static const char *wide = getenv("DD_TUNE_ATTN_WIDE");
-        if (wide && wide[0] == '1') return launch_attention_wide(a, stream);
+        // The wide-wave kernel (256 query rows per workgroup, one wave per SIMD) wins once there are enough
+        // row tiles to occupy the chip; below that the 128-row workgroups of this file spread better.
+        // DD_TUNE_ATTN_WIDE=0/1 forces the choice (read per call so that tests can switch it).
+        const long tiles = (long)a.B * a.Hkv * (((long)(a.H / a.Hkv) * a.Nq + 255) / 256);
+        bool wide = tiles >= 192 && a.N >= 512;
+        if (const char *e = getenv("DD_TUNE_ATTN_WIDE")) wide = e[0] == '1';
+        if (wide) return launch_attention_wide(a, stream);
     }
     if (!blk) {
         if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)

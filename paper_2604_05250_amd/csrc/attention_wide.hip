@@ -100,10 +100,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hh = lane >> 5;
-#ifdef DDW_TIMING
-    unsigned long long tstamp[6];
-    tstamp[0] = wall_clock64(); tstamp[1] = __builtin_readcyclecounter();
-#endif
 
     // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD (own L2 each)
     int bid = blockIdx.x;
@@ -234,12 +230,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     __attribute__((always_inline)) {
         constexpr bool PRIMED = decltype(primed)::value, CHAIN = decltype(chain)::value;
         constexpr bool DMA = decltype(dma)::value;
-#ifndef DDW_NOFETCH
         if (!PRIMED) {
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
-#endif
         if (32 * (u + 1) > nkeys) {                          // uniform branch: keys at or past the end score -inf
 #pragma unroll
             for (int q = 0; q < QB; ++q)
@@ -259,11 +253,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         };
         // everything of the step that is not an MFMA, dealt out over the NP pieces
         auto piece = [&](int t) __attribute__((always_inline)) {
-#ifdef DDW_NODMA
-            if (false) {
-#else
             if (DMA && t >= 1 && t <= 2 * NDMA) {
-#endif
                 if (t <= NDMA) dma_one(dk, k_glob, dma_koff, ktile, t - 1);
                 else dma_one(dv, v_glob, dma_voff, vtile, t - 1 - NDMA);
             }
@@ -293,11 +283,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
                 for (int e = 32 * (t - MAXC) / EXC; e < 32 * (t - MAXC + 1) / EXC; ++e) {
                     const int pr = e >> 1, q = pr & 1, r = (pr >> 1) * 2 + (e & 1);
-#ifdef DDW_NOEXP
-                    pe[e] = s_cur[q][r];
-#else
                     pe[e] = fast_exp2(fmaf(s_cur[q][r], c[q], -mc[q]));
-#endif
                 }
             }
             // pairs completed in the previous piece are packed now: a transcendental result cannot be
@@ -314,10 +300,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
             for (int q = 0; q < QB; ++q) {
                 if (j == 0) qk_first(s_nxt[q], kfr[0], qf[q][0]);
                 else qk_next(s_nxt[q], kfr[j % RD], qf[q][j]);
-#ifndef DDW_NOFETCH
                 if (q == QB - 1 && j + RD < KS) kfr[j % RD] = k_frag(kb, ksub, j + RD);
                 if (q == 0 && j >= KS - RD) vfr[j - (KS - RD)] = v_frag(vb, vsub, j - (KS - RD));
-#endif
                 piece(j * QB + q);
             }
         }
@@ -332,12 +316,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     const uint4 pw = make_uint4(pk_prev[q][st][0], pk_prev[q][st][1], pk_prev[q][st][2], pk_prev[q][st][3]);
                     acc[q][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[jv % RD], __builtin_bit_cast(bf16x8, pw),
                                                                         acc[q][i], 0, 0, 0);
-#ifndef DDW_NOFETCH
                     if (q == QB - 1) {
                         if (jv + RD < 2 * DC) vfr[jv % RD] = v_frag(vb, vsub, jv + RD);
                         else if (CHAIN) kfr[jv + RD - 2 * DC] = k_frag(kb, 1, jv + RD - 2 * DC);
                     }
-#endif
                     piece(NQK + st * (DC + 1) * QB + i * QB + q);
                 }
             }
@@ -372,29 +354,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // Stage sp = steps 2sp+1 and 2sp+2.  With PAR = sp & 1 it reads K tile sp+1 from K[1-PAR] and V tile sp
     // from V[PAR], while K tile sp+2 streams into K[PAR] and V tile sp+1 into V[1-PAR] (stand-ins past the end).
-#ifdef DDW_TIMING2
-    unsigned long long tacc[3] = {0, 0, 0};
-#endif
     auto stage = [&](int sp, auto par) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par)::value;
         if (wave_active) {
-#ifdef DDW_TIMING2
-            const unsigned long long ta = __builtin_readcyclecounter();
-#endif
             step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
                  kbuf(I_<PAR>{}), sp + 2, vbuf(I_<1 - PAR>{}), sp + 1);
-#ifdef DDW_TIMING2
-            const unsigned long long tb = __builtin_readcyclecounter();
-#endif
             step(2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
                  kbuf(I_<PAR>{}), 0, vbuf(I_<1 - PAR>{}), 0);
-#ifdef DDW_TIMING2
-            const unsigned long long tc = __builtin_readcyclecounter();
-            __syncthreads();
-            const unsigned long long td = __builtin_readcyclecounter();
-            tacc[0] += tb - ta; tacc[1] += tc - tb; tacc[2] += td - tc;
-            return;
-#endif
         } else {
             dma_tile(kbuf(I_<PAR>{}), k_glob, dma_koff, sp + 2);
             dma_tile(vbuf(I_<1 - PAR>{}), v_glob, dma_voff, sp + 1);
@@ -419,16 +385,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // the compiler does not know that the statements above are matrix instructions whose results
         // need 11 more wait states before a vector instruction may read them
         asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-#ifdef DDW_NOFETCH
-        kfr[0] = kfr[1] = kfr[2] = k_frag(K0, 0, 0);
-        vfr[0] = vfr[1] = vfr[2] = v_frag(V0, 0, 0);
-#endif
         step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, 0, V0, 0);
     }
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
-#ifdef DDW_TIMING
-    tstamp[2] = wall_clock64(); tstamp[3] = __builtin_readcyclecounter();
-#endif
 
     // ---- stages 0 .. ntiles-1 = steps 1 .. 2 ntiles: the product with P(u) happens in step u+1, so this
     // covers every unit; the one or two surplus steps work on masked stand-in units
@@ -439,36 +398,39 @@ void attn_wide_kernel(const AttnKernelArgs a)
     }
     if (sp < ntiles) stage(sp, I_<0>{});
 
-#ifdef DDW_TIMING
-    tstamp[4] = wall_clock64(); tstamp[5] = __builtin_readcyclecounter();
-#endif
     if (!wave_active) return;
-    // accumulator register r of chunk i holds dim 32*i + 8*(r/4) + 4*hh + (r%4) of the lane's query
+    // ---- normalise, transpose through LDS, write whole rows.  The tile buffers are free now (the barrier
+    // that ended the last stage also waited for its loads); wave w uses buffer w: 64 rows of ROWB bytes.
+    // O^T register r of chunk i holds dim 32 i + 8 (r / 4) + 4 hh + (r % 4) of query row l32 of its block.
+    {
+        constexpr int SL = D / 4;                                          // 8-byte slots per row
+        char *region = reinterpret_cast<char *>(wave == 0 ? K0 : wave == 1 ? K1 : wave == 2 ? V0 : V1);
 #pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        if (!row_ok[q]) continue;
-        const float inv = 1.0f / acc_l[q][0];
-        uint16_t *o = static_cast<uint16_t *>(a.O) + orow[q] * D;
+        for (int q = 0; q < QB; ++q) {
+            const float inv = 1.0f / acc_l[q][0];
+            const int row = q * 32 + l32;
 #pragma unroll
-        for (int i = 0; i < DC; ++i)
+            for (int i = 0; i < DC; ++i)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
-                                           pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
-                *reinterpret_cast<uint2 *>(o + i * 32 + q4 * 8 + hh * 4) = w;
-            }
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
+                                               pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
+                    const int slot = i * 8 + q4 * 2 + hh;
+                    // slots are XOR-ed with the row so that the 16 rows written together hit different banks
+                    *reinterpret_cast<uint2 *>(region + row * ROWB + (slot ^ ((row & (SL / 2 - 1)) << 1)) * 8) = w;
+                }
+        }
+        // query rows of one (batch, kv head) are contiguous in memory: row of virtual row v = first row + v
+        uint8_t *og = static_cast<uint8_t *>(a.O) + ((size_t)b * a.H + (size_t)kvh * a.group) * a.Nq * ROWB;
+        constexpr int LPR = ROWB / 16, RPI = 64 / LPR;                     // lanes per row, rows per store
+        const int v_first = rt * kRowsWGWide + wave * kRowsWave;
+#pragma unroll
+        for (int it = 0; it < kRowsWave / RPI; ++it) {
+            const int row = it * RPI + lane / LPR, ch = lane % LPR;
+            const uint4 w = *reinterpret_cast<const uint4 *>(region + row * ROWB + (ch ^ (row & (SL / 2 - 1))) * 16);
+            if (v_first + row < rows_total) *reinterpret_cast<uint4 *>(og + (size_t)(v_first + row) * ROWB + ch * 16) = w;
+        }
     }
-#ifdef DDW_TIMING
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long *dbg = reinterpret_cast<unsigned long long *>(static_cast<uint16_t *>(a.O) + orow[0] * D);
-        for (int i = 0; i < 6; ++i) dbg[i] = tstamp[i];
-        dbg[6] = wall_clock64(); dbg[7] = __builtin_readcyclecounter();
-#ifdef DDW_TIMING2
-        dbg[8] = tacc[0]; dbg[9] = tacc[1]; dbg[10] = tacc[2];
-#endif
-    }
-#endif
 }
 
 }  // namespace

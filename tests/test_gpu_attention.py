@@ -117,6 +117,37 @@ def test_cfg5_bidir_full_size():
     _bidir_full_size(5, 256)
 
 
+# The bf16 verifier call has two kernels (128-row workgroups with two waves per SIMD; 256-row workgroups with
+# one 64-row wave per SIMD); the library picks by problem size and DD_TUNE_ATTN_WIDE forces the choice.
+WIDE = [
+    # (B, H, Hkv, N, d): one key, ragged tails, odd tile counts, GQA groups that straddle 256-row tiles, idle waves
+    (1, 1, 1, 1, 128), (1, 2, 1, 64, 128), (1, 2, 2, 33, 64), (2, 4, 2, 200, 128), (1, 4, 1, 257, 64),
+    (1, 2, 2, 1000, 128), (1, 3, 1, 130, 64), (1, 8, 2, 200, 128), (2, 6, 6, 300, 128), (1, 12, 4, 70, 64),
+]
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d", WIDE)
+def test_bidir_wide_kernel_small_shapes(monkeypatch, B, H, Hkv, N, d):
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", "1")
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, prompt=0, G=N, bl=min(16, N))
+    inp = wl.attention_inputs(cfg, seed=N + d)
+    got = gpu_bidir(inp, cfg)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], wl.BF16, wl.BF16, inp["q_scale"], inp["k_scale"])
+    assert_attention_close(got, ref, wl.BF16, f"wide kernel {B}x{H}/{Hkv}x{N}x{d}")
+
+
+@pytest.mark.parametrize("wide", ["0", "1"])
+def test_cfg3_bidir_each_kernel(monkeypatch, wide):
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    _bidir_full_size(3, 192)
+
+
+@pytest.mark.parametrize("wide", ["0", "1"])
+def test_cfg2_bidir_each_kernel(monkeypatch, wide):
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    _bidir_full_size(2, 0, full=True)
+
+
 # ------------------------------------------------------------------ block attention over the cache
 def _block_case(cfg, seed, step, full_rows=True, n_rows=256):
     cache = wl.cache_inputs(cfg, seed)
