@@ -234,7 +234,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
-        if (32 * (u + 1) > nkeys) {                          // uniform branch: keys at or past the end score -inf
+        if (__builtin_expect(32 * (u + 1) > nkeys, 0)) {     // uniform branch: keys at or past the end score -inf
 #pragma unroll
             for (int q = 0; q < QB; ++q)
 #pragma unroll
@@ -334,7 +334,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr)
             if (exp_piece(2 * pr + 1) == NP - 1) pack_pair(pr);
-        if (changed) {                                       // rare: everything accumulated so far changes units
+        if (__builtin_expect(changed, 0)) {                  // rare: everything accumulated so far changes units
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
 #pragma unroll
