@@ -447,16 +447,32 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     const long row = gid / per_row;
     const int c4 = (int)(gid % per_row);
     if (row >= rows) return;
-    const float *ml = part_ml + row * splits * 2;
+    // every load of the row is issued before the first use (at most 16 splits): one memory round trip
+    constexpr int kMaxSplits = 16;
+    const float2 *ml = reinterpret_cast<const float2 *>(part_ml + row * splits * 2);
+    float2 st[kMaxSplits];
+    float4 po[kMaxSplits];
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+        st[s] = make_float2(-INFINITY, 0.f);
+        po[s] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s < splits) {
+            st[s] = ml[s];
+            po[s] = *reinterpret_cast<const float4 *>(part_o + (row * splits + s) * d + c4 * 4);
+        }
+    }
     float M = -INFINITY;
-    for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[2 * s]);
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) M = fmaxf(M, st[s].x);
     float L = 0.f;
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < splits; ++s) {
-        const float w = fast_exp2(ml[2 * s] - M);
-        L += w * ml[2 * s + 1];
-        const float4 p = *reinterpret_cast<const float4 *>(part_o + (row * splits + s) * d + c4 * 4);
-        o.x += w * p.x; o.y += w * p.y; o.z += w * p.z; o.w += w * p.w;
+#pragma unroll
+    for (int s = 0; s < kMaxSplits; ++s) {
+        if (s < splits) {
+            const float w = fast_exp2(st[s].x - M);
+            L += w * st[s].y;
+            o.x += w * po[s].x; o.y += w * po[s].y; o.z += w * po[s].z; o.w += w * po[s].w;
+        }
     }
     const float inv = 1.0f / L;
     if (OUT_BF16) {

@@ -3,6 +3,8 @@
 #include "../../include/dd.h"
 #include "dd_internal.h"
 
+#include <cstdlib>
+
 namespace {
 
 inline bool misaligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -38,7 +40,10 @@ int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
     (void)d;
     const int group = H / Hkv;
     const long base = (long)B * Hkv * ((group * block_len + 127) / 128);
-    long s = (1024 + base - 1) / base;
+    // One workgroup per compute unit is the target: every extra split adds partial-state traffic and
+    // merge work (measured: 256 beats 512 and 1024 on all four benchmark shapes, 128 loses on N = 4096).
+    static const int target = [] { const char *e = getenv("DD_TUNE_BLOCK_TARGET_WGS"); return e && *e ? atoi(e) : 256; }();
+    long s = (target + base - 1) / base;
     const long max_s = N / 128 > 1 ? N / 128 : 1;   // at least 128 keys per split
     if (s > max_s) s = max_s;
     if (s > 16) s = 16;
