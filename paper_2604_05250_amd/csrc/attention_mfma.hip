@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
 
     // ---- which (batch, kv head, row tile, key split) this workgroup owns
     int bid = blockIdx.x;
-    if (!BLOCK) {
+    {
         // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Remap so that the
         // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD.
         const int total = gridDim.x, per = total >> 3, rem = total & 7;
