@@ -19,7 +19,8 @@ struct AttnKernelArgs {
     const float *q_scale, *k_scale;
     int B, H, Hkv, Nq, N;
     int group;                 // H / Hkv
-    int row_tiles;             // ceil(group * Nq / rows per workgroup)
+    int rows_per_wg;           // query rows per workgroup (a multiple of a wave's rows)
+    int row_tiles;             // ceil(group * Nq / rows_per_wg)
     int splits;                // key-range splits
     int keys_per_split;        // multiple of the key tile
     int block_start, block_len;

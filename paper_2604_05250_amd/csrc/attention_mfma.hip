@@ -119,12 +119,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     const int kvh = bid % a.Hkv;
     const int b = bid / a.Hkv;
     const int rows_total = a.group * a.Nq;
-    const int v = rt * kRowsPerWG + wave * kRowsPerWave + l32;
+    const int v = rt * a.rows_per_wg + wave * kRowsPerWave + l32;
     const bool row_ok = v < rows_total;
     const int vv = row_ok ? v : rows_total - 1;
     const int head = kvh * a.group + vv / a.Nq;
     const int qi = vv % a.Nq;
-    const bool wave_active = rt * kRowsPerWG + wave * kRowsPerWave < rows_total;
+    // waves past the workgroup's rows only help to stage the tiles
+    const bool wave_active = wave * kRowsPerWave < a.rows_per_wg && rt * a.rows_per_wg + wave * kRowsPerWave < rows_total;
     const size_t orow = ((size_t)b * a.H + head) * (size_t)a.Nq + qi;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane (query l32, half hh) holds dims 16*ks + 8*hh .. +7
@@ -492,6 +493,7 @@ void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int
     k.q_scale = a.q_scale; k.k_scale = a.k_scale;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.Nq = a.Nq; k.N = a.N;
     k.group = a.H / a.Hkv;
+    k.rows_per_wg = rows_per_wg;
     k.row_tiles = (k.group * a.Nq + rows_per_wg - 1) / rows_per_wg;
     k.splits = a.splits;
     int per = (a.N + a.splits - 1) / a.splits;
@@ -511,7 +513,7 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     AttnKernelArgs k;
     const bool fp8 = a.qk_dtype == 2;
     const bool blk = a.Nq != a.N || a.Kblk != nullptr || a.splits > 1;   // drafter form of the call
-    fill_kernel_args(a, k, kRowsPerWG, TK);
+    fill_kernel_args(a, k, blk && a.Nq != a.N ? attn_block_rows_per_wg(a.Nq, a.B, a.H, a.Hkv) : kRowsPerWG, TK);
     const long blocks = (long)a.B * a.Hkv * k.row_tiles * k.splits;
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors

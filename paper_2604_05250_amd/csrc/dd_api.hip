@@ -35,14 +35,31 @@ int check_workspace(const void *ws, size_t have, size_t need)
 
 namespace dd {
 
+static int env_or(const char *name, int dflt)
+{
+    const char *e = getenv(name);
+    return e && *e ? atoi(e) : dflt;
+}
+
+// Query rows per workgroup of the drafter's MFMA kernel.  Smaller row tiles (64, 32: more workgroups that
+// stream the same K/V side by side) were measured and lose on every benchmark shape, so 128 it is;
+// DD_TUNE_BLOCK_ROWS keeps the experiment repeatable.
+int attn_block_rows_per_wg(int block_len, int B, int H, int Hkv)
+{
+    (void)block_len; (void)B; (void)H; (void)Hkv;
+    static const int forced = env_or("DD_TUNE_BLOCK_ROWS", 0);
+    return (forced == 32 || forced == 64) ? forced : 128;
+}
+
 int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
 {
     (void)d;
     const int group = H / Hkv;
-    const long base = (long)B * Hkv * ((group * block_len + 127) / 128);
-    // One workgroup per compute unit is the target: every extra split adds partial-state traffic and
-    // merge work (measured: 256 beats 512 and 1024 on all four benchmark shapes, 128 loses on N = 4096).
-    static const int target = [] { const char *e = getenv("DD_TUNE_BLOCK_TARGET_WGS"); return e && *e ? atoi(e) : 256; }();
+    const int r = attn_block_rows_per_wg(block_len, B, H, Hkv);
+    const long base = (long)B * Hkv * ((group * block_len + r - 1) / r);
+    // Every extra split adds partial-state traffic and merge work, so the key range is only split until
+    // there is about one workgroup per compute unit.
+    static const int target = env_or("DD_TUNE_BLOCK_TARGET_WGS", 256);
     long s = (target + base - 1) / base;
     const long max_s = N / 128 > 1 ? N / 128 : 1;   // at least 128 keys per split
     if (s > max_s) s = max_s;

@@ -57,6 +57,7 @@ struct AttnArgs {
 };
 
 int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d);
+int attn_block_rows_per_wg(int block_len, int B, int H, int Hkv);
 size_t attn_partial_bytes(int B, int H, int Nq, int d, int splits);
 hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream);   // bf16 / fp8 inputs
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t stream);    // fp32 inputs
