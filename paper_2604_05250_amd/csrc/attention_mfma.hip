@@ -527,6 +527,12 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
         if (const char *e = getenv("DD_TUNE_ATTN_WIDE")) wide = e[0] == '1';
         if (wide) return launch_attention_wide(a, stream);
     }
+    if (blk && !fp8 && a.Nq != a.N && attn_stream_fits(a)) {
+        // The drafter's call is bound by streaming K/V once: a kernel built around the memory pipeline
+        // serves it (DD_TUNE_BLOCK_STREAM=0 keeps it on this file's kernel).
+        const char *env = getenv("DD_TUNE_BLOCK_STREAM");
+        if (!(env && env[0] == '0')) return launch_attention_stream(a, stream);
+    }
     if (!blk) {
         if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)
                                 : launch(attn_mfma_kernel<128, false, false>, grid, block, stream, k);

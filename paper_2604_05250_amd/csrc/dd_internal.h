@@ -62,6 +62,8 @@ size_t attn_partial_bytes(int B, int H, int Nq, int d, int splits);
 hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream);   // bf16 / fp8 inputs
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t stream);    // fp32 inputs
 hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream);   // bf16 verifier form, 64 rows per wave
+hipError_t launch_attention_stream(const AttnArgs &a, hipStream_t stream);  // bf16 drafter form, few query rows
+bool attn_stream_fits(const AttnArgs &a);
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream);
 
 }  // namespace dd

@@ -193,6 +193,31 @@ BLOCK_SMALL = [
 ]
 
 
+# The bf16 drafter call has two kernels as well: the streaming kernel (up to 64 query rows per kv head) and the
+# MFMA kernel with 128-row workgroups; DD_TUNE_BLOCK_STREAM=0 keeps every call on the latter.
+STREAM_SHAPES = [
+    # (B, H, Hkv, N, d, bl, block_start): one tile, ragged last tile, block at both ends and across tiles,
+    # one query, 33 rows (second row block nearly empty), GQA 2 x 32 rows, key splits with a short last split
+    (1, 2, 2, 64, 128, 64, 0), (1, 2, 2, 100, 64, 16, 84), (2, 4, 2, 333, 128, 32, 101), (1, 2, 1, 150, 64, 1, 77),
+    (1, 3, 3, 500, 128, 33, 467), (1, 4, 2, 700, 128, 32, 60), (1, 2, 2, 4096, 128, 64, 2000), (1, 1, 1, 1090, 64, 64, 1026),
+]
+
+
+@pytest.mark.parametrize("stream", ["1", "0"])
+@pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs", STREAM_SHAPES)
+def test_block_each_kernel(monkeypatch, stream, B, H, Hkv, N, d, bl, bs):
+    monkeypatch.setenv("DD_TUNE_BLOCK_STREAM", stream)
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, bl=bl, prompt=0, G=N)
+    cache = wl.cache_inputs(cfg, seed=bs + d)
+    blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+    for fresh in (True, False):
+        Kb, Vb = (blk["Kblk"], blk["Vblk"]) if fresh else (None, None)
+        got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, Kb, Vb, blk["q_scale"], cache["k_scale"])
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, wl.BF16, wl.BF16, Kb, Vb,
+                                            blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, wl.BF16, f"block kernel stream={stream} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} fresh={fresh}")
+
+
 @pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", BLOCK_SMALL)
 def test_block_small_shapes(B, H, Hkv, N, d, bl, bs, qk):
     vd = wl.F32 if qk == wl.F32 else wl.BF16
