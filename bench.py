@@ -187,7 +187,8 @@ def main():
         "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
         "block_attention_GBps": round(blk_gbps, 1),
-        "roofline": {"kernel": "attn_mfma_kernel (dd_bidir_attention)", "bound": "mfma",
+        "roofline": {"kernel": "dd_bidir_attention (attn_wide_kernel on large bf16 shapes, else attn_mfma_kernel)",
+                     "bound": "mfma",
                      "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),

@@ -22,6 +22,13 @@
 // assembly.  The hazards the compiler would otherwise pad are kept apart by construction: a score block
 // is written by the first half of step u's MFMAs and first read by a vector instruction in step u+1.
 //
+// Persistence.  A lone wave cannot hide the start (operand loads, pipeline fill) and the end (normalise,
+// store) of a row tile behind another workgroup's work, so a workgroup walks through a contiguous range of
+// row tiles and the K/V tile stream simply wraps into the next row tile: the two surplus steps that drain
+// one tile's pipeline compute the first two score blocks of the next.  The next tile's Q rows are
+// prefetched into LDS one stage earlier; the finished tile is normalised, transposed through the same
+// LDS region and written out in full rows.
+//
 // Staging.  K and V tiles (64 keys) are double-buffered in four separate LDS arrays and filled by
 // global_load_lds_dwordx4 (no registers, no LDS store instructions); the arrays are distinct objects and
 // selected statically, so the compiler only waits for those loads at the barrier that ends a stage.
@@ -31,6 +38,7 @@
 #include "attention_common.h"
 #include "dd_internal.h"
 
+#include <cstdlib>
 #include <type_traits>
 
 namespace dd {
@@ -72,6 +80,9 @@ __device__ __forceinline__ void qk_next(floatx16 &s, const intx4 kf, const intx4
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
 }
 
+// s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
 template <int N> using I_ = std::integral_constant<int, N>;
 using T_ = std::true_type;
 using F_ = std::false_type;
@@ -83,54 +94,72 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per row
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
-    constexpr int ROWB = D * 2;                      // bytes per K / V row
+    constexpr int ROWB = D * 2;                      // bytes per Q / K / V / O row
     constexpr int DMA_ROWS = 1024 / ROWB;            // rows moved by one wave-wide 16-byte-per-lane load
-    constexpr int NDMA = TKW / DMA_ROWS / 4;         // such loads per wave per tile
+    constexpr int NDMA = TKW / DMA_ROWS / 4;         // such loads per wave per K or V tile
+    constexpr int NQDMA = kRowsWave / DMA_ROWS;      // ... per wave for its Q rows
     constexpr int NQK = KS * QB;                     // pieces of a step: S(u+1) ...
     constexpr int NPV = 2 * DC * QB;                 // ... O += V P ...
     constexpr int NP = NQK + NPV + 2 * QB;           // ... and the row sums
     constexpr int MAXC = NP >= 32 ? 8 : 4;           // pieces that carry the row maxima
     constexpr int EXC = NP - MAXC;                   // pieces that carry the 32 exponentials
+    constexpr int RD = 3;                            // fragment rings: fetched RD uses (2 RD MFMAs) ahead
     static_assert(2 * NDMA + 1 <= NP, "one tile load per piece");
-    static_assert(KS >= 3 && 2 * DC >= 3, "fragment rings are three deep");
+    static_assert(KS >= RD && 2 * DC >= RD, "fragment rings are three deep");
+    static_assert((4 * DMA_ROWS) % 8 == 0 && DMA_ROWS <= 8, "swizzle phase must not depend on the load index");
 
-    __shared__ uint4 K0[TKW * CH], K1[TKW * CH];     // [key][chunk ^ (key & 7)]
-    __shared__ uint4 V0[TKW * CH], V1[TKW * CH];     // [key][chunk ^ ((key % (CH/4)) << 2)]  (row-major, 64-byte granules)
+    __shared__ __attribute__((aligned(4096))) uint4 K0[TKW * CH], K1[TKW * CH];     // [key][chunk ^ (key & 7)]
+    __shared__ __attribute__((aligned(4096))) uint4 V0[TKW * CH], V1[TKW * CH];     // [key][chunk ^ ((key % (CH/4)) << 2)]  (row-major, 64-byte granules)
+    __shared__ uint4 QO[kRowsWGWide * CH];           // next tile's Q rows [row][chunk ^ (row & 7)], then O on its way out
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+#ifdef DDW_TIMING2
+    const unsigned long long t_kernel = __builtin_readcyclecounter();
+#endif
     const int l32 = lane & 31, hh = lane >> 5;
 
-    // workgroups sharing one (batch, kv head) - hence the same K/V - run on the same XCD (own L2 each)
-    int bid = blockIdx.x;
+    // ---- this workgroup's range of row tiles.  Tile t = ((b * Hkv + kvh) * row_tiles + rt); neighbours
+    // share K/V, and consecutive workgroup ranges go to the same XCD (own L2 each).
+    const int tiles_total = a.B * a.Hkv * a.row_tiles;
+    int t_cur, t_end;
     {
-        const int total = gridDim.x, per = total >> 3, rem = total & 7;
-        const int xcd = bid & 7, slot = bid >> 3;
-        bid = xcd * per + min(xcd, rem) + slot;
+        const int G = gridDim.x, per = G >> 3, rem = G & 7;
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int w = xcd * per + min(xcd, rem) + slot;
+        const int base = tiles_total / G, extra = tiles_total % G;
+        t_cur = w * base + min(w, extra);
+        t_end = t_cur + base + (w < extra ? 1 : 0);
     }
-    const int rt = bid % a.row_tiles; bid /= a.row_tiles;
-    const int kvh = bid % a.Hkv;
-    const int b = bid / a.Hkv;
-    const int rows_total = a.group * a.Nq;
-    const bool wave_active = rt * kRowsWGWide + wave * kRowsWave < rows_total;
+    const int rows_total = a.group * a.Nq;           // query rows per (batch, kv head); contiguous in memory
     const int nkeys = a.N;
-    const int ntiles = (nkeys + TKW - 1) / TKW;
-    const size_t kv_head = (size_t)b * a.Hkv + kvh;
+    const int nt_even = ((nkeys + TKW - 1) / TKW + 1) & ~1;   // tiles per pass, padded to an even count
+    struct Tile { const uint8_t *k, *v; size_t row_base; int v0, bh0, kvs; };
+    auto tile_of = [&](int t) __attribute__((always_inline)) {
+        const int rt = t % a.row_tiles, bk = t / a.row_tiles, kvh = bk % a.Hkv, b = bk / a.Hkv;
+        Tile r;
+        r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.N * (size_t)ROWB;
+        r.v = static_cast<const uint8_t *>(a.V) + (size_t)bk * a.N * (size_t)ROWB;
+        r.bh0 = b * a.H + kvh * a.group;             // first query head of the group
+        r.row_base = (size_t)r.bh0 * a.Nq;           // row of virtual row 0 in Q and O
+        r.v0 = rt * kRowsWGWide;                     // first virtual row of the tile
+        r.kvs = bk;                                  // index into k_scale
+        return r;
+    };
 
     // ---- staging by LDS DMA: load i of this wave moves rows (4i + wave) * DMA_ROWS .. of a tile; lane l
     // lands at chunk position l % CH of row l / CH and therefore fetches the chunk the swizzle maps there.
     // Both swizzles only depend on the row modulo 4 DMA_ROWS, so the chunk a lane fetches is the same for every load.
     const int dma_row = lane / CH, dma_pos = lane % CH;
-    const uint8_t *const k_glob = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)ROWB;
-    const uint8_t *const v_glob = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)ROWB;
     const int dma_row0 = wave * DMA_ROWS + dma_row;                        // row of load 0; load i: + 4 i DMA_ROWS
     const unsigned dma_koff = (dma_pos ^ (dma_row0 & 7)) * 16;
     const unsigned dma_voff = (dma_pos ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
-    static_assert((4 * DMA_ROWS) % 8 == 0, "swizzle phase must not depend on the load index");
     // one load (index i) of a tile; rows past the last key repeat it (finite stand-ins, masked later)
     auto dma_one = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int tile, int i) __attribute__((always_inline)) {
         const int r0 = (i * 4 + wave) * DMA_ROWS;
-        const int row = min(tile * TKW + i * 4 * DMA_ROWS + dma_row0, nkeys - 1);
+        int row0 = dma_row0;
+        asm volatile("" : "+v"(row0));           // keeps the address arithmetic here (not hoisted and spilled)
+        const int row = min(tile * TKW + i * 4 * DMA_ROWS + row0, nkeys - 1);
         const uint8_t *src = glob + (size_t)((unsigned)row * (unsigned)ROWB + lane_off);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                          (__attribute__((address_space(3))) void *)(dst + r0 * CH), 16, 0, 0);
@@ -139,49 +168,42 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
         for (int i = 0; i < NDMA; ++i) dma_one(dst, glob, lane_off, tile, i);
     };
+    // this wave's 64 query rows of a tile -> its quarter of QO (rows past the end repeat the last one)
+    auto dma_q = [&](const Tile &t) __attribute__((always_inline)) {
+        const uint8_t *qg = static_cast<const uint8_t *>(a.Q) + t.row_base * ROWB;
+        // Rarely executed code derives its per-lane values from an opaque copy of the lane number: otherwise
+        // they are all computed once at kernel start and occupy registers (or scratch) throughout.
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int drow = ln / CH, dpos = ln % CH;
+#pragma unroll
+        for (int i = 0; i < NQDMA; ++i) {
+            const int r0 = wave * kRowsWave + i * DMA_ROWS;
+            const int row = min(t.v0 + r0 + drow, rows_total - 1);
+            const uint8_t *src = qg + (size_t)((unsigned)row * (unsigned)ROWB + (dpos ^ ((i * DMA_ROWS + drow) & 7)) * 16);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                             (__attribute__((address_space(3))) void *)(QO + r0 * CH), 16, 0, 0);
+        }
+    };
     auto kbuf = [&](auto p) __attribute__((always_inline)) -> uint4 * { if constexpr (decltype(p)::value == 0) return K0; else return K1; };
     auto vbuf = [&](auto p) __attribute__((always_inline)) -> uint4 * { if constexpr (decltype(p)::value == 0) return V0; else return V1; };
 
-    // ---- prologue loads: K tiles 0 and 1, V tile 0 go straight to LDS while the Q fragments are fetched
-    dma_tile(K0, k_glob, dma_koff, 0);
-    dma_tile(V0, v_glob, dma_voff, 0);
-    dma_tile(K1, k_glob, dma_koff, 1);
-
-    bool row_ok[QB];
-    size_t orow[QB];
+    // ---- per-lane state of the two query blocks
     float c[QB];                                     // scores are exponentiated as 2^(s*c)
     intx4 qf[QB][KS];                                // B operand of S^T = K Q^T (8 bf16), kept in accumulation VGPRs
-#pragma unroll
-    for (int q = 0; q < QB; ++q) {
-        const int v = rt * kRowsWGWide + wave * kRowsWave + q * 32 + l32;
-        row_ok[q] = v < rows_total;
-        const int vv = row_ok[q] ? v : rows_total - 1;
-        const int head = kvh * a.group + vv / a.Nq;
-        orow[q] = ((size_t)b * a.H + head) * (size_t)a.Nq + vv % a.Nq;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qf[q][ks] = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
-                            static_cast<const uint16_t *>(a.Q) + orow[q] * D + ks * 16 + hh * 8));
-        c[q] = a.scale_log2;
-        if (a.q_scale) c[q] *= a.q_scale[b * a.H + head];
-        if (a.k_scale) c[q] *= a.k_scale[b * a.Hkv + kvh];
-    }
-#pragma unroll
-    for (int q = 0; q < QB; ++q)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qf[q][ks]));
-
-    // ---- per-lane state of the two query blocks
     floatx16 acc[QB][DC], acc_l[QB];                 // O^T (unnormalised) and the row sums (all 16 registers equal)
+    auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int q = 0; q < QB; ++q) {
+        for (int q = 0; q < QB; ++q) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_l[q][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc_l[q][r] = 0.f;
 #pragma unroll
-        for (int i = 0; i < DC; ++i)
+            for (int i = 0; i < DC; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[q][i][r] = 0.f;
-    }
+                for (int r = 0; r < 16; ++r) acc[q][i][r] = 0.f;
+        }
+    };
+    clear_acc();
     float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
     intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
@@ -213,33 +235,92 @@ void attn_wide_kernel(const AttnKernelArgs a)
         const short8v w = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         return __builtin_bit_cast(bf16x8, w);
     };
+    // Q fragments of a tile out of this wave's quarter of QO (same addressing as a K tile), and its scales
+    auto install_q = [&](const Tile &t) __attribute__((always_inline)) {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                // addresses derived from the opaque lane copy: see dma_q
+                const int lo = ((ln & 31) * CH + ((2 * ks + (ln >> 5)) ^ (ln & 7))) * 16;
+                qf[q][ks] = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
+                                reinterpret_cast<const char *>(QO) + (wave * kRowsWave + q * 32) * ROWB + lo));
+                asm volatile("" : "+a"(qf[q][ks]));
+            }
+            const int v = min(t.v0 + wave * kRowsWave + q * 32 + (ln & 31), rows_total - 1);
+            c[q] = a.scale_log2;
+            if (a.q_scale) c[q] *= a.q_scale[t.bh0 + v / a.Nq];
+            if (a.k_scale) c[q] *= a.k_scale[t.kvs];
+        }
+        // the matrix instructions written as assembly are invisible to the compiler's hazard padding:
+        // keep them clear of the register writes above
+        asm volatile("s_nop 15" : "+a"(qf[0][0]), "+a"(qf[QB - 1][KS - 1]));
+    };
+    // Finished tile: normalise, transpose through this wave's quarter of QO, write whole rows.
+    // O^T register r of chunk i holds dim 32 i + 8 (r / 4) + 4 hh + (r % 4) of query row l32 of its block.
+    auto write_out = [&](const Tile &t) __attribute__((always_inline)) {
+        constexpr int SL = D / 4;                                          // 8-byte slots per row
+        char *region = reinterpret_cast<char *>(QO) + wave * kRowsWave * ROWB;
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int hh = ln >> 5;
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            const float inv = 1.0f / acc_l[q][0];
+            const int row = q * 32 + (ln & 31);
+#pragma unroll
+            for (int i = 0; i < DC; ++i)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
+                                               pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
+                    const int slot = i * 8 + q4 * 2 + hh;
+                    *reinterpret_cast<uint2 *>(region + row * ROWB + (slot ^ ((row & (SL / 2 - 1)) << 1)) * 8) = w;
+                }
+        }
+        uint8_t *og = static_cast<uint8_t *>(a.O) + t.row_base * ROWB;
+        constexpr int LPR = ROWB / 16, RPI = 64 / LPR;                     // lanes per row, rows per store
+#pragma unroll
+        for (int it = 0; it < kRowsWave / RPI; ++it) {
+            const int row = it * RPI + ln / LPR, ch = ln % LPR;
+            const uint4 w = *reinterpret_cast<const uint4 *>(region + row * ROWB + (ch ^ (row & (SL / 2 - 1))) * 16);
+            const int v = t.v0 + wave * kRowsWave + row;
+            if (v < rows_total) *reinterpret_cast<uint4 *>(og + (size_t)v * ROWB + ch * 16) = w;
+        }
+    };
 
-    constexpr int RD = 3;                                    // fragment rings: fetched RD uses (2 RD MFMAs) ahead
     intx4 kfr[RD];
     bf16x8 vfr[RD];
-    // Pipeline step u.  In: s_cur = S(u), pk_prev = P(u-1).  Out: pk_cur = P(u), s_nxt = S(u+1).
+    // Pipeline step.  In: s_cur = S(u), pk_prev = P(u-1).  Out: pk_cur = P(u), s_nxt = S(u+1).
     // kb / ksub: tile buffer and unit of K(u+1); vb / vsub: those of V(u-1).
     // Every step has the same shape: units at or past the end of the keys are computed on finite
     // stand-in rows and masked to -inf, so they contribute exact zeros; P(-1) is zero.
     // `chain`: the next step reads unit 1 of the same tile buffers, so its first K fragments are fetched
     // in this step's last pieces; `primed`: the previous step did that for this one.
     // `dma`: this step also issues the tile loads of its stage (K tile into dk, V tile into dv).
+    // `fin` (run time, only looked at when `can_finish`): S(u) is the first score block of the NEXT row
+    // tile and this step's products are the last of the current one, which is then written out.
     auto step = [&](int u, floatx16 (&s_cur)[QB], floatx16 (&s_nxt)[QB], unsigned (&pk_prev)[QB][2][4],
                     unsigned (&pk_cur)[QB][2][4], const uint4 *kb, int ksub, const uint4 *vb, int vsub,
-                    auto primed, auto chain, auto dma, uint4 *dk, int ktile, uint4 *dv, int vtile)
+                    auto primed, auto chain, auto dma, uint4 *dk, const uint8_t *kg, int ktile,
+                    uint4 *dv, const uint8_t *vg, int vtile, auto can_finish, bool fin, const Tile &cur)
                     __attribute__((always_inline)) {
         constexpr bool PRIMED = decltype(primed)::value, CHAIN = decltype(chain)::value;
-        constexpr bool DMA = decltype(dma)::value;
+        constexpr bool DMA = decltype(dma)::value, CANFIN = decltype(can_finish)::value;
         if (!PRIMED) {
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
         if (__builtin_expect(32 * (u + 1) > nkeys, 0)) {     // uniform branch: keys at or past the end score -inf
+            int k0 = 32 * u + 4 * hh;
+            asm volatile("" : "+v"(k0));
 #pragma unroll
             for (int q = 0; q < QB; ++q)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (32 * u + 8 * (r >> 2) + 4 * hh + (r & 3) >= nkeys) s_cur[q][r] = -INFINITY;
+                    if (k0 + 8 * (r >> 2) + (r & 3) >= nkeys) s_cur[q][r] = -INFINITY;
         }
         float corr[QB], tm[QB], tpart[QB], pe[32];
         bool changed = false;
@@ -254,8 +335,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // everything of the step that is not an MFMA, dealt out over the NP pieces
         auto piece = [&](int t) __attribute__((always_inline)) {
             if (DMA && t >= 1 && t <= 2 * NDMA) {
-                if (t <= NDMA) dma_one(dk, k_glob, dma_koff, ktile, t - 1);
-                else dma_one(dv, v_glob, dma_voff, vtile, t - 1 - NDMA);
+                if (t <= NDMA) dma_one(dk, kg, dma_koff, ktile, t - 1);
+                else dma_one(dv, vg, dma_voff, vtile, t - 1 - NDMA);
             }
             if (t < MAXC) {
                 // row maxima of S(u) decide, without a divergent branch, whether the maxima in use are raised
@@ -334,7 +415,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr)
             if (exp_piece(2 * pr + 1) == NP - 1) pack_pair(pr);
-        if (__builtin_expect(changed, 0)) {                  // rare: everything accumulated so far changes units
+        if (CANFIN && fin) {                                 // uniform: the row tile is complete
+            write_out(cur);
+            clear_acc();
+        } else if (__builtin_expect(changed, 0)) {           // rare: everything accumulated so far changes units
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
 #pragma unroll
@@ -351,86 +435,123 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     floatx16 s0[QB], s1[QB];                                 // S(u) lives in s{u & 1}
     unsigned pk0[QB][2][4], pk1[QB][2][4];                   // P(u) lives in pk{u & 1}
+    Tile cur = tile_of(t_cur), nxt = cur;
+    bool has_next = false;
 
-    // Stage sp = steps 2sp+1 and 2sp+2.  With PAR = sp & 1 it reads K tile sp+1 from K[1-PAR] and V tile sp
-    // from V[PAR], while K tile sp+2 streams into K[PAR] and V tile sp+1 into V[1-PAR] (stand-ins past the end).
-    auto stage = [&](int sp, auto par) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(par)::value;
-        if (wave_active) {
-            step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
-                 kbuf(I_<PAR>{}), sp + 2, vbuf(I_<1 - PAR>{}), sp + 1);
-            step(2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
-                 kbuf(I_<PAR>{}), 0, vbuf(I_<1 - PAR>{}), 0);
-        } else {
-            dma_tile(kbuf(I_<PAR>{}), k_glob, dma_koff, sp + 2);
-            dma_tile(vbuf(I_<1 - PAR>{}), v_glob, dma_voff, sp + 1);
+    // Stage sp = steps 2sp+1 and 2sp+2 of a pass over one row tile (nt_even stages).  With PAR = sp & 1 it
+    // reads K tile sp+1 from K[1-PAR] and V tile sp from V[PAR], while K tile sp+2 streams into K[PAR] and
+    // V tile sp+1 into V[1-PAR]; tile numbers at or past nt_even are tiles of the next row tile.
+    // The last stage of a pass (always PAR = 1) therefore already works for the next row tile: its first
+    // step computes that tile's S(0) - with that tile's Q - and its second step S(1) and P(0), while
+    // their products still belong to the current tile, which the second step then writes out.
+    // `kind`: 0 = a stage in the middle of a pass (the hot loop: no tile-boundary logic at all),
+    //         1 = the last but one stage (PAR = 0; its K load is tile 0 of the next row tile),
+    //         2 = the last stage (PAR = 1).
+    auto stage = [&](int sp, auto par, auto kind) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par)::value, KIND = decltype(kind)::value;
+        static_assert(KIND == 0 || (KIND == 1 && PAR == 0) || (KIND == 2 && PAR == 1), "stage kinds");
+        constexpr bool last = KIND == 2;
+        if (last && has_next) {
+            // the Q rows were requested a stage ago and deliberately not waited for at its barrier
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+            install_q(nxt);
         }
-        __syncthreads();                                     // also the point where the streamed tiles are waited for
+        step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
+             kbuf(I_<PAR>{}), KIND == 0 ? cur.k : nxt.k, KIND == 0 ? sp + 2 : KIND - 1,
+             vbuf(I_<1 - PAR>{}), last ? nxt.v : cur.v, last ? 0 : sp + 1, F_{}, false, cur);
+        if (KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
+        if (last) {
+            mc[0] = -INFINITY;                               // the second step starts the next tile's softmax
+            mc[1] = -INFINITY;
+        }
+        step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
+             kbuf(I_<PAR>{}), cur.k, 0, vbuf(I_<1 - PAR>{}), cur.v, 0, std::integral_constant<bool, last>{}, last, cur);
+        // The barrier that ends a stage waits for the stage's tile loads.  Memory operations complete in
+        // order, so the requests issued after those loads - the next tile's Q rows, the finished tile's
+        // output rows - can stay in flight: wait until only that many are outstanding.
+        constexpr int NST = kRowsWave / (64 / (ROWB / 16));  // output stores per wave
+        // (An explicit s_waitcnt builtin is understood by the compiler's own wait insertion, which then does
+        // not add a full wait before the next LDS read; the empty asm statements keep it from moving
+        // memory accesses across the barrier, which by itself is not a fence.)
+        if (KIND == 1 && has_next) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NQDMA));
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        } else if (last && cur.v0 + kRowsWGWide <= rows_total) {
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NST));
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        } else {
+            __syncthreads();
+        }
     };
 
-    // ---- prologue: S(0), then step 0 (its P(-1) is zero)
+    // ---- prologue of the first row tile: Q rows and K tiles 0, 1 and V tile 0 go straight to LDS
+    dma_q(cur);
+    dma_tile(K0, cur.k, dma_koff, 0);
+    dma_tile(V0, cur.v, dma_voff, 0);
+    dma_tile(K1, cur.k, dma_koff, 1);
     __syncthreads();
-    if (wave_active) {
+    install_q(cur);
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int q = 0; q < QB; ++q) {
-                if (ks == 0) qk_first(s0[q], k_frag(K0, 0, 0), qf[q][0]);
-                else qk_next(s0[q], k_frag(K0, 0, ks), qf[q][ks]);
-            }
-#pragma unroll
-        for (int q = 0; q < QB; ++q)
-#pragma unroll
-            for (int t = 0; t < 8; ++t) pk1[q][t >> 2][t & 3] = 0u;
-        // the compiler does not know that the statements above are matrix instructions whose results
-        // need 11 more wait states before a vector instruction may read them
-        asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-        step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, 0, V0, 0);
-    }
-    __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
-
-    // ---- stages 0 .. ntiles-1 = steps 1 .. 2 ntiles: the product with P(u) happens in step u+1, so this
-    // covers every unit; the one or two surplus steps work on masked stand-in units
-    int sp = 0;
-    for (; sp + 1 < ntiles; sp += 2) {
-        stage(sp, I_<0>{});
-        stage(sp + 1, I_<1>{});
-    }
-    if (sp < ntiles) stage(sp, I_<0>{});
-
-    if (!wave_active) return;
-    // ---- normalise, transpose through LDS, write whole rows.  The tile buffers are free now (the barrier
-    // that ended the last stage also waited for its loads); wave w uses buffer w: 64 rows of ROWB bytes.
-    // O^T register r of chunk i holds dim 32 i + 8 (r / 4) + 4 hh + (r % 4) of query row l32 of its block.
-    {
-        constexpr int SL = D / 4;                                          // 8-byte slots per row
-        char *region = reinterpret_cast<char *>(wave == 0 ? K0 : wave == 1 ? K1 : wave == 2 ? V0 : V1);
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            const float inv = 1.0f / acc_l[q][0];
-            const int row = q * 32 + l32;
-#pragma unroll
-            for (int i = 0; i < DC; ++i)
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
-                                               pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
-                    const int slot = i * 8 + q4 * 2 + hh;
-                    // slots are XOR-ed with the row so that the 16 rows written together hit different banks
-                    *reinterpret_cast<uint2 *>(region + row * ROWB + (slot ^ ((row & (SL / 2 - 1)) << 1)) * 8) = w;
-                }
+            if (ks == 0) qk_first(s0[q], k_frag(K0, 0, 0), qf[q][0]);
+            else qk_next(s0[q], k_frag(K0, 0, ks), qf[q][ks]);
         }
-        // query rows of one (batch, kv head) are contiguous in memory: row of virtual row v = first row + v
-        uint8_t *og = static_cast<uint8_t *>(a.O) + ((size_t)b * a.H + (size_t)kvh * a.group) * a.Nq * ROWB;
-        constexpr int LPR = ROWB / 16, RPI = 64 / LPR;                     // lanes per row, rows per store
-        const int v_first = rt * kRowsWGWide + wave * kRowsWave;
 #pragma unroll
-        for (int it = 0; it < kRowsWave / RPI; ++it) {
-            const int row = it * RPI + lane / LPR, ch = lane % LPR;
-            const uint4 w = *reinterpret_cast<const uint4 *>(region + row * ROWB + (ch ^ (row & (SL / 2 - 1))) * 16);
-            if (v_first + row < rows_total) *reinterpret_cast<uint4 *>(og + (size_t)(v_first + row) * ROWB + ch * 16) = w;
+    for (int q = 0; q < QB; ++q)
+#pragma unroll
+        for (int t = 0; t < 8; ++t) pk1[q][t >> 2][t & 3] = 0u;
+    // the compiler does not know that the statements above are matrix instructions whose results
+    // need 11 more wait states before a vector instruction may read them
+    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
+    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, 0, V0, cur.v, 0, F_{}, false, cur);
+    __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
+
+    // ---- passes: stages 0 .. nt_even-1 = steps 1 .. 2 nt_even; the product with P(u) happens in step u+1,
+    // so this covers every unit, and the surplus steps work for the next row tile (or on masked stand-ins)
+#ifdef DDW_TIMING2
+    unsigned long long tacc[3] = {0, 0, 0};
+    const unsigned long long t_loop = __builtin_readcyclecounter();
+#endif
+    for (;;) {
+        has_next = t_cur + 1 < t_end;
+        if (has_next) nxt = tile_of(t_cur + 1);
+        int sp = 0;
+#ifdef DDW_TIMING2
+        const unsigned long long t0 = __builtin_readcyclecounter();
+#endif
+        for (; sp + 2 < nt_even; sp += 2) {
+            stage(sp, I_<0>{}, I_<0>{});
+            stage(sp + 1, I_<1>{}, I_<0>{});
         }
+#ifdef DDW_TIMING2
+        const unsigned long long t1 = __builtin_readcyclecounter();
+#endif
+        stage(sp, I_<0>{}, I_<1>{});
+#ifdef DDW_TIMING2
+        const unsigned long long t2 = __builtin_readcyclecounter();
+#endif
+        stage(sp + 1, I_<1>{}, I_<2>{});
+#ifdef DDW_TIMING2
+        const unsigned long long t3 = __builtin_readcyclecounter();
+        tacc[0] += t1 - t0; tacc[1] += t2 - t1; tacc[2] += t3 - t2;
+#endif
+        if (!has_next) break;
+        cur = nxt;
+        ++t_cur;
     }
+#ifdef DDW_TIMING2
+    if (tid == 0) {
+        unsigned long long *dbg = reinterpret_cast<unsigned long long *>(const_cast<float *>(a.q_scale)) + blockIdx.x * 8;
+        dbg[0] = tacc[0]; dbg[1] = tacc[1]; dbg[2] = tacc[2];
+        dbg[3] = __builtin_readcyclecounter() - t_loop; dbg[4] = t_loop - t_kernel;
+    }
+#endif
 }
 
 }  // namespace
@@ -439,7 +560,20 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
 {
     AttnKernelArgs k;
     fill_kernel_args(a, k, kRowsWGWide, TKW);
-    const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles)), block(kAttnThreads);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    const long tiles = (long)a.B * a.Hkv * k.row_tiles;
+    long wgs = tiles < cus ? tiles : cus;                  // one persistent workgroup per compute unit
+    if (const char *e = getenv("DD_TUNE_ATTN_WIDE_GRID")) {
+        const long v = atol(e);
+        if (v >= 1 && v < wgs) wgs = v;
+    }
+    const dim3 grid((unsigned)wgs), block(kAttnThreads);
     if (a.d == 128) return launch(attn_wide_kernel<128>, grid, block, stream, k);
     return launch(attn_wide_kernel<64>, grid, block, stream, k);
 }

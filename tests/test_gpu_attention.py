@@ -126,9 +126,17 @@ WIDE = [
 ]
 
 
+# The wide kernel's workgroups are persistent: each walks through a contiguous range of 256-row tiles.
+# DD_TUNE_ATTN_WIDE_GRID caps the number of workgroups, so that small shapes also exercise the hand-over
+# from one row tile to the next (and ranges of unequal length).
+@pytest.mark.parametrize("grid", [None, "1", "3"])
 @pytest.mark.parametrize("B,H,Hkv,N,d", WIDE)
-def test_bidir_wide_kernel_small_shapes(monkeypatch, B, H, Hkv, N, d):
+def test_bidir_wide_kernel_small_shapes(monkeypatch, B, H, Hkv, N, d, grid):
     monkeypatch.setenv("DD_TUNE_ATTN_WIDE", "1")
+    if grid is not None:
+        if B * Hkv * -(-(H // Hkv) * N // 256) <= int(grid):
+            pytest.skip("no more row tiles than workgroups: same launch as the uncapped case")
+        monkeypatch.setenv("DD_TUNE_ATTN_WIDE_GRID", grid)
     cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, prompt=0, G=N, bl=min(16, N))
     inp = wl.attention_inputs(cfg, seed=N + d)
     got = gpu_bidir(inp, cfg)
