@@ -525,7 +525,7 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
         const long tiles = (long)a.B * a.Hkv * (((long)(a.H / a.Hkv) * a.Nq + 255) / 256);
         bool wide = tiles >= 192 && a.N >= 512;
         if (const char *e = getenv("DD_TUNE_ATTN_WIDE")) wide = e[0] == '1';
-        if (wide) return launch_attention_wide(a, stream);
+        if (wide && a.N >= 64) return launch_attention_wide(a, stream);   // its K/V tiles are 64 whole rows
     }
     if (blk && !fp8 && a.Nq != a.N && attn_stream_fits(a)) {
         // The drafter's call is bound by streaming K/V once: a kernel built around the memory pipeline

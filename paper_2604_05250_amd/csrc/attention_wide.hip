@@ -55,6 +55,10 @@ constexpr int TKW = 64;                 // keys per tile
 constexpr int QB = 2;                   // 32-row query blocks per wave
 constexpr int kRowsWave = 32 * QB;
 constexpr int kRowsWGWide = 4 * kRowsWave;
+#ifndef DDW_PACK_LAG
+#define DDW_PACK_LAG 2
+#endif
+constexpr int kPackLag = DDW_PACK_LAG;   // pieces between an exponential and its conversion to bf16
 constexpr float kSlack = 8.0f;          // the maximum in use is raised when exceeded by 2^8
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -68,7 +72,21 @@ __device__ __forceinline__ float half_swap_max(float x)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+    return __uint_as_float(r.x) > __uint_as_float(r.y) ? __uint_as_float(r.x) : __uint_as_float(r.y);
+}
+// Maxima as single instructions: fmaxf() on values the compiler cannot prove canonical (results of inline
+// assembly, lane swaps) costs an extra instruction per operand.
+__device__ __forceinline__ float vmax(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ __forceinline__ float vmax3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
 }
 // S = K Q^T step with the result in architectural VGPRs and the Q fragment read from accumulation VGPRs.
 __device__ __forceinline__ void qk_first(floatx16 &s, const intx4 kf, const intx4 qfrag)
@@ -84,6 +102,14 @@ __device__ __forceinline__ void qk_next(floatx16 &s, const intx4 kf, const intx4
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 template <int N> using I_ = std::integral_constant<int, N>;
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(I_<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
 using T_ = std::true_type;
 using F_ = std::false_type;
 
@@ -105,12 +131,18 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int EXC = NP - MAXC;                   // pieces that carry the 32 exponentials
     constexpr int RD = 3;                            // fragment rings: fetched RD uses (2 RD MFMAs) ahead
     static_assert(2 * NDMA + 1 <= NP, "one tile load per piece");
+    static_assert(16 % (2 * MAXC) == 0, "whole pairs of scores per maximum piece");
     static_assert(KS >= RD && 2 * DC >= RD, "fragment rings are three deep");
     static_assert((4 * DMA_ROWS) % 8 == 0 && DMA_ROWS <= 8, "swizzle phase must not depend on the load index");
 
     __shared__ __attribute__((aligned(4096))) uint4 K0[TKW * CH], K1[TKW * CH];     // [key][chunk ^ (key & 7)]
     __shared__ __attribute__((aligned(4096))) uint4 V0[TKW * CH], V1[TKW * CH];     // [key][chunk ^ ((key % (CH/4)) << 2)]  (row-major, 64-byte granules)
-    __shared__ uint4 QO[kRowsWGWide * CH];           // next tile's Q rows [row][chunk ^ (row & 7)], then O on its way out
+    // Per wave: the next tile's 64 Q rows [row][chunk ^ (row & 7)], later the finished tile's O rows on
+    // their way out, in rows of OPITCH bytes (8 bytes of padding rotate the banks from row to row).
+    constexpr int OPITCH = ROWB + 8;
+    constexpr int QOW = kRowsWave * OPITCH;          // bytes per wave
+    static_assert(QOW % 16 == 0, "wave regions stay 16-byte aligned");
+    __shared__ uint4 QO[4 * QOW / 16];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -149,40 +181,84 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // ---- staging by LDS DMA: load i of this wave moves rows (4i + wave) * DMA_ROWS .. of a tile; lane l
     // lands at chunk position l % CH of row l / CH and therefore fetches the chunk the swizzle maps there.
-    // Both swizzles only depend on the row modulo 4 DMA_ROWS, so the chunk a lane fetches is the same for every load.
+    // Both swizzles only depend on the row modulo 4 DMA_ROWS, so the chunk a lane fetches is the same for
+    // every load, and a tile has the same row pitch in LDS as in memory: load i differs from load 0 by the
+    // same 4096 i bytes on both sides, which is what the instruction's immediate offset adds.  Its range is
+    // +-4 KB, so loads pair up around bases 4 KB and 12 KB into the tile.  All address arithmetic per load
+    // is then scalar.
+    // A tile always holds 64 valid rows: tile T covers rows a(T) = min(64 T, N - 64) .. a(T) + 63, and the
+    // rows before 64 T (already seen in the previous tile, or all of them for a tile past the end) are
+    // masked in the scores.
+    auto lds_addr = [](const void *p) __attribute__((always_inline)) {
+        return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
+    };
     const int dma_row = lane / CH, dma_pos = lane % CH;
     const int dma_row0 = wave * DMA_ROWS + dma_row;                        // row of load 0; load i: + 4 i DMA_ROWS
-    const unsigned dma_koff = (dma_pos ^ (dma_row0 & 7)) * 16;
-    const unsigned dma_voff = (dma_pos ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
-    // one load (index i) of a tile; rows past the last key repeat it (finite stand-ins, masked later)
-    auto dma_one = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int tile, int i) __attribute__((always_inline)) {
-        const int r0 = (i * 4 + wave) * DMA_ROWS;
-        int row0 = dma_row0;
-        asm volatile("" : "+v"(row0));           // keeps the address arithmetic here (not hoisted and spilled)
-        const int row = min(tile * TKW + i * 4 * DMA_ROWS + row0, nkeys - 1);
-        const uint8_t *src = glob + (size_t)((unsigned)row * (unsigned)ROWB + lane_off);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(dst + r0 * CH), 16, 0, 0);
+    const unsigned dma_koff = dma_row0 * ROWB + (dma_pos ^ (dma_row0 & 7)) * 16;
+    const unsigned dma_voff = dma_row0 * ROWB + (dma_pos ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
+    const int last_start = nkeys - TKW;                                    // >= 0: checked by the launcher
+    auto tile_start = [&](int tile) __attribute__((always_inline)) { return min(tile * TKW, last_start); };
+    // one load (index i) of the tile whose first row is at `glob`
+    auto dma_one = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int i) __attribute__((always_inline)) {
+        static_assert(4 * DMA_ROWS * ROWB == 4096, "loads of a wave are 4 KB apart");
+        const int mid = 4096 + 8192 * (i >> 1);
+        const uint8_t *sbase = glob + mid;                                 // uniform: a scalar register pair
+        const unsigned d = lds_addr(dst) + wave * DMA_ROWS * ROWB + mid;
+        // Written as assembly so that the address stays "scalar base + 32-bit lane offset + immediate" (the
+        // compiler prefers to carry a 64-bit address per lane and per load).  It therefore knows nothing of
+        // these loads: every wait for them in this kernel is explicit.
+        if (i & 1)
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(d), "v"(lane_off), "s"(sbase) : "memory", "m0");
+        else
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:-4096" : : "s"(d), "v"(lane_off), "s"(sbase) : "memory", "m0");
     };
-    auto dma_tile = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int tile) __attribute__((always_inline)) {
+    // Wait until at most `pending` of this wave's memory operations are outstanding, then meet the other
+    // waves.  (The barrier by itself is no fence for the compiler: the empty statements keep it from
+    // moving LDS accesses across.)
+    auto wait_loads_and_sync = [&](auto pending) __attribute__((always_inline)) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(waitcnt_vm(decltype(pending)::value));
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    auto dma_tile = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) dma_one(dst, glob, lane_off, tile, i);
+        for (int i = 0; i < NDMA; ++i) dma_one(dst, glob, lane_off, i);
     };
-    // this wave's 64 query rows of a tile -> its quarter of QO (rows past the end repeat the last one)
+    // this wave's 64 query rows of a tile -> its region of QO (rows past the end repeat the last one)
     auto dma_q = [&](const Tile &t) __attribute__((always_inline)) {
-        const uint8_t *qg = static_cast<const uint8_t *>(a.Q) + t.row_base * ROWB;
+        const uint8_t *qg = static_cast<const uint8_t *>(a.Q) + (t.row_base + t.v0 + wave * kRowsWave) * ROWB;
+        const unsigned dst = lds_addr(QO) + wave * QOW;
         // Rarely executed code derives its per-lane values from an opaque copy of the lane number: otherwise
         // they are all computed once at kernel start and occupy registers (or scratch) throughout.
         int ln = lane;
         asm volatile("" : "+v"(ln));
         const int drow = ln / CH, dpos = ln % CH;
+        if (__builtin_expect(t.v0 + kRowsWGWide <= rows_total, 1)) {
+            // whole tile: 1 KB per load, contiguous on both sides - scalar bases 8 KB apart and immediates;
+            // the chunk a lane fetches depends on the row modulo 8, hence on the parity of a 4-row load
+            unsigned off[2];
 #pragma unroll
-        for (int i = 0; i < NQDMA; ++i) {
-            const int r0 = wave * kRowsWave + i * DMA_ROWS;
-            const int row = min(t.v0 + r0 + drow, rows_total - 1);
-            const uint8_t *src = qg + (size_t)((unsigned)row * (unsigned)ROWB + (dpos ^ ((i * DMA_ROWS + drow) & 7)) * 16);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                             (__attribute__((address_space(3))) void *)(QO + r0 * CH), 16, 0, 0);
+            for (int par = 0; par < 2; ++par)
+                off[par] = drow * ROWB + (dpos ^ ((par * DMA_ROWS + drow) & 7)) * 16;
+            static_for<NQDMA>([&](auto ic) __attribute__((always_inline)) {
+                constexpr int i = decltype(ic)::value, mid = 4096 + 8192 * (i / 8), imm = i * 1024 - mid;
+                const uint8_t *sbase = qg + mid;
+                const unsigned d = dst + mid, o = off[(i * DMA_ROWS / 4) & 1];
+                if constexpr (imm >= 0)
+                    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
+                                 : : "s"(d), "v"(o), "s"(sbase), "n"(imm) : "memory", "m0");
+                else
+                    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:-%3"
+                                 : : "s"(d), "v"(o), "s"(sbase), "n"(-imm) : "memory", "m0");
+            });
+        } else {
+#pragma unroll
+            for (int i = 0; i < NQDMA; ++i) {
+                const int row = min(i * DMA_ROWS + drow, rows_total - 1 - t.v0 - wave * kRowsWave);
+                const uint8_t *src = qg + (ptrdiff_t)row * ROWB + (dpos ^ ((i * DMA_ROWS + drow) & 7)) * 16;
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst + i * 1024), "v"(src) : "memory", "m0");
+            }
         }
     };
     auto kbuf = [&](auto p) __attribute__((always_inline)) -> uint4 * { if constexpr (decltype(p)::value == 0) return K0; else return K1; };
@@ -204,7 +280,21 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
     };
     clear_acc();
+    // The same between two row tiles: ten matrix instructions with zero operands instead of 160 register
+    // writes (written as assembly: the results stay in accumulation VGPRs and are next read, as the addend
+    // of a matrix instruction, a whole step later).
+    auto clear_acc_mfma = [&]() __attribute__((always_inline)) {
+        intx4 z = {0, 0, 0, 0};
+        asm volatile("s_nop 3" : "+v"(z));                   // the zeros are in place before a matrix instruction reads them
+#pragma unroll
+        for (int q = 0; q < QB; ++q) {
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc_l[q]) : "v"(z));
+#pragma unroll
+            for (int i = 0; i < DC; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[q][i]) : "v"(z));
+        }
+    };
     float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
+    float thr[QB] = {-INFINITY, -INFINITY};          // raw scores above (mc + slack) / c raise the maximum in use
     intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
 
@@ -246,7 +336,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 // addresses derived from the opaque lane copy: see dma_q
                 const int lo = ((ln & 31) * CH + ((2 * ks + (ln >> 5)) ^ (ln & 7))) * 16;
                 qf[q][ks] = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
-                                reinterpret_cast<const char *>(QO) + (wave * kRowsWave + q * 32) * ROWB + lo));
+                                reinterpret_cast<const char *>(QO) + wave * QOW + q * 32 * ROWB + lo));
                 asm volatile("" : "+a"(qf[q][ks]));
             }
             const int v = min(t.v0 + wave * kRowsWave + q * 32 + (ln & 31), rows_total - 1);
@@ -258,39 +348,62 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // keep them clear of the register writes above
         asm volatile("s_nop 15" : "+a"(qf[0][0]), "+a"(qf[QB - 1][KS - 1]));
     };
-    // Finished tile: normalise, transpose through this wave's quarter of QO, write whole rows.
-    // O^T register r of chunk i holds dim 32 i + 8 (r / 4) + 4 hh + (r % 4) of query row l32 of its block.
+    // Finished tile: normalise, transpose through this wave's region of QO, write whole rows.
+    // O^T register r of chunk i holds dim 32 i + 8 (r / 4) + 4 hh + (r % 4) of query row l32 of its block:
+    // four consecutive dims = one 8-byte slot (i * 8 + (r / 4) * 2 + hh) of the row.  All addresses are one
+    // per-lane base plus constants.
     auto write_out = [&](const Tile &t) __attribute__((always_inline)) {
-        constexpr int SL = D / 4;                                          // 8-byte slots per row
-        char *region = reinterpret_cast<char *>(QO) + wave * kRowsWave * ROWB;
+        char *region = reinterpret_cast<char *>(QO) + wave * QOW;
         int ln = lane;
         asm volatile("" : "+v"(ln));
-        const int hh = ln >> 5;
+        char *wbase = region + (ln & 31) * OPITCH + (ln >> 5) * 8;
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            const float inv = 1.0f / acc_l[q][0];
-            const int row = q * 32 + (ln & 31);
+            const float inv = __builtin_amdgcn_rcpf(acc_l[q][0]);         // 1 ulp; the result is rounded to bf16
 #pragma unroll
             for (int i = 0; i < DC; ++i)
 #pragma unroll
                 for (int q4 = 0; q4 < 4; ++q4) {
                     const uint2 w = make_uint2(pack_bf16_rne(acc[q][i][4 * q4] * inv, acc[q][i][4 * q4 + 1] * inv),
                                                pack_bf16_rne(acc[q][i][4 * q4 + 2] * inv, acc[q][i][4 * q4 + 3] * inv));
-                    const int slot = i * 8 + q4 * 2 + hh;
-                    *reinterpret_cast<uint2 *>(region + row * ROWB + (slot ^ ((row & (SL / 2 - 1)) << 1)) * 8) = w;
+                    *reinterpret_cast<uint2 *>(wbase + q * 32 * OPITCH + (i * 8 + q4 * 2) * 8) = w;
                 }
         }
-        uint8_t *og = static_cast<uint8_t *>(a.O) + t.row_base * ROWB;
         constexpr int LPR = ROWB / 16, RPI = 64 / LPR;                     // lanes per row, rows per store
+        const int row0 = ln / LPR, ch = ln % LPR;
+        const char *rbase = region + row0 * OPITCH + ch * 16;
+        const int v_first = t.v0 + wave * kRowsWave;                       // virtual row of the wave's row 0
+        uint8_t *og = static_cast<uint8_t *>(a.O) + (t.row_base + v_first) * ROWB;      // uniform
+        const unsigned goff = row0 * ROWB + ch * 16;
+        const bool whole = v_first + kRowsWave <= rows_total;              // uniform
+        auto staged = [&](int it) __attribute__((always_inline)) {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(rbase + it * RPI * OPITCH);
+            const uint2 hi = *reinterpret_cast<const uint2 *>(rbase + it * RPI * OPITCH + 8);
+            return make_uint4(lo.x, lo.y, hi.x, hi.y);
+        };
+        constexpr int NIT = kRowsWave / RPI, BATCH = 8;
+        if (__builtin_expect(whole, 1)) {
+            // reads in batches, so that their latencies overlap instead of adding up
 #pragma unroll
-        for (int it = 0; it < kRowsWave / RPI; ++it) {
-            const int row = it * RPI + ln / LPR, ch = ln % LPR;
-            const uint4 w = *reinterpret_cast<const uint4 *>(region + row * ROWB + (ch ^ (row & (SL / 2 - 1))) * 16);
-            const int v = t.v0 + wave * kRowsWave + row;
-            if (v < rows_total) *reinterpret_cast<uint4 *>(og + (size_t)v * ROWB + ch * 16) = w;
+            for (int b = 0; b < NIT; b += BATCH) {
+                uint4 w[BATCH];
+#pragma unroll
+                for (int k = 0; k < BATCH; ++k) w[k] = staged(b + k);
+#pragma unroll
+                for (int k = 0; k < BATCH; ++k) *reinterpret_cast<uint4 *>(og + (b + k) * RPI * ROWB + goff) = w[k];
+            }
+        } else {
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const uint4 w = staged(it);
+                if (v_first + it * RPI + row0 < rows_total) *reinterpret_cast<uint4 *>(og + it * RPI * ROWB + goff) = w;
+            }
         }
     };
 
+#ifdef DDW_TIMING2
+    unsigned long long tfine[4] = {0, 0, 0, 0};      // waiting for Q, installing Q, writing out, the last barrier
+#endif
     intx4 kfr[RD];
     bf16x8 vfr[RD];
     // Pipeline step.  In: s_cur = S(u), pk_prev = P(u-1).  Out: pk_cur = P(u), s_nxt = S(u+1).
@@ -299,13 +412,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // stand-in rows and masked to -inf, so they contribute exact zeros; P(-1) is zero.
     // `chain`: the next step reads unit 1 of the same tile buffers, so its first K fragments are fetched
     // in this step's last pieces; `primed`: the previous step did that for this one.
-    // `dma`: this step also issues the tile loads of its stage (K tile into dk, V tile into dv).
+    // `dma`: this step also issues the tile loads of its stage (the K tile at kg into dk, the V tile at vg into dv).
     // `fin` (run time, only looked at when `can_finish`): S(u) is the first score block of the NEXT row
     // tile and this step's products are the last of the current one, which is then written out.
     auto step = [&](int u, floatx16 (&s_cur)[QB], floatx16 (&s_nxt)[QB], unsigned (&pk_prev)[QB][2][4],
                     unsigned (&pk_cur)[QB][2][4], const uint4 *kb, int ksub, const uint4 *vb, int vsub,
-                    auto primed, auto chain, auto dma, uint4 *dk, const uint8_t *kg, int ktile,
-                    uint4 *dv, const uint8_t *vg, int vtile, auto can_finish, bool fin, const Tile &cur)
+                    auto primed, auto chain, auto dma, uint4 *dk, const uint8_t *kg,
+                    uint4 *dv, const uint8_t *vg, auto can_finish, bool fin, const Tile &cur)
                     __attribute__((always_inline)) {
         constexpr bool PRIMED = decltype(primed)::value, CHAIN = decltype(chain)::value;
         constexpr bool DMA = decltype(dma)::value, CANFIN = decltype(can_finish)::value;
@@ -313,16 +426,18 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
-        if (__builtin_expect(32 * (u + 1) > nkeys, 0)) {     // uniform branch: keys at or past the end score -inf
-            int k0 = 32 * u + 4 * hh;
+        // rows of unit u's tile that lie before its nominal start repeat keys of the previous tile
+        const int lim = (u >> 1) * TKW - tile_start(u >> 1) - 32 * (u & 1);
+        if (__builtin_expect(lim > 0, 0)) {                  // uniform branch: those score -inf
+            int k0 = 4 * hh;
             asm volatile("" : "+v"(k0));
 #pragma unroll
             for (int q = 0; q < QB; ++q)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
-                    if (k0 + 8 * (r >> 2) + (r & 3) >= nkeys) s_cur[q][r] = -INFINITY;
+                    if (k0 + 8 * (r >> 2) + (r & 3) < lim) s_cur[q][r] = -INFINITY;
         }
-        float corr[QB], tm[QB], tpart[QB], pe[32];
+        float corr[QB], tpart[QB], pe[32];
         bool changed = false;
         // element e = 2 pr + (0/1) of the exponential stream is S(u)[q = pr & 1][r = 2 (pr >> 1) + (0/1)]
         auto exp_piece = [](int e) constexpr { int t = MAXC; while (!(e < 32 * (t - MAXC + 1) / EXC)) ++t; return t; };
@@ -335,29 +450,29 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // everything of the step that is not an MFMA, dealt out over the NP pieces
         auto piece = [&](int t) __attribute__((always_inline)) {
             if (DMA && t >= 1 && t <= 2 * NDMA) {
-                if (t <= NDMA) dma_one(dk, kg, dma_koff, ktile, t - 1);
-                else dma_one(dv, vg, dma_voff, vtile, t - 1 - NDMA);
+                if (t <= NDMA) dma_one(dk, kg, dma_koff, t - 1);
+                else dma_one(dv, vg, dma_voff, t - 1 - NDMA);
             }
             if (t < MAXC) {
                 // row maxima of S(u) decide, without a divergent branch, whether the maxima in use are raised
 #pragma unroll
-                for (int v = 32 * t / MAXC; v < 32 * (t + 1) / MAXC; ++v) {
-                    const int q = v >> 4, r = v & 15;
-                    tpart[q] = r == 0 ? s_cur[q][0] : fmaxf(tpart[q], s_cur[q][r]);
-                }
+                for (int r = 16 * t / MAXC; r < 16 * (t + 1) / MAXC; r += 2)
+#pragma unroll
+                    for (int q = 0; q < QB; ++q)             // alternating blocks: no back-to-back dependence
+                        tpart[q] = r == 0 ? vmax(s_cur[q][0], s_cur[q][1]) : vmax3(tpart[q], s_cur[q][r], s_cur[q][r + 1]);
                 if (t == MAXC - 1) {
-                    bool need = false;
+                    // Each lane half compares the maximum of its own keys with the threshold; whether any
+                    // lane is above it is wave-uniform (always true for the first unit of a row tile).
+                    changed = (__builtin_amdgcn_ballot_w64(tpart[0] > thr[0]) | __builtin_amdgcn_ballot_w64(tpart[1] > thr[1])) != 0;
+                    if (__builtin_expect(changed, 0)) {      // rare: raise the maxima in use
 #pragma unroll
-                    for (int q = 0; q < QB; ++q) {
-                        tm[q] = half_swap_max(tpart[q]) * c[q];
-                        need = need || (tm[q] > mc[q] + kSlack);
-                    }
-                    changed = __any(need);                   // wave-uniform; always true for the first unit
-#pragma unroll
-                    for (int q = 0; q < QB; ++q) {
-                        const float mn = changed ? fmaxf(mc[q], tm[q]) : mc[q];
-                        corr[q] = fast_exp2(mc[q] - mn);     // first unit: 2^(-inf) = 0
-                        mc[q] = mn;
+                        for (int q = 0; q < QB; ++q) {
+                            const float tmq = half_swap_max(tpart[q]) * c[q];
+                            const float mn = tmq > mc[q] ? tmq : mc[q];
+                            corr[q] = fast_exp2(mc[q] - mn); // first unit: 2^(-inf) = 0
+                            mc[q] = mn;
+                            thr[q] = (mn + kSlack) / c[q];
+                        }
                     }
                 }
             } else {
@@ -371,7 +486,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
             // consumed by the very next instruction without a bubble
 #pragma unroll
             for (int pr = 0; pr < 16; ++pr)
-                if (exp_piece(2 * pr + 1) == t - 1) pack_pair(pr);
+                if (exp_piece(2 * pr + 1) == t - kPackLag) pack_pair(pr);
             __builtin_amdgcn_sched_barrier(0);               // nothing moves between pieces
         };
         // ---- S(u+1): the first V fragments are fetched meanwhile
@@ -414,10 +529,16 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr)
-            if (exp_piece(2 * pr + 1) == NP - 1) pack_pair(pr);
+            if (exp_piece(2 * pr + 1) >= NP - kPackLag) pack_pair(pr);
         if (CANFIN && fin) {                                 // uniform: the row tile is complete
+#ifdef DDW_TIMING2
+            const unsigned long long ta = __builtin_readcyclecounter();
+#endif
             write_out(cur);
-            clear_acc();
+            clear_acc_mfma();
+#ifdef DDW_TIMING2
+            tfine[2] += __builtin_readcyclecounter() - ta;
+#endif
         } else if (__builtin_expect(changed, 0)) {           // rare: everything accumulated so far changes units
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
@@ -453,47 +574,52 @@ void attn_wide_kernel(const AttnKernelArgs a)
         constexpr bool last = KIND == 2;
         if (last && has_next) {
             // the Q rows were requested a stage ago and deliberately not waited for at its barrier
+#ifdef DDW_TIMING2
+            const unsigned long long ta = __builtin_readcyclecounter();
+#endif
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+#ifdef DDW_TIMING2
+            const unsigned long long tb = __builtin_readcyclecounter();
+#endif
             install_q(nxt);
+#ifdef DDW_TIMING2
+            tfine[0] += tb - ta; tfine[1] += __builtin_readcyclecounter() - tb;
+#endif
         }
+        const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
-             kbuf(I_<PAR>{}), KIND == 0 ? cur.k : nxt.k, KIND == 0 ? sp + 2 : KIND - 1,
-             vbuf(I_<1 - PAR>{}), last ? nxt.v : cur.v, last ? 0 : sp + 1, F_{}, false, cur);
+             kbuf(I_<PAR>{}), (KIND == 0 ? cur.k : nxt.k) + (size_t)tile_start(ktile) * ROWB,
+             vbuf(I_<1 - PAR>{}), (last ? nxt.v : cur.v) + (size_t)tile_start(vtile) * ROWB, F_{}, false, cur);
         if (KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
-            mc[0] = -INFINITY;                               // the second step starts the next tile's softmax
-            mc[1] = -INFINITY;
+            mc[0] = mc[1] = -INFINITY;                       // the second step starts the next tile's softmax
+            thr[0] = thr[1] = -INFINITY;
         }
         step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
-             kbuf(I_<PAR>{}), cur.k, 0, vbuf(I_<1 - PAR>{}), cur.v, 0, std::integral_constant<bool, last>{}, last, cur);
+             kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur);
         // The barrier that ends a stage waits for the stage's tile loads.  Memory operations complete in
         // order, so the requests issued after those loads - the next tile's Q rows, the finished tile's
         // output rows - can stay in flight: wait until only that many are outstanding.
         constexpr int NST = kRowsWave / (64 / (ROWB / 16));  // output stores per wave
-        // (An explicit s_waitcnt builtin is understood by the compiler's own wait insertion, which then does
-        // not add a full wait before the next LDS read; the empty asm statements keep it from moving
-        // memory accesses across the barrier, which by itself is not a fence.)
-        if (KIND == 1 && has_next) {
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NQDMA));
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        } else if (last && cur.v0 + kRowsWGWide <= rows_total) {
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_waitcnt(waitcnt_vm(NST));
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-        } else {
-            __syncthreads();
+        if (KIND == 1 && has_next) wait_loads_and_sync(I_<NQDMA>{});
+        else if (last && cur.v0 + kRowsWGWide <= rows_total) {
+#ifdef DDW_TIMING2
+            const unsigned long long ta = __builtin_readcyclecounter();
+#endif
+            wait_loads_and_sync(I_<NST>{});
+#ifdef DDW_TIMING2
+            tfine[3] += __builtin_readcyclecounter() - ta;
+#endif
         }
+        else wait_loads_and_sync(I_<0>{});
     };
 
     // ---- prologue of the first row tile: Q rows and K tiles 0, 1 and V tile 0 go straight to LDS
     dma_q(cur);
-    dma_tile(K0, cur.k, dma_koff, 0);
-    dma_tile(V0, cur.v, dma_voff, 0);
-    dma_tile(K1, cur.k, dma_koff, 1);
-    __syncthreads();
+    dma_tile(K0, cur.k, dma_koff);
+    dma_tile(V0, cur.v, dma_voff);
+    dma_tile(K1, cur.k + (size_t)tile_start(1) * ROWB, dma_koff);
+    wait_loads_and_sync(I_<0>{});
     install_q(cur);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
@@ -509,7 +635,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, 0, V0, cur.v, 0, F_{}, false, cur);
+    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur);
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
 
     // ---- passes: stages 0 .. nt_even-1 = steps 1 .. 2 nt_even; the product with P(u) happens in step u+1,
@@ -550,6 +676,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         unsigned long long *dbg = reinterpret_cast<unsigned long long *>(const_cast<float *>(a.q_scale)) + blockIdx.x * 8;
         dbg[0] = tacc[0]; dbg[1] = tacc[1]; dbg[2] = tacc[2];
         dbg[3] = __builtin_readcyclecounter() - t_loop; dbg[4] = t_loop - t_kernel;
+        unsigned long long *fine = reinterpret_cast<unsigned long long *>(const_cast<float *>(a.q_scale)) + 256 * 8 + blockIdx.x * 4;
+        for (int i = 0; i < 4; ++i) fine[i] = tfine[i];
     }
 #endif
 }
@@ -558,6 +686,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
 hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
 {
+    if (a.N < TKW) return hipErrorInvalidValue;            // a K/V tile is 64 whole rows
     AttnKernelArgs k;
     fill_kernel_args(a, k, kRowsWGWide, TKW);
     static int cus = 0;

@@ -120,8 +120,11 @@ def test_cfg5_bidir_full_size():
 # The bf16 verifier call has two kernels (128-row workgroups with two waves per SIMD; 256-row workgroups with
 # one 64-row wave per SIMD); the library picks by problem size and DD_TUNE_ATTN_WIDE forces the choice.
 WIDE = [
-    # (B, H, Hkv, N, d): one key, ragged tails, odd tile counts, GQA groups that straddle 256-row tiles, idle waves
-    (1, 1, 1, 1, 128), (1, 2, 1, 64, 128), (1, 2, 2, 33, 64), (2, 4, 2, 200, 128), (1, 4, 1, 257, 64),
+    # (B, H, Hkv, N, d): the smallest N the wide kernel takes (one 64-key tile; shorter calls stay on the
+    # other kernel, which the first two shapes check), last tiles that overlap the one before by 1 .. 63 keys,
+    # odd tile counts, GQA groups that straddle 256-row tiles, idle waves
+    (1, 1, 1, 1, 128), (1, 2, 2, 33, 64), (1, 2, 1, 64, 128), (1, 2, 1, 65, 128), (1, 4, 2, 100, 64),
+    (1, 2, 1, 127, 64), (1, 2, 1, 191, 128), (1, 2, 1, 193, 128), (2, 4, 2, 200, 128), (1, 4, 1, 257, 64),
     (1, 2, 2, 1000, 128), (1, 3, 1, 130, 64), (1, 8, 2, 200, 128), (2, 6, 6, 300, 128), (1, 12, 4, 70, 64),
 ]
 
