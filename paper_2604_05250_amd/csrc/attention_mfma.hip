@@ -526,6 +526,12 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
         bool wide = tiles >= 192 && a.N >= 512;
         if (const char *e = getenv("DD_TUNE_ATTN_WIDE")) wide = e[0] == '1';
         if (wide && a.N >= 64) return launch_attention_wide(a, stream);   // its K/V tiles are 64 whole rows
+        // A small call leaves most compute units idle with 128-row workgroups: the streaming kernel's
+        // 64-row workgroups (two row blocks x two key phases) spread it over more of them.
+        // DD_TUNE_BIDIR_STREAM=0/1 forces the choice.
+        bool small = blocks < 256;
+        if (const char *e = getenv("DD_TUNE_BIDIR_STREAM")) small = e[0] == '1';
+        if (small) return launch_attention_stream(a, stream);
     }
     if (blk && !fp8 && a.Nq != a.N && attn_stream_fits(a)) {
         // The drafter's call is bound by streaming K/V once: a kernel built around the memory pipeline

@@ -53,8 +53,15 @@ SMALL = [
 ]
 
 
+# A bf16 call that is too small for the wide kernel goes to the streaming kernel (64-row workgroups) when it
+# would leave compute units idle, else to the MFMA kernel with 128-row workgroups; DD_TUNE_BIDIR_STREAM forces it.
+@pytest.mark.parametrize("stream", ["0", "1"])
 @pytest.mark.parametrize("B,H,Hkv,N,d,qk", SMALL)
-def test_bidir_small_shapes(B, H, Hkv, N, d, qk):
+def test_bidir_small_shapes(monkeypatch, B, H, Hkv, N, d, qk, stream):
+    if qk != wl.BF16 and stream == "1":
+        pytest.skip("only bf16 calls have the choice")
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", "0")
+    monkeypatch.setenv("DD_TUNE_BIDIR_STREAM", stream)
     vd = wl.F32 if qk == wl.F32 else wl.BF16
     cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=vd, prompt=0, G=N, bl=min(16, N))
     inp = wl.attention_inputs(cfg, seed=N)
@@ -147,15 +154,17 @@ def test_bidir_wide_kernel_small_shapes(monkeypatch, B, H, Hkv, N, d, grid):
     assert_attention_close(got, ref, wl.BF16, f"wide kernel {B}x{H}/{Hkv}x{N}x{d}")
 
 
-@pytest.mark.parametrize("wide", ["0", "1"])
-def test_cfg3_bidir_each_kernel(monkeypatch, wide):
+@pytest.mark.parametrize("wide,stream", [("1", "0"), ("0", "0"), ("0", "1")])
+def test_cfg3_bidir_each_kernel(monkeypatch, wide, stream):
     monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    monkeypatch.setenv("DD_TUNE_BIDIR_STREAM", stream)
     _bidir_full_size(3, 192)
 
 
-@pytest.mark.parametrize("wide", ["0", "1"])
-def test_cfg2_bidir_each_kernel(monkeypatch, wide):
+@pytest.mark.parametrize("wide,stream", [("1", "0"), ("0", "0"), ("0", "1")])
+def test_cfg2_bidir_each_kernel(monkeypatch, wide, stream):
     monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    monkeypatch.setenv("DD_TUNE_BIDIR_STREAM", stream)
     _bidir_full_size(2, 0, full=True)
 
 
