@@ -7,13 +7,16 @@
 // one workgroup = 4 waves = 256 query rows of one (batch, kv head).  Every K fragment and every V
 // fragment read from LDS feeds two MFMAs (one per block): half the LDS bytes per FLOP.
 //
-// A single wave per SIMD has no other wave to overlap with, and a wave issues in order: a matrix
-// instruction only overlaps with the vector instructions that directly follow it.  Each pipeline step
-// (one 32-key unit u) is therefore a fixed sequence of "pieces" = one MFMA + its share of everything else:
+// A single wave per SIMD has no other wave to overlap with, and a wave issues in order, one instruction
+// per ~4 cycles whatever its kind: a matrix instruction (32 cycles of matrix-core time) only overlaps with
+// the handful of instructions that directly follow it.  Each pipeline step (one 32-key unit u) is therefore
+// a fixed sequence of "pieces" = one MFMA + its share of everything else, and what counts is the number of
+// instructions per piece:
 //     matrix cores   S(u+1) = K(u+1) Q^T,   O^T += V(u-1)^T P(u-1)^T,   l += 1^T P(u-1)^T (row sums)
 //     vector ALUs    row maxima of S(u), then P(u) = 2^(S(u) c - m), packed to bf16
-//     memory         LDS fragment reads two MFMAs ahead, one global->LDS tile load per piece
-// The maximum in use is raised (accumulators rescaled) in a rare branch at the end of a step.
+//     memory         LDS fragment reads three uses ahead, one global->LDS tile load per piece
+// Whether a score exceeds the maximum in use (by more than 2^8) is one comparison per row block against a
+// threshold in raw score units; raising the maximum and rescaling the accumulators are rare branches.
 //
 // Register files.  S lives in architectural VGPRs (the vector ALUs cannot read accumulation VGPRs and a
 // copy costs as much as two FMAs and does not overlap with the matrix cores); O, the row sums and the Q
@@ -29,12 +32,19 @@
 // prefetched into LDS one stage earlier; the finished tile is normalised, transposed through the same
 // LDS region and written out in full rows.
 //
-// Staging.  K and V tiles (64 keys) are double-buffered in four separate LDS arrays and filled by
-// global_load_lds_dwordx4 (no registers, no LDS store instructions); the arrays are distinct objects and
-// selected statically, so the compiler only waits for those loads at the barrier that ends a stage.
+// Staging.  K and V tiles (64 keys) are double-buffered in four LDS arrays and filled by
+// global_load_lds_dwordx4 (no registers, no LDS store instructions).  A tile always holds 64 whole rows -
+// the last one of a pass overlaps its predecessor and the repeated keys score -inf - so a load's address is
+// "scalar tile base + constant lane offset + immediate" with no vector arithmetic; the loads are written
+// as assembly to keep that form, and every wait for them is explicit (only the barrier that ends a stage
+// waits, and it lets the requests issued after the tile loads stay in flight).
 // K is XOR-swizzled for its 16-byte operand reads; V stays row-major (swizzled in 64-byte granules) and
 // its transposed operand comes from ds_read_b64_tr_b16 (lane j of a 16-lane group receives column j of
 // the 4-row x 16-column block whose row r is addressed by lanes 4r..4r+3).
+//
+// Measured on MI355X: with realistic operand data the matrix cores are power-limited (a register-only
+// MFMA loop runs at about 1.65 GHz and 1.75 PFLOP/s on all 256 CUs, against 2.2 GHz with constant
+// operands), and so is this kernel: instructions removed from the pieces come back partly as a lower clock.
 #include "attention_common.h"
 #include "dd_internal.h"
 
