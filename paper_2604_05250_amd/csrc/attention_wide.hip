@@ -60,6 +60,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
 
 constexpr int TKW = 64;                 // keys per tile
 constexpr int QB = 2;                   // 32-row query blocks per wave
@@ -75,6 +76,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ unsigned pack_bf16_rne(float lo, float hi)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
     floatx2 f = {lo, hi};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
 }
@@ -99,13 +101,18 @@ __device__ __forceinline__ float vmax3(float a, float b, float c)
     return r;
 }
 // S = K Q^T step with the result in architectural VGPRs and the Q fragment read from accumulation VGPRs.
-__device__ __forceinline__ void qk_first(floatx16 &s, const intx4 kf, const intx4 qfrag)
+// bf16: 8 values per lane and operand (16 bytes); fp8 e4m3: 8 values in 8 bytes.  Same shape, same layout.
+template <bool FP8, typename KT, typename QT>
+__device__ __forceinline__ void qk_first(floatx16 &s, const KT kf, const QT qfrag)
 {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
+    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x16_fp8_fp8 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
 }
-__device__ __forceinline__ void qk_next(floatx16 &s, const intx4 kf, const intx4 qfrag)
+template <bool FP8, typename KT, typename QT>
+__device__ __forceinline__ void qk_next(floatx16 &s, const KT kf, const QT qfrag)
 {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
+    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x16_fp8_fp8 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
 }
 
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
@@ -123,29 +130,37 @@ __device__ __forceinline__ void static_for(F &&f)
 using T_ = std::true_type;
 using F_ = std::false_type;
 
-template <int D>
+// FP8: Q and K are fp8 e4m3 (with per-head scales folded into the exponent's factor), V and O bf16.
+template <int D, bool FP8>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_wide_kernel(const AttnKernelArgs a)
 {
-    constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per row
+    constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per V / O row
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
-    constexpr int ROWB = D * 2;                      // bytes per Q / K / V / O row
-    constexpr int DMA_ROWS = 1024 / ROWB;            // rows moved by one wave-wide 16-byte-per-lane load
-    constexpr int NDMA = TKW / DMA_ROWS / 4;         // such loads per wave per K or V tile
-    constexpr int NQDMA = kRowsWave / DMA_ROWS;      // ... per wave for its Q rows
+    constexpr int ROWB = D * 2;                      // bytes per V / O row
+    constexpr int KROWB = FP8 ? D : 2 * D;           // bytes per Q / K row
+    constexpr int KCH = KROWB / 16;                  // 16-byte chunks per Q / K row
+    constexpr int KF = KROWB / 32;                   // 16-byte fragments per lane and Q / K row, each feeding ...
+    constexpr int MPF = KS / KF;                     // ... this many MFMAs (bf16 1, fp8 2)
+    constexpr int DMA_ROWS = 1024 / ROWB;            // rows moved by one wave-wide 16-byte-per-lane load (V)
+    constexpr int KDMA_ROWS = 1024 / KROWB;          // ... (Q, K)
+    constexpr int NDMA = TKW / DMA_ROWS / 4;         // such loads per wave per V tile
+    constexpr int NDMA_K = TKW / KDMA_ROWS / 4;      // ... per K tile
+    constexpr int NQDMA = kRowsWave / KDMA_ROWS;     // ... per wave for its Q rows
     constexpr int NQK = KS * QB;                     // pieces of a step: S(u+1) ...
     constexpr int NPV = 2 * DC * QB;                 // ... O += V P ...
     constexpr int NP = NQK + NPV + 2 * QB;           // ... and the row sums
     constexpr int MAXC = NP >= 32 ? 8 : 4;           // pieces that carry the row maxima
     constexpr int EXC = NP - MAXC;                   // pieces that carry the 32 exponentials
     constexpr int RD = 3;                            // fragment rings: fetched RD uses (2 RD MFMAs) ahead
-    static_assert(2 * NDMA + 1 <= NP, "one tile load per piece");
+    static_assert(NDMA_K + NDMA + 1 <= NP, "one tile load per piece");
     static_assert(16 % (2 * MAXC) == 0, "whole pairs of scores per maximum piece");
-    static_assert(KS >= RD && 2 * DC >= RD, "fragment rings are three deep");
+    static_assert(KF >= RD && 2 * DC >= RD, "fragment rings are three deep");
     static_assert((4 * DMA_ROWS) % 8 == 0 && DMA_ROWS <= 8, "swizzle phase must not depend on the load index");
+    static_assert((4 * KDMA_ROWS) % 8 == 0 && KDMA_ROWS <= 8, "swizzle phase must not depend on the load index");
 
-    __shared__ __attribute__((aligned(4096))) uint4 K0[TKW * CH], K1[TKW * CH];     // [key][chunk ^ (key & 7)]
+    __shared__ __attribute__((aligned(4096))) uint4 K0[TKW * KCH], K1[TKW * KCH];   // [key][chunk ^ (key & 7)]
     __shared__ __attribute__((aligned(4096))) uint4 V0[TKW * CH], V1[TKW * CH];     // [key][chunk ^ ((key % (CH/4)) << 2)]  (row-major, 64-byte granules)
     // Per wave: the next tile's 64 Q rows [row][chunk ^ (row & 7)], later the finished tile's O rows on
     // their way out, in rows of OPITCH bytes (8 bytes of padding rotate the banks from row to row).
@@ -180,7 +195,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto tile_of = [&](int t) __attribute__((always_inline)) {
         const int rt = t % a.row_tiles, bk = t / a.row_tiles, kvh = bk % a.Hkv, b = bk / a.Hkv;
         Tile r;
-        r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.N * (size_t)ROWB;
+        r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.N * (size_t)KROWB;
         r.v = static_cast<const uint8_t *>(a.V) + (size_t)bk * a.N * (size_t)ROWB;
         r.bh0 = b * a.H + kvh * a.group;             // first query head of the group
         r.row_base = (size_t)r.bh0 * a.Nq;           // row of virtual row 0 in Q and O
@@ -202,18 +217,18 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto lds_addr = [](const void *p) __attribute__((always_inline)) {
         return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
     };
-    const int dma_row = lane / CH, dma_pos = lane % CH;
-    const int dma_row0 = wave * DMA_ROWS + dma_row;                        // row of load 0; load i: + 4 i DMA_ROWS
-    const unsigned dma_koff = dma_row0 * ROWB + (dma_pos ^ (dma_row0 & 7)) * 16;
-    const unsigned dma_voff = dma_row0 * ROWB + (dma_pos ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
+    const int dma_row0 = wave * DMA_ROWS + lane / CH;                      // row of load 0; load i: + 4 i DMA_ROWS
+    const int dma_krow0 = wave * KDMA_ROWS + lane / KCH;
+    const unsigned dma_koff = dma_krow0 * KROWB + ((lane % KCH) ^ (dma_krow0 & 7)) * 16;
+    const unsigned dma_voff = dma_row0 * ROWB + ((lane % CH) ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
     const int last_start = nkeys - TKW;                                    // >= 0: checked by the launcher
     auto tile_start = [&](int tile) __attribute__((always_inline)) { return min(tile * TKW, last_start); };
     // one load (index i) of the tile whose first row is at `glob`
     auto dma_one = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int i) __attribute__((always_inline)) {
-        static_assert(4 * DMA_ROWS * ROWB == 4096, "loads of a wave are 4 KB apart");
+        static_assert(4 * DMA_ROWS * ROWB == 4096 && 4 * KDMA_ROWS * KROWB == 4096, "loads of a wave are 4 KB apart");
         const int mid = 4096 + 8192 * (i >> 1);
         const uint8_t *sbase = glob + mid;                                 // uniform: a scalar register pair
-        const unsigned d = lds_addr(dst) + wave * DMA_ROWS * ROWB + mid;
+        const unsigned d = lds_addr(dst) + wave * 1024 + mid;
         // Written as assembly so that the address stays "scalar base + 32-bit lane offset + immediate" (the
         // compiler prefers to carry a 64-bit address per lane and per load).  It therefore knows nothing of
         // these loads: every wait for them in this kernel is explicit.
@@ -231,30 +246,30 @@ void attn_wide_kernel(const AttnKernelArgs a)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
-    auto dma_tile = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off) __attribute__((always_inline)) {
+    auto dma_tile = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, auto n) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NDMA; ++i) dma_one(dst, glob, lane_off, i);
+        for (int i = 0; i < decltype(n)::value; ++i) dma_one(dst, glob, lane_off, i);
     };
     // this wave's 64 query rows of a tile -> its region of QO (rows past the end repeat the last one)
     auto dma_q = [&](const Tile &t) __attribute__((always_inline)) {
-        const uint8_t *qg = static_cast<const uint8_t *>(a.Q) + (t.row_base + t.v0 + wave * kRowsWave) * ROWB;
+        const uint8_t *qg = static_cast<const uint8_t *>(a.Q) + (t.row_base + t.v0 + wave * kRowsWave) * KROWB;
         const unsigned dst = lds_addr(QO) + wave * QOW;
         // Rarely executed code derives its per-lane values from an opaque copy of the lane number: otherwise
         // they are all computed once at kernel start and occupy registers (or scratch) throughout.
         int ln = lane;
         asm volatile("" : "+v"(ln));
-        const int drow = ln / CH, dpos = ln % CH;
+        const int drow = ln / KCH, dpos = ln % KCH;
         if (__builtin_expect(t.v0 + kRowsWGWide <= rows_total, 1)) {
             // whole tile: 1 KB per load, contiguous on both sides - scalar bases 8 KB apart and immediates;
             // the chunk a lane fetches depends on the row modulo 8, hence on the parity of a 4-row load
             unsigned off[2];
 #pragma unroll
             for (int par = 0; par < 2; ++par)
-                off[par] = drow * ROWB + (dpos ^ ((par * DMA_ROWS + drow) & 7)) * 16;
+                off[par] = drow * KROWB + (dpos ^ ((par * KDMA_ROWS + drow) & 7)) * 16;
             static_for<NQDMA>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value, mid = 4096 + 8192 * (i / 8), imm = i * 1024 - mid;
                 const uint8_t *sbase = qg + mid;
-                const unsigned d = dst + mid, o = off[(i * DMA_ROWS / 4) & 1];
+                const unsigned d = dst + mid, o = off[(i * KDMA_ROWS / 4) & 1];
                 if constexpr (imm >= 0)
                     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
                                  : : "s"(d), "v"(o), "s"(sbase), "n"(imm) : "memory", "m0");
@@ -265,8 +280,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         } else {
 #pragma unroll
             for (int i = 0; i < NQDMA; ++i) {
-                const int row = min(i * DMA_ROWS + drow, rows_total - 1 - t.v0 - wave * kRowsWave);
-                const uint8_t *src = qg + (ptrdiff_t)row * ROWB + (dpos ^ ((i * DMA_ROWS + drow) & 7)) * 16;
+                const int row = min(i * KDMA_ROWS + drow, rows_total - 1 - t.v0 - wave * kRowsWave);
+                const uint8_t *src = qg + (ptrdiff_t)row * KROWB + (dpos ^ ((i * KDMA_ROWS + drow) & 7)) * 16;
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(dst + i * 1024), "v"(src) : "memory", "m0");
             }
         }
@@ -275,8 +290,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto vbuf = [&](auto p) __attribute__((always_inline)) -> uint4 * { if constexpr (decltype(p)::value == 0) return V0; else return V1; };
 
     // ---- per-lane state of the two query blocks
-    float c[QB];                                     // scores are exponentiated as 2^(s*c)
-    intx4 qf[QB][KS];                                // B operand of S^T = K Q^T (8 bf16), kept in accumulation VGPRs
+    float c[QB], c_next[QB];                         // scores are exponentiated as 2^(s*c); the next row tile's factor
+    using qfrag_t = std::conditional_t<FP8, intx2, intx4>;
+    qfrag_t qf[QB][KS];                              // B operands of S^T = K Q^T (8 values each), kept in accumulation VGPRs
     floatx16 acc[QB][DC], acc_l[QB];                 // O^T (unnormalised) and the row sums (all 16 registers equal)
     auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
@@ -309,9 +325,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
 
     // operand addresses inside a tile buffer (bytes), without the unit offset
-    int k_off[KS], v_off[DC];
+    int k_off[KF], v_off[DC];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) k_off[ks] = (l32 * CH + ((2 * ks + hh) ^ (l32 & 7))) * 16;
+    for (int f = 0; f < KF; ++f) k_off[f] = (l32 * KCH + ((2 * f + hh) ^ (l32 & 7))) * 16;
     {
         const int t = lane & 15, gq = l32 >> 4, row = 4 * hh + (t >> 2);
 #pragma unroll
@@ -320,10 +336,20 @@ void attn_wide_kernel(const AttnKernelArgs a)
             v_off[i] = (row * CH + (chunk ^ ((row & (CH / 4 - 1)) << 2))) * 16 + (t & 1) * 8;
         }
     }
-    // K fragment ks of the unit `sub` (0/1) of a tile buffer: keys 32 sub + l32, dims 16ks + 8hh .. +7
-    auto k_frag = [&](const uint4 *kb, int sub, int ks) __attribute__((always_inline)) {
+    // K fragment f of the unit `sub` (0/1) of a tile buffer: key 32 sub + l32, bytes 32 f + 16 hh .. +15 of its
+    // row: bf16 dims 16 f + 8 hh .. +7 (one MFMA); fp8 dims 32 f + 16 hh .. +15 (two MFMAs, 8 dims each -
+    // any split of the head dim over k-steps and lane halves will do as long as Q uses the same)
+    auto k_frag = [&](const uint4 *kb, int sub, int f) __attribute__((always_inline)) {
         return __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
-                   reinterpret_cast<const char *>(kb) + sub * 32 * ROWB + k_off[ks]));
+                   reinterpret_cast<const char *>(kb) + sub * 32 * KROWB + k_off[f]));
+    };
+    // the operand of MFMA j out of its fragment
+    auto k_op = [&](const intx4 &fr, int j) __attribute__((always_inline)) {
+        if constexpr (FP8) {
+            const intx2 lo = {fr.x, fr.y}, hi = {fr.z, fr.w};
+            return (j & 1) ? hi : lo;
+        }
+        else return fr;
     };
     // V^T fragment jv of the unit `sub` of a tile buffer: dims 32i + l32 (i = jv % DC),
     // keys 32 sub + 16 st + 4hh + {0..3, 8..11} (st = jv / DC)
@@ -342,17 +368,21 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+            for (int f = 0; f < KF; ++f) {
                 // addresses derived from the opaque lane copy: see dma_q
-                const int lo = ((ln & 31) * CH + ((2 * ks + (ln >> 5)) ^ (ln & 7))) * 16;
-                qf[q][ks] = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
-                                reinterpret_cast<const char *>(QO) + wave * QOW + q * 32 * ROWB + lo));
-                asm volatile("" : "+a"(qf[q][ks]));
+                const int lo = ((ln & 31) * KCH + ((2 * f + (ln >> 5)) ^ (ln & 7))) * 16;
+                const intx4 w = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
+                                    reinterpret_cast<const char *>(QO) + wave * QOW + q * 32 * KROWB + lo));
+#pragma unroll
+                for (int m = 0; m < MPF; ++m) {
+                    qf[q][f * MPF + m] = k_op(w, m);
+                    asm volatile("" : "+a"(qf[q][f * MPF + m]));
+                }
             }
             const int v = min(t.v0 + wave * kRowsWave + q * 32 + (ln & 31), rows_total - 1);
-            c[q] = a.scale_log2;
-            if (a.q_scale) c[q] *= a.q_scale[t.bh0 + v / a.Nq];
-            if (a.k_scale) c[q] *= a.k_scale[t.kvs];
+            c_next[q] = a.scale_log2;                        // takes effect with the tile's first score block
+            if (a.q_scale) c_next[q] *= a.q_scale[t.bh0 + v / a.Nq];
+            if (a.k_scale) c_next[q] *= a.k_scale[t.kvs];
         }
         // the matrix instructions written as assembly are invisible to the compiler's hazard padding:
         // keep them clear of the register writes above
@@ -459,9 +489,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
         };
         // everything of the step that is not an MFMA, dealt out over the NP pieces
         auto piece = [&](int t) __attribute__((always_inline)) {
-            if (DMA && t >= 1 && t <= 2 * NDMA) {
-                if (t <= NDMA) dma_one(dk, kg, dma_koff, t - 1);
-                else dma_one(dv, vg, dma_voff, t - 1 - NDMA);
+            if (DMA && t >= 1 && t <= NDMA_K + NDMA) {
+                if (t <= NDMA_K) dma_one(dk, kg, dma_koff, t - 1);
+                else dma_one(dv, vg, dma_voff, t - 1 - NDMA_K);
             }
             if (t < MAXC) {
                 // row maxima of S(u) decide, without a divergent branch, whether the maxima in use are raised
@@ -504,9 +534,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
         for (int j = 0; j < KS; ++j) {
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
-                if (j == 0) qk_first(s_nxt[q], kfr[0], qf[q][0]);
-                else qk_next(s_nxt[q], kfr[j % RD], qf[q][j]);
-                if (q == QB - 1 && j + RD < KS) kfr[j % RD] = k_frag(kb, ksub, j + RD);
+                const int f = j / MPF;                       // fragment of this k-step; it is free after its last use
+                if (j == 0) qk_first<FP8>(s_nxt[q], k_op(kfr[0], 0), qf[q][0]);
+                else qk_next<FP8>(s_nxt[q], k_op(kfr[f % RD], j), qf[q][j]);
+                if (q == QB - 1 && j % MPF == MPF - 1 && f + RD < KF) kfr[f % RD] = k_frag(kb, ksub, f + RD);
                 if (q == 0 && j >= KS - RD) vfr[j - (KS - RD)] = v_frag(vb, vsub, j - (KS - RD));
                 piece(j * QB + q);
             }
@@ -598,12 +629,14 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
         const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
-             kbuf(I_<PAR>{}), (KIND == 0 ? cur.k : nxt.k) + (size_t)tile_start(ktile) * ROWB,
+             kbuf(I_<PAR>{}), (KIND == 0 ? cur.k : nxt.k) + (size_t)tile_start(ktile) * KROWB,
              vbuf(I_<1 - PAR>{}), (last ? nxt.v : cur.v) + (size_t)tile_start(vtile) * ROWB, F_{}, false, cur);
         if (KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
             mc[0] = mc[1] = -INFINITY;                       // the second step starts the next tile's softmax
             thr[0] = thr[1] = -INFINITY;
+            c[0] = c_next[0];
+            c[1] = c_next[1];
         }
         step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
              kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur);
@@ -626,17 +659,19 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // ---- prologue of the first row tile: Q rows and K tiles 0, 1 and V tile 0 go straight to LDS
     dma_q(cur);
-    dma_tile(K0, cur.k, dma_koff);
-    dma_tile(V0, cur.v, dma_voff);
-    dma_tile(K1, cur.k + (size_t)tile_start(1) * ROWB, dma_koff);
+    dma_tile(K0, cur.k, dma_koff, I_<NDMA_K>{});
+    dma_tile(V0, cur.v, dma_voff, I_<NDMA>{});
+    dma_tile(K1, cur.k + (size_t)tile_start(1) * KROWB, dma_koff, I_<NDMA_K>{});
     wait_loads_and_sync(I_<0>{});
     install_q(cur);
+    c[0] = c_next[0];
+    c[1] = c_next[1];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            if (ks == 0) qk_first(s0[q], k_frag(K0, 0, 0), qf[q][0]);
-            else qk_next(s0[q], k_frag(K0, 0, ks), qf[q][ks]);
+            if (ks == 0) qk_first<FP8>(s0[q], k_op(k_frag(K0, 0, 0), 0), qf[q][0]);
+            else qk_next<FP8>(s0[q], k_op(k_frag(K0, 0, ks / MPF), ks), qf[q][ks]);
         }
 #pragma unroll
     for (int q = 0; q < QB; ++q)
@@ -713,8 +748,12 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
         if (v >= 1 && v < wgs) wgs = v;
     }
     const dim3 grid((unsigned)wgs), block(kAttnThreads);
-    if (a.d == 128) return launch(attn_wide_kernel<128>, grid, block, stream, k);
-    return launch(attn_wide_kernel<64>, grid, block, stream, k);
+    if (a.qk_dtype == 2) {
+        if (a.d != 128) return hipErrorInvalidValue;      // 64-byte fp8 rows are not worth a variant
+        return launch(attn_wide_kernel<128, true>, grid, block, stream, k);
+    }
+    if (a.d == 128) return launch(attn_wide_kernel<128, false>, grid, block, stream, k);
+    return launch(attn_wide_kernel<64, false>, grid, block, stream, k);
 }
 
 }  // namespace dd

@@ -154,6 +154,48 @@ def test_bidir_wide_kernel_small_shapes(monkeypatch, B, H, Hkv, N, d, grid):
     assert_attention_close(got, ref, wl.BF16, f"wide kernel {B}x{H}/{Hkv}x{N}x{d}")
 
 
+WIDE_FP8 = [
+    # (B, H, Hkv, N): fp8 Q/K with per-head scales, d = 128; GQA, overlapping last tiles, several row tiles
+    (1, 2, 1, 64), (1, 4, 2, 100), (2, 8, 2, 130), (1, 4, 1, 257), (1, 2, 2, 1000), (1, 16, 2, 320),
+]
+
+
+@pytest.mark.parametrize("grid", [None, "2"])
+@pytest.mark.parametrize("B,H,Hkv,N", WIDE_FP8)
+def test_bidir_wide_kernel_fp8(monkeypatch, B, H, Hkv, N, grid):
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", "1")
+    if grid is not None:
+        if B * Hkv * -(-(H // Hkv) * N // 256) <= int(grid):
+            pytest.skip("no more row tiles than workgroups: same launch as the uncapped case")
+        monkeypatch.setenv("DD_TUNE_ATTN_WIDE_GRID", grid)
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=128, qk_dtype=wl.FP8_E4M3, v_dtype=wl.BF16, prompt=0, G=N,
+                           bl=min(16, N))
+    inp = wl.attention_inputs(cfg, seed=N)
+    got = gpu_bidir(inp, cfg)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], wl.FP8_E4M3, wl.BF16, inp["q_scale"], inp["k_scale"])
+    assert_attention_close(got, ref, wl.FP8_E4M3, f"wide kernel fp8 {B}x{H}/{Hkv}x{N}")
+
+
+def test_bidir_wide_kernel_scales_change_between_row_tiles(monkeypatch):
+    # one workgroup walks through the row tiles of four heads, each with its own score scale
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", "1")
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE_GRID", "1")
+    cfg = wl.custom_config(B=1, H=4, Hkv=2, N=256, d=128, prompt=0, G=256)
+    inp = wl.attention_inputs(cfg, seed=11)
+    rng = np.random.default_rng(5)
+    inp["q_scale"] = rng.uniform(0.4, 2.5, size=cfg.B * cfg.H).astype(np.float32)
+    inp["k_scale"] = rng.uniform(0.4, 2.5, size=cfg.B * cfg.Hkv).astype(np.float32)
+    got = gpu_bidir(inp, cfg)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], wl.BF16, wl.BF16, inp["q_scale"], inp["k_scale"])
+    assert_attention_close(got, ref, wl.BF16, "wide kernel, per-head scales")
+
+
+@pytest.mark.parametrize("wide", ["0", "1"])
+def test_cfg5_bidir_each_kernel(monkeypatch, wide):
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    _bidir_full_size(5, 192)
+
+
 @pytest.mark.parametrize("wide,stream", [("1", "0"), ("0", "0"), ("0", "1")])
 def test_cfg3_bidir_each_kernel(monkeypatch, wide, stream):
     monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
