@@ -6,7 +6,7 @@ bidirectional attention, one verification pass over the vocabulary (Alg. 1, one 
 on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line:
   value        = verifier attention TFLOP/s (4*B*H*N^2*d FLOP per call / its measured time)
   ms_per_step  = wall time of the whole step (events around all kernels of the step)
-  roofline     = the attention kernel against the dense bf16 MFMA peak
+  roofline     = the attention kernel against the dense MFMA peak of its operand types
   roofline_verify = the verification kernels against the HBM peak
   cpu_baseline = the fp64 CPU oracle timed on a bounded sample of the same workload
 """
@@ -25,6 +25,8 @@ if ROOT not in sys.path:
 
 METRIC = "verifier attn TFLOP/s (% MFMA peak); verify GB/s (% HBM); draft+verify step ms"
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP8_TFLOPS = 5000.0      # MI355X dense fp8 MFMA
+PEAK_FP32_VALU_TFLOPS = 157.3 # MI355X fp32 vector
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 LLC_ROTATE_BYTES = 600e6      # rotate input sets until their total exceeds 2x the 256 MB last-level cache
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
@@ -172,6 +174,19 @@ def main():
     ver_gbps = verify_bytes / (t_ver * 1e-3) / 1e9
     blk_gbps = block_bytes / (t_block / cfg.K * 1e-3) / 1e9
 
+    # the peak the attention call is priced against: each contraction at the peak of its own operand type
+    if cfg.qk_dtype == wl.F32:
+        attn_kernel, attn_bound, attn_peak = "attn_f32_kernel", "alu", PEAK_FP32_VALU_TFLOPS
+        attn_peak_note = "fp32 inputs: vector ALUs (no fp32 MFMA path is used), 157.3 TFLOP/s"
+    elif cfg.qk_dtype == wl.FP8_E4M3:
+        attn_kernel, attn_bound = "attn_wide_kernel<128, fp8> (large shapes) / attn_mfma_kernel", "mfma"
+        attn_peak = 2.0 / (1.0 / PEAK_FP8_TFLOPS + 1.0 / PEAK_BF16_TFLOPS)
+        attn_peak_note = ("half of the FLOPs (S = Q K^T) run as fp8 MFMA (5.0 PFLOP/s), half (O = P V) as bf16 MFMA "
+                          "(2.5 PFLOP/s): time-weighted peak 3.33 PFLOP/s")
+    else:
+        attn_kernel, attn_bound, attn_peak = "attn_wide_kernel / attn_stream_kernel / attn_mfma_kernel by size", "mfma", PEAK_BF16_TFLOPS
+        attn_peak_note = "dense bf16 MFMA, 2.5 PFLOP/s"
+
     out = {
         "metric": METRIC, "value": round(attn_tflops, 3), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -187,10 +202,9 @@ def main():
         "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
         "block_attention_GBps": round(blk_gbps, 1),
-        "roofline": {"kernel": "dd_bidir_attention (attn_wide_kernel on large bf16 shapes, else attn_mfma_kernel)",
-                     "bound": "mfma",
-                     "achieved": round(attn_tflops, 3), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"kernel": attn_kernel, "bound": attn_bound,
+                     "achieved": round(attn_tflops, 3), "peak": round(attn_peak, 1), "unit": "TFLOP/s",
+                     "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
                      "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),
                      "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
         "roofline_verify": {"kernel": "verify_partial_kernel + verify_finalize_kernel (dd_verify_remask)",

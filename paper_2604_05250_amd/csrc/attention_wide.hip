@@ -1,4 +1,4 @@
-// Verifier attention, wide-wave form (bf16):  O = softmax(Q K^T / sqrt(d_k)) V over all positions
+// Verifier attention, wide-wave form (bf16, or fp8 e4m3 Q/K with bf16 V):  O = softmax(Q K^T / sqrt(d_k)) V over all positions
 // (Eq. 3 applied bidirectionally, Sec. 2.2) -- the O(N^2)-per-step cost of a masked diffusion model.
 //
 // Why a second kernel.  With 32 query rows per wave every matrix-core instruction needs its own 1 KB
@@ -26,8 +26,8 @@
 // is written by the first half of step u's MFMAs and first read by a vector instruction in step u+1.
 //
 // Persistence.  A lone wave cannot hide the start (operand loads, pipeline fill) and the end (normalise,
-// store) of a row tile behind another workgroup's work, so a workgroup walks through a contiguous range of
-// row tiles and the K/V tile stream simply wraps into the next row tile: the two surplus steps that drain
+// store) of a row tile behind another workgroup's work, so a workgroup walks through every G-th row
+// tile (G workgroups) and the K/V tile stream simply wraps into the next row tile: the two surplus steps that drain
 // one tile's pipeline compute the first two score blocks of the next.  The next tile's Q rows are
 // prefetched into LDS one stage earlier; the finished tile is normalised, transposed through the same
 // LDS region and written out in full rows.
@@ -176,17 +176,16 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #endif
     const int l32 = lane & 31, hh = lane >> 5;
 
-    // ---- this workgroup's range of row tiles.  Tile t = ((b * Hkv + kvh) * row_tiles + rt); neighbours
-    // share K/V, and consecutive workgroup ranges go to the same XCD (own L2 each).
+    // ---- this workgroup's row tiles.  Tile t = ((b * Hkv + kvh) * row_tiles + rt); workgroup w takes tiles
+    // w, w + G, w + 2G ...: at any time the G workgroups are on consecutive tiles, so neighbours work on the
+    // same K/V, and neighbours are placed on the same XCD (own L2 each).
     const int tiles_total = a.B * a.Hkv * a.row_tiles;
-    int t_cur, t_end;
+    const int t_stride = gridDim.x;
+    int t_cur;
     {
         const int G = gridDim.x, per = G >> 3, rem = G & 7;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int w = xcd * per + min(xcd, rem) + slot;
-        const int base = tiles_total / G, extra = tiles_total % G;
-        t_cur = w * base + min(w, extra);
-        t_end = t_cur + base + (w < extra ? 1 : 0);
+        t_cur = xcd * per + min(xcd, rem) + slot;
     }
     const int rows_total = a.group * a.Nq;           // query rows per (batch, kv head); contiguous in memory
     const int nkeys = a.N;
@@ -690,8 +689,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
     const unsigned long long t_loop = __builtin_readcyclecounter();
 #endif
     for (;;) {
-        has_next = t_cur + 1 < t_end;
-        if (has_next) nxt = tile_of(t_cur + 1);
+        has_next = t_cur + t_stride < tiles_total;
+        if (has_next) nxt = tile_of(t_cur + t_stride);
         int sp = 0;
 #ifdef DDW_TIMING2
         const unsigned long long t0 = __builtin_readcyclecounter();
@@ -714,7 +713,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #endif
         if (!has_next) break;
         cur = nxt;
-        ++t_cur;
+        t_cur += t_stride;
     }
 #ifdef DDW_TIMING2
     if (tid == 0) {
