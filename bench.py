@@ -37,6 +37,11 @@ PROFILED_TRAFFIC_BYTES = {
 }
 
 
+def wl_mode_names():
+    from paper_2604_05250_amd import workloads as wl
+    return list(wl.MODE_NAMES.values())
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +54,9 @@ def parse():
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed steps, run one device-to-device copy of this many MiB (a kernel of known "
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--verify-mode", default=None, choices=sorted(wl_mode_names()),
+                    help="verification rule to run instead of the workload's own (kl_topk / conf_topk: threshold = budget k)")
+    ap.add_argument("--verify-threshold", type=float, default=0.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -72,7 +80,10 @@ def main():
     dev = torch.device("cuda:0")
     cfg = wl.CONFIGS[args.config]
     mode, tau = cfg.modes[-1]
-    kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB)
+    if args.verify_mode is not None:                     # another rule of the same call on the same inputs
+        mode = {v: k for k, v in wl.MODE_NAMES.items()}[args.verify_mode]
+        tau = args.verify_threshold
+    kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB, wl.KL_TOPK)
 
     def up(a):
         if a is None:

@@ -62,7 +62,11 @@ typedef enum {
     DD_KL_THRESH = 1,    /* remask i iff KL_i > threshold                      (Sec. 3.2.2) */
     DD_CONF_THRESH = 2,  /* remask i iff c_V,i < threshold                     (Sec. 3.2.3) */
     DD_KL_PROB = 3,      /* remask i with probability KL_i / sum_j KL_j (Eq. 6) */
-    DD_CONF_PROB = 4     /* remask i with probability 1 - c_V,i                (Sec. 3.2.3) */
+    DD_CONF_PROB = 4,    /* remask i with probability 1 - c_V,i                (Sec. 3.2.3) */
+    /* Budgeted forms of the two rules above (not rules of the paper, which only thresholds or draws):
+     * per sequence, the k = floor(threshold) worst eligible positions are remasked. */
+    DD_KL_TOPK = 5,      /* the k eligible positions with the largest KL_i   */
+    DD_CONF_TOPK = 6     /* the k eligible positions with the smallest c_V,i */
 } dd_mode;
 
 /* Human-readable text for a dd_status (static storage; never NULL). */
@@ -139,6 +143,11 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
  *         DD_KL_PROB      u_i < max(score_i,0) / sum_{j eligible, same sequence} max(score_j,0)
  *                         (an empty or zero sum remasks nothing)
  *         DD_CONF_PROB    u_i < 1 - score_i
+ *         DD_KL_TOPK      fewer than k eligible positions j of the same sequence are worse than i, where
+ *         DD_CONF_TOPK    j is worse than i iff its score is larger (KL) / smaller (confidence), or equal
+ *                         with j < i; k = floor(threshold), threshold >= 0 and finite (else DD_ERR_SHAPE);
+ *                         scores compared in fp32; a sequence with at most k eligible positions
+ *                         remasks all of them
  *     u_i = top 24 bits of word 0 of Philox-4x32-10(counter = (i_lo, i_hi, 0, 0),
  *           key = (seed_lo, seed_hi)) times 2^-24, i = global row index b*G+g.
  *
@@ -150,7 +159,7 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
  *   out_scores [P] f32  = score_i          (every row)
  * logit_dtype in {DD_F32, DD_BF16}; V >= 1 with V * sizeof(element) a multiple of 16;
  * B, G >= 0 (P == 0 is a no-op returning DD_OK); V < 2^31, P < 2^31.
- * `seed` is ignored by DD_TRUST and the threshold modes.
+ * `seed` is ignored by DD_TRUST, the threshold modes and the budgeted modes.
  * Each logit is read from memory exactly once (single pass; rows are split across
  * workgroups and their partial states merged in `workspace`).
  */

@@ -19,7 +19,7 @@ _SRC = os.path.join(_HERE, "dd_oracle.c")
 _LIB = os.path.join(_HERE, "libdd_oracle.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
-TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB = 0, 1, 2, 3, 4
+TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
 
 
 def build(force: bool = False) -> str:
@@ -189,7 +189,7 @@ def remask_decide(score32, mask, mode: int, threshold: float, seed: int, B: int,
 def verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed: int, B: int, G: int, dtype: int):
     """Whole verification pass: scores for every row, then the remask rule.
     Returns dict(out_mask, out_tokens, out_scores (fp32-rounded), kl, conf, prob)."""
-    need_d = mode in (KL_THRESH, KL_PROB)
+    need_d = mode in (KL_THRESH, KL_PROB, KL_TOPK)
     if need_d and logits_d is None:
         raise ValueError("KL modes need drafter logits")
     kl, conf, tok = verify_scores(logits_d if need_d else None, logits_v, dtype)

@@ -32,7 +32,8 @@
 #include <string.h>
 
 enum { ORA_F32 = 0, ORA_BF16 = 1, ORA_FP8_E4M3 = 2 };
-enum { ORA_TRUST = 0, ORA_KL_THRESH = 1, ORA_CONF_THRESH = 2, ORA_KL_PROB = 3, ORA_CONF_PROB = 4 };
+enum { ORA_TRUST = 0, ORA_KL_THRESH = 1, ORA_CONF_THRESH = 2, ORA_KL_PROB = 3, ORA_CONF_PROB = 4,
+       ORA_KL_TOPK = 5, ORA_CONF_TOPK = 6 };
 
 /* ---------------------------------------------------------------- decoding */
 
@@ -334,6 +335,10 @@ double ora_row_uniform(uint64_t seed, uint64_t row)
  *   KL_PROB      remask iff u_i < KL_i / sum_{j eligible, same sequence} KL_j   (Eq. 6);
  *                negative round-off in KL is clamped to 0; an empty or all-zero sum remasks nothing
  *   CONF_PROB    remask iff u_i < 1 - c_V
+ *   KL_TOPK      budgeted forms of the two threshold rules (a variant, not a rule of the paper): of each
+ *   CONF_TOPK    sequence's eligible positions the k = floor(tau) worst are remasked - largest KL, or
+ *                smallest c_V; equal scores: the lower position first.  Written as the definition:
+ *                position i is remasked iff fewer than k eligible positions are worse than it.
  *
  * out_mask[i] = mask[i] OR remask_i.  prob[i] (optional) receives the remask probability
  * used in the probabilistic modes (0 elsewhere), so that a test can exempt draws that
@@ -344,7 +349,9 @@ int ora_remask_decide(const float *score32, const uint8_t *mask, int mode, float
 {
     if (!score32 || !mask || !out_mask || B < 0 || G < 0)
         return -1;
-    if (mode < ORA_TRUST || mode > ORA_CONF_PROB)
+    if (mode < ORA_TRUST || mode > ORA_CONF_TOPK)
+        return -1;
+    if ((mode == ORA_KL_TOPK || mode == ORA_CONF_TOPK) && !(threshold >= 0.0f && threshold <= 3.0e38f))
         return -1;
     for (int b = 0; b < B; ++b) {
         double total = 0.0;
@@ -378,6 +385,20 @@ int ora_remask_decide(const float *score32, const uint8_t *mask, int mode, float
                 p = 1.0 - (double)score32[i];
                 remask = ora_row_uniform(seed, (uint64_t)i) < p;
                 break;
+            case ORA_KL_TOPK:
+            case ORA_CONF_TOPK: {
+                double worse = 0.0;                       /* eligible positions of this sequence worse than g */
+                for (int h = 0; h < G; ++h) {
+                    size_t j = (size_t)b * G + h;
+                    if (mask[j] != 0)
+                        continue;
+                    int more = mode == ORA_KL_TOPK ? score32[j] > score32[i] : score32[j] < score32[i];
+                    if (more || (score32[j] == score32[i] && h < g))
+                        worse += 1.0;
+                }
+                remask = worse < floor((double)threshold);
+                break;
+            }
             }
             out_mask[i] = (uint8_t)(mask[i] != 0 || (eligible && remask));
             if (prob)

@@ -13,7 +13,7 @@ import os
 from typing import Optional
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
-TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB = 0, 1, 2, 3, 4
+TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdd.so")

@@ -76,7 +76,6 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ unsigned pack_bf16_rne(float lo, float hi)
 {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef int intx2 __attribute__((ext_vector_type(2)));
     floatx2 f = {lo, hi};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
 }

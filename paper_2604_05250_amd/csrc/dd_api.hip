@@ -169,14 +169,15 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
                      int B, int G, int V, dd_dtype logit_dtype,
                      void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (mode < DD_TRUST || mode > DD_CONF_PROB) return DD_ERR_MODE;
+    if (mode < DD_TRUST || mode > DD_CONF_TOPK) return DD_ERR_MODE;
+    if ((mode == DD_KL_TOPK || mode == DD_CONF_TOPK) && !(threshold >= 0.0f && threshold <= 3.0e38f)) return DD_ERR_SHAPE;
     if (logit_dtype != DD_F32 && logit_dtype != DD_BF16) return DD_ERR_DTYPE;
     if (B < 0 || G < 0 || V < 1) return DD_ERR_SHAPE;
     if ((double)B * G >= 2147483648.0) return DD_ERR_SHAPE;
     const int eb = logit_dtype == DD_BF16 ? 2 : 4;
     if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
     if (B == 0 || G == 0) return DD_OK;
-    const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB);
+    const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB || mode == DD_KL_TOPK);
     if (!logits_v || !mask || !out_mask || !out_tokens || !out_scores) return DD_ERR_NULL;
     if (kl && !logits_d) return DD_ERR_NULL;
     if (misaligned16(logits_v) || (kl && misaligned16(logits_d))) return DD_ERR_ALIGN;

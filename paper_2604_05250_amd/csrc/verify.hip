@@ -310,7 +310,7 @@ __device__ __forceinline__ void finish_row(int row, double md, double sd, double
     case 1: remask = s32 > threshold; break;                                // KL threshold
     case 2: remask = s32 < threshold; break;                                // confidence threshold
     case 4: remask = row_uniform(seed, (uint64_t)row) < 1.0 - (double)s32; break;
-    default: break;                                                         // trust; KL-prob decided later
+    default: break;                                                         // trust; per-sequence rules decided later
     }
     out_mask[row] = (uint8_t)((m != 0) || remask);
 }
@@ -397,6 +397,49 @@ __global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restr
     }
 }
 
+// Budgeted remasking: rank the eligible rows of a sequence by badness (KL: larger score, confidence: smaller
+// score; equal scores: lower row first) and remask those of rank < k.  The rank of a row is the number of
+// eligible rows of its sequence that are worse.  One workgroup takes 64 rows of one sequence, four lanes per
+// row, each lane a quarter of the comparisons; the sequence's scores pass through LDS in chunks and are
+// read back 16 bytes at a time (a scalar loop here is bound by the LDS latency of every single read).
+constexpr int kTopkRows = 64, kTopkChunk = 2048;
+__global__ __launch_bounds__(256) void verify_topk_kernel(const float *__restrict__ scores,
+                                                          const uint8_t *__restrict__ mask, int G, int kl_mode,
+                                                          float budget, uint8_t *__restrict__ out_mask)
+{
+    __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];   // -inf marks a row that is not eligible
+    const int slabs = (G + kTopkRows - 1) / kTopkRows;        // workgroups per sequence
+    const int b = blockIdx.x / slabs, tid = threadIdx.x;
+    const size_t base = (size_t)b * G;
+    const float sign = kl_mode ? 1.0f : -1.0f;
+    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4, sub = tid % 4;
+    const bool mine = g < G;
+    const bool eligible = mine && mask[base + g] == 0;
+    const float bad = eligible ? sign * scores[base + g] : 0.0f;
+    int rank = 0;
+    for (int c0 = 0; c0 < G; c0 += kTopkChunk) {             // uniform trip count: every lane reaches the barriers
+        const int n = min(kTopkChunk, G - c0), n16 = (n + 15) & ~15;
+        __syncthreads();
+        for (int j = tid; j < n16; j += 256)
+            bad_sh[j] = (j < n && mask[base + c0 + j] == 0) ? sign * scores[base + c0 + j] : kNegInf;
+        __syncthreads();
+        if (eligible) {
+#pragma unroll 4
+            for (int j = 4 * sub; j < n16; j += 16) {
+                const float4 o = *reinterpret_cast<const float4 *>(&bad_sh[j]);
+                const int i = c0 + j;
+                rank += (o.x > bad || (o.x == bad && i < g)) ? 1 : 0;
+                rank += (o.y > bad || (o.y == bad && i + 1 < g)) ? 1 : 0;
+                rank += (o.z > bad || (o.z == bad && i + 2 < g)) ? 1 : 0;
+                rank += (o.w > bad || (o.w == bad && i + 3 < g)) ? 1 : 0;
+            }
+        }
+    }
+    rank += __shfl_xor(rank, 1);
+    rank += __shfl_xor(rank, 2);
+    if (mine && sub == 0) out_mask[base + g] = (uint8_t)(mask[base + g] != 0 || (eligible && (float)rank < budget));
+}
+
 int env_int(const char *name, int dflt)
 {
     const char *v = getenv(name);
@@ -457,7 +500,7 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     if (P == 0) return hipSuccess;
     const int eb = logit_is_bf16 ? 2 : 4;
     const int nvec = (int)((long)V * eb / 16);
-    const bool kl = (mode == 1 || mode == 3);
+    const bool kl = (mode == 1 || mode == 3 || mode == 5);
     const uint4 *ld = static_cast<const uint4 *>(logits_d);
     const uint4 *lv = static_cast<const uint4 *>(logits_v);
     hipError_t e;
@@ -489,6 +532,9 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     if (e != hipSuccess) return e;
     if (mode == 3)
         e = launch(verify_klprob_kernel, dim3(B), dim3(256), stream, (const float *)out_scores, mask, G, seed, out_mask);
+    if (mode == 5 || mode == 6)
+        e = launch(verify_topk_kernel, dim3((unsigned)((long)((G + kTopkRows - 1) / kTopkRows) * B)), dim3(256), stream,
+                   (const float *)out_scores, mask, G, kl ? 1 : 0, floorf(threshold), out_mask);
     return e;
 }
 

@@ -66,9 +66,13 @@ def test_verify_argument_validation():
     L = dd.lib()
 
     def call(ld=FAKE, lv=FAKE, mask=FAKE, mode=dd.KL_THRESH, om=FAKE, ot=FAKE, osc=FAKE, B=2, G=8, V=1024,
-             dt=dd.BF16, ws=None, wsn=0):
-        return L.dd_verify_remask(ld, lv, mask, mode, C.c_float(0.3), 0, om, ot, osc, B, G, V, dt, ws, wsn, None)
-    assert call(mode=5) == -4 and call(mode=-1) == -4
+             dt=dd.BF16, ws=None, wsn=0, tau=0.3):
+        return L.dd_verify_remask(ld, lv, mask, mode, C.c_float(tau), 0, om, ot, osc, B, G, V, dt, ws, wsn, None)
+    assert call(mode=7) == -4 and call(mode=-1) == -4
+    # the budget of the budgeted modes is a non-negative finite number; drafter logits only for the KL form
+    assert call(mode=dd.KL_TOPK, tau=-1.0) == -2 and call(mode=dd.CONF_TOPK, tau=float("inf")) == -2
+    assert call(mode=dd.CONF_TOPK, tau=float("nan")) == -2
+    assert call(mode=dd.KL_TOPK, ld=None, tau=3.0) == -1 and call(mode=dd.CONF_TOPK, ld=None, tau=3.0) == -5
     assert call(dt=dd.FP8_E4M3) == -3
     assert call(B=-1) == -2 and call(V=0) == -2
     assert call(V=1001) == -6                              # row pitch not a multiple of 16 bytes

@@ -216,3 +216,70 @@ def test_cfg4_full_size():
 
 def test_cfg5_full_size():
     _full_size(5, 64)
+
+
+# ------------------------------------------------------------------ budgeted remasking (k worst positions per sequence)
+def check_budgeted(inp, mode, k, B, G, dtype, what):
+    kl_mode = mode == wl.KL_TOPK
+    om, ot, osc = run_gpu(inp, mode, float(k), 0, B, G, dtype, with_drafter=kl_mode)
+    ora = oracle.verify_remask(inp["logits_d"] if kl_mode else None, inp["logits_v"], inp["mask"], mode, float(k), 0,
+                               B, G, dtype)
+    assert np.array_equal(ot, ora["out_tokens"]), f"{what}: argmax tokens differ"
+    assert_scores_close(osc, ora["score64"], what)
+    mask = inp["mask"].reshape(B, G)
+    s = ora["score64"].reshape(B, G)
+    exempt = np.zeros((B, G), bool)
+    for b in range(B):
+        elig = np.flatnonzero(mask[b] == 0)
+        n = min(int(k), len(elig))
+        # exactly min(k, eligible) positions per sequence, whatever happens at the boundary
+        assert int(om.reshape(B, G)[b].sum()) - int((mask[b] != 0).sum()) == n, f"{what}: sequence {b} remask count"
+        if 0 < n < len(elig):
+            srt = np.sort(s[b][elig])
+            edge = srt[::-1][n - 1] if kl_mode else srt[n - 1]           # score of the last position inside the budget
+            # the two sides rank their own fp32 scores, which agree to 1e-3 relative: positions that close
+            # to the boundary score may swap
+            exempt[b] = np.abs(s[b] - edge) <= 2e-3 * abs(edge) + 2e-6
+    diff = (om != ora["out_mask"]) & ~exempt.reshape(-1)
+    assert not diff.any(), f"{what}: remask decisions differ at rows {np.nonzero(diff)[0][:8]}"
+    assert (om[inp["mask"] != 0] == 1).all()
+    return om, osc
+
+
+@pytest.mark.parametrize("mode", [wl.KL_TOPK, wl.CONF_TOPK])
+def test_budgeted_modes_small_and_fused_paths(mode):
+    for (B, G, V, dtype, frac) in ((3, 50, 4096, wl.BF16, 0.6), (4, 300, 1000, wl.BF16, 0.5), (1, 64, 1024, wl.F32, None),
+                                   (2, 2500, 520, wl.F32, 0.7)):
+        cfg = wl.custom_config(B=B, G=G, V=V, logit_dtype=dtype, sigma_d=3.0, sigma_n=1.0, decoded_frac=frac)
+        inp = wl.verify_inputs(cfg, seed=G)
+        for k in (0, 1, 7, G // 3, G, 10 * G):
+            check_budgeted(inp, mode, k, B, G, dtype, f"budget {k} mode {mode} B{B} G{G} V{V}")
+
+
+@pytest.mark.parametrize("mode", [wl.KL_TOPK, wl.CONF_TOPK])
+def test_budgeted_modes_break_ties_by_position(mode):
+    # identical rows give bit-identical scores: the budget boundary falls inside groups of equal scores
+    cfg = wl.custom_config(B=2, G=96, V=2048, logit_dtype=wl.BF16, sigma_d=3.0, sigma_n=1.0)
+    inp = wl.verify_inputs(cfg, seed=2)
+    for name in ("logits_d", "logits_v"):
+        a = inp[name].reshape(cfg.B, cfg.G, -1)
+        a[:, 8:, :] = a[:, np.arange(8, cfg.G) % 8, :]               # every sequence: 12 copies of 8 distinct rows
+    mask = np.zeros(cfg.P, np.uint8); mask[5::11] = 1
+    inp["mask"] = mask
+    for k in (1, 5, 13, 30, 50):
+        om, osc = check_budgeted(inp, mode, k, cfg.B, cfg.G, wl.BF16, f"ties budget {k} mode {mode}")
+        s = osc.reshape(cfg.B, cfg.G)
+        assert (s[:, 8:] == s[:, np.arange(8, cfg.G) % 8]).all()
+        ora_mask = oracle.remask_decide(osc, mask, mode, float(k), 0, cfg.B, cfg.G)[0]
+        assert np.array_equal(om, ora_mask)                           # the rule itself, on the GPU's own scores: exact
+
+
+def test_cfg3_budgeted_kl():
+    cfg = wl.CONFIGS[3]
+    inp = wl.verify_inputs(cfg, seed=0)
+    om, ot, osc = run_gpu(inp, wl.KL_TOPK, 32.0, 0, cfg.B, cfg.G, cfg.logit_dtype)
+    assert np.array_equal(om, oracle.remask_decide(osc, inp["mask"], wl.KL_TOPK, 32.0, 0, cfg.B, cfg.G)[0])
+    rows = np.random.default_rng(3).integers(0, cfg.P, 64)
+    kl, _, tok = oracle.verify_scores(inp["logits_d"], inp["logits_v"], cfg.logit_dtype, rows=rows)
+    assert np.array_equal(ot[rows], tok)
+    assert_scores_close(osc[rows], kl, "cfg3 budgeted KL (sampled rows)")

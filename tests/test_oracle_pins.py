@@ -10,7 +10,7 @@ import pytest
 import scipy.special as sp
 
 import oracle
-from oracle import BF16, CONF_PROB, CONF_THRESH, F32, FP8_E4M3, KL_PROB, KL_THRESH, TRUST
+from oracle import BF16, CONF_PROB, CONF_THRESH, CONF_TOPK, F32, FP8_E4M3, KL_PROB, KL_THRESH, KL_TOPK, TRUST
 from paper_2604_05250_amd import workloads as wl
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -283,6 +283,50 @@ def test_probabilistic_rules():
     a, _ = oracle.remask_decide(kl, mask, KL_THRESH, 0.5, 1, B, G)
     b, _ = oracle.remask_decide(kl, mask, KL_THRESH, 0.5, 2, B, G)
     assert np.array_equal(a, b)
+
+
+def test_budgeted_rules():
+    # hand-checked: per sequence the k worst eligible positions, equal scores -> the lower position first
+    score = np.array([0.2, 0.9, 0.9, 0.1, 0.5, 0.9,   0.3, 0.3, 0.3, 0.3, 0.0, 0.7], np.float32)
+    mask = np.array([0, 0, 0, 0, 0, 1,                  0, 1, 0, 0, 0, 0], np.uint8)
+    kt, _ = oracle.remask_decide(score, mask, KL_TOPK, 2.0, 0, 2, 6)
+    assert kt.tolist() == [0, 1, 1, 0, 0, 1,   1, 1, 0, 0, 0, 1]     # 0.9, 0.9 (the masked 0.9 does not count) | 0.7, first 0.3
+    ct, _ = oracle.remask_decide(score, mask, CONF_TOPK, 2.9, 0, 2, 6)  # k = floor(2.9) = 2
+    assert ct.tolist() == [1, 0, 0, 1, 0, 1,   1, 1, 0, 0, 1, 0]     # 0.1, 0.2 | 0.0, first eligible 0.3 (position 0)
+    # against an independent formulation (stable argsort) on random scores with many ties
+    B, G = 4, 257
+    rng = np.random.default_rng(9)
+    sc = (rng.integers(0, 40, B * G) / 40.0).astype(np.float32)
+    mk = (rng.random(B * G) < 0.3).astype(np.uint8)
+    prev = {KL_TOPK: mk, CONF_TOPK: mk}
+    for k in (0, 1, 5, 100, 180, 257, 1000):
+        for mode, sign in ((KL_TOPK, -1.0), (CONF_TOPK, 1.0)):
+            got, _ = oracle.remask_decide(sc, mk, mode, float(k), 0, B, G)
+            want = mk.copy().reshape(B, G)
+            for b in range(B):
+                elig = np.flatnonzero(mk.reshape(B, G)[b] == 0)
+                order = elig[np.argsort(sign * sc.reshape(B, G)[b][elig], kind="stable")]
+                want[b, order[:k]] = 1
+            assert np.array_equal(got.reshape(B, G), want), (k, mode)
+            assert (got >= prev[mode]).all()                         # a larger budget never remasks less
+            assert (got.reshape(B, G).sum(1) - mk.reshape(B, G).sum(1) == np.minimum(k, (mk.reshape(B, G) == 0).sum(1))).all()
+            prev[mode] = got
+    # k = 0 changes nothing; a budget beyond the eligible count remasks every eligible position
+    z, _ = oracle.remask_decide(sc, mk, KL_TOPK, 0.0, 0, B, G)
+    assert np.array_equal(z, mk)
+    a, _ = oracle.remask_decide(sc, mk, CONF_TOPK, 1e9, 0, B, G)
+    assert a.all()
+    # with distinct scores the budgeted rule equals the threshold rule at a threshold between ranks k and k+1
+    d = rng.permutation(G).astype(np.float32) / G
+    m0 = np.zeros(G, np.uint8)
+    srt = np.sort(d)[::-1]
+    for k in (1, 17, 200):
+        tau = (srt[k - 1] + srt[k]) / 2
+        a, _ = oracle.remask_decide(d, m0, KL_TOPK, float(k), 0, 1, G)
+        b, _ = oracle.remask_decide(d, m0, KL_THRESH, tau, 0, 1, G)
+        assert np.array_equal(a, b)
+    with pytest.raises(ValueError):
+        oracle.remask_decide(d, m0, KL_TOPK, -1.0, 0, 1, G)
 
 
 # ------------------------------------------------------------------ attention
