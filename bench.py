@@ -50,13 +50,16 @@ def parse():
     ap.add_argument("--config", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--parts", default="block,attention,verify",
-                    help="comma list of the step's parts to run (profiling a single kernel); default: the whole step")
+                    help="comma list of the step's parts to run (profiling a single kernel); default: the whole step; "
+                         "'unmask' adds the drafter's unmasking step after the K block calls")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed steps, run one device-to-device copy of this many MiB (a kernel of known "
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     ap.add_argument("--verify-mode", default=None, choices=sorted(wl_mode_names()),
                     help="verification rule to run instead of the workload's own (kl_topk / conf_topk: threshold = budget k)")
     ap.add_argument("--verify-threshold", type=float, default=0.0)
+    ap.add_argument("--unmask-threshold", type=float, default=0.9,
+                    help="confidence threshold of the optional 'unmask' part (add it to --parts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -132,14 +135,35 @@ def main():
 
     parts = set(args.parts.split(","))
 
+    # optional part: the drafter's unmasking step after each of the K block calls (Alg. 1, drafting phase), on the
+    # drafter's logits of the active block: [B*bl, V] per step, cut from the workload's drafter logits
+    unmask_dev = []
+    unmask_bytes = cfg.B * cfg.bl * cfg.V * eb_l
+    if "unmask" in parts:
+        ld_full = up(ver["logits_d"]).view(cfg.B, cfg.G, cfg.V)
+        rng_m = np.random.default_rng(args.seed + 77)
+        for k in range(cfg.K):
+            g0 = (k * cfg.bl) % max(1, cfg.G - cfg.bl + 1)
+            unmask_dev.append({"ld": ld_full[:, g0:g0 + cfg.bl, :].contiguous().view(cfg.B * cfg.bl, cfg.V),
+                               "mask": up((rng_m.random(cfg.B * cfg.bl) < 0.5).astype(np.uint8))})
+        del ld_full
+        um_mask = torch.empty(cfg.B * cfg.bl, dtype=torch.uint8, device=dev)
+        um_tok = torch.empty(cfg.B * cfg.bl, dtype=torch.int32, device=dev)
+        um_conf = torch.empty(cfg.B * cfg.bl, dtype=torch.float32, device=dev)
+        um_x = torch.zeros(cfg.B * cfg.bl, dtype=torch.int32, device=dev)
+
     def step(i, rec=None):
         s = sets[i % n_sets]
-        marks = [ev() for _ in range(4)] if rec is not None else None
+        marks = [ev() for _ in range(5)] if rec is not None else None
         if marks: marks[0].record()
         for b in (blk_dev if "block" in parts else ()):
             dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], O=Oblk, Kblk=b["K"], Vblk=b["V"],
                                          q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
         if marks: marks[1].record()
+        for u in unmask_dev:
+            dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
+                         out_mask=um_mask, out_tokens=um_tok, out_conf=um_conf, logit_dtype=cfg.logit_dtype)
+        if marks: marks[4].record()
         if "attention" in parts:
             dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
                                   qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
@@ -166,7 +190,8 @@ def main():
     total_ms = t_begin.elapsed_time(t_end)
     ms_per_step = total_ms / args.steps
     t_block = sum(m[0].elapsed_time(m[1]) for m in rec) / len(rec)         # K calls
-    t_attn = sum(m[1].elapsed_time(m[2]) for m in rec) / len(rec)
+    t_unmask = sum(m[1].elapsed_time(m[4]) for m in rec) / len(rec)
+    t_attn = sum(m[4].elapsed_time(m[2]) for m in rec) / len(rec)
     t_ver = sum(m[2].elapsed_time(m[3]) for m in rec) / len(rec)
     if "verify" in parts:
         assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
@@ -224,6 +249,15 @@ def main():
                             "traffic": PROFILED_TRAFFIC_BYTES["verify"].get(args.config),
                             "algorithmic_bytes": verify_bytes},
     }
+
+    if "unmask" in parts:
+        um_gbps = unmask_bytes / (max(t_unmask, 1e-9) / cfg.K * 1e-3) / 1e9
+        out["components_ms"]["unmask_xK"] = round(t_unmask, 4)
+        out["roofline_unmask"] = {"kernel": "verify_row_kernel / verify_partial_kernel + unmask_select_kernel (dd_unmask)",
+                                  "bound": "hbm", "achieved": round(um_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                  "frac": round(um_gbps / PEAK_HBM_GBPS, 4), "traffic": None,
+                                  "algorithmic_bytes": unmask_bytes,
+                                  "note": f"K={cfg.K} calls per step on the active block's drafter logits [{cfg.B * cfg.bl}, {cfg.V}]"}
 
     if not args.no_cpu_baseline:
         import oracle

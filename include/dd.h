@@ -170,6 +170,41 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
                      void *workspace, size_t workspace_bytes, void *stream);
 size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype);
 
+typedef enum {
+    DD_UNMASK_THRESH = 0,  /* every masked position whose drafter confidence exceeds the threshold */
+    DD_UNMASK_TOPK = 1     /* a fixed number per step: the k = floor(threshold) most confident masked positions */
+} dd_unmask_mode;
+
+/*
+ * One drafter unmasking step, x <- Unmask(p_D, x) (Alg. 1, drafting phase): the model's probabilities at the
+ * masked positions decide which of them are revealed (Sec. 2.1: "a subset of high-confidence tokens");
+ * the two selection rules are the ones Sec. 2.3 names: all tokens above a confidence threshold
+ * (confidence-aware parallel decoding) or a fixed number per step.  For P = B*G positions, softmax at
+ * temperature 1 over the whole vocabulary:
+ *     c_D,i = max_x p_D(x | i),  t_D,i = lowest x attaining it
+ *     candidate_i = (mask[i] != 0)                        -- only positions that still hold [MASK]
+ *     rank_i = number of candidates j of the same sequence with c_D,j > c_D,i, or equal with j < i
+ *     select_i = candidate_i and
+ *         DD_UNMASK_THRESH   c_D,i > threshold (strict, fp32)  or  rank_i == 0
+ *                            (the most confident candidate is always taken, so that every step reveals
+ *                             at least one token per unfinished sequence; the paper leaves this open)
+ *         DD_UNMASK_TOPK     rank_i < floor(threshold), threshold >= 0 and finite (else DD_ERR_SHAPE)
+ *
+ *   logits_d [P,V] logit_dtype  drafter logits
+ *   mask     [P] u8             1 = position still holds [MASK], 0 = decoded
+ *   x_tokens [P] i32, optional  the sequence's token ids: x_tokens[i] = t_D,i is written where select_i,
+ *                               every other entry is left as it is (may be NULL)
+ *   out_mask   [P] u8   = mask[i] and not select_i
+ *   out_tokens [P] i32  = t_D,i     (every row)
+ *   out_conf   [P] f32  = c_D,i     (every row)
+ * Same shape rules, workspace and single-pass property as dd_verify_remask; out_mask must not alias mask.
+ */
+int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, float threshold,
+              int32_t *x_tokens, uint8_t *out_mask, int32_t *out_tokens, float *out_conf,
+              int B, int G, int V, dd_dtype logit_dtype,
+              void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_unmask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libdd_oracle.so")
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
+UNMASK_THRESH, UNMASK_TOPK = 0, 1
 
 
 def build(force: bool = False) -> str:
@@ -57,6 +58,9 @@ def lib():
         _lib.ora_remask_decide.restype = C.c_int
         _lib.ora_remask_decide.argtypes = [fp, C.POINTER(C.c_uint8), C.c_int, C.c_float, C.c_uint64,
                                            C.c_int, C.c_int, C.POINTER(C.c_uint8), dp]
+        _lib.ora_unmask_decide.restype = C.c_int
+        _lib.ora_unmask_decide.argtypes = [fp, C.POINTER(C.c_uint8), C.c_int, C.c_float, C.c_int, C.c_int,
+                                           C.POINTER(C.c_uint8)]
     return _lib
 
 
@@ -198,3 +202,30 @@ def verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed: i
     out_mask, prob = remask_decide(score32, mask, mode, threshold, seed, B, G)
     return {"out_mask": out_mask, "out_tokens": tok, "out_scores": score32, "kl": kl, "conf": conf,
             "prob": prob, "score64": score}
+
+
+def unmask_decide(conf32, mask, mode: int, threshold: float, B: int, G: int) -> np.ndarray:
+    """out_mask of one drafter unmasking step from fp32 confidences; see ora_unmask_decide in the C file."""
+    c = np.ascontiguousarray(conf32, dtype=np.float32).reshape(B * G)
+    m = np.ascontiguousarray(mask, dtype=np.uint8).reshape(B * G)
+    out = np.empty(B * G, dtype=np.uint8)
+    rc = lib().ora_unmask_decide(c.ctypes.data_as(C.POINTER(C.c_float)), m.ctypes.data_as(C.POINTER(C.c_uint8)),
+                                 mode, float(np.float32(threshold)), B, G, out.ctypes.data_as(C.POINTER(C.c_uint8)))
+    if rc != 0:
+        raise ValueError("oracle unmask_decide: bad argument")
+    return out
+
+
+def unmask(logits_d, mask, mode: int, threshold: float, B: int, G: int, dtype: int, x_tokens=None):
+    """Whole drafter unmasking step: confidence and most likely token of every row, then the selection.
+    Returns dict(out_mask, out_tokens, out_conf (fp32-rounded), conf64, x_tokens (updated copy or None))."""
+    _, conf, tok = verify_scores(None, logits_d, dtype)
+    conf32 = conf.astype(np.float32)
+    out_mask = unmask_decide(conf32, mask, mode, threshold, B, G)
+    m = np.asarray(mask).reshape(-1)
+    x = None
+    if x_tokens is not None:
+        x = np.array(x_tokens, dtype=np.int32).reshape(-1)
+        sel = (m != 0) & (out_mask == 0)
+        x[sel] = tok[sel]
+    return {"out_mask": out_mask, "out_tokens": tok, "out_conf": conf32, "conf64": conf, "x_tokens": x}

@@ -407,3 +407,41 @@ int ora_remask_decide(const float *score32, const uint8_t *mask, int mode, float
     }
     return 0;
 }
+
+/* ---------------------------------------------------------------- drafter unmasking step */
+
+/*
+ * x <- Unmask(p_D, x) of Alg. 1 (drafting phase): of the positions that still hold [MASK] (mask[i] != 0)
+ * a subset is revealed according to the drafter's confidence c_D,i = max_x p_D(x | i) (Sec. 2.1), given here
+ * rounded to fp32.  Selection rules (Sec. 2.3 names both):
+ *   mode 0  every candidate with c_D,i > tau, and in any case the most confident candidate of the sequence
+ *           (so that each step reveals something; the paper leaves the empty case open)
+ *   mode 1  a fixed number per step: the k = floor(tau) most confident candidates
+ * "more confident" = larger c_D, equal values: the lower position.  Written as the definition: the rank of
+ * a candidate is the number of candidates of its sequence that are more confident than it.
+ * out_mask[i] = mask[i] != 0 and not selected_i.
+ */
+int ora_unmask_decide(const float *conf32, const uint8_t *mask, int mode, float threshold, int B, int G,
+                      uint8_t *out_mask)
+{
+    if (!conf32 || !mask || !out_mask || B < 0 || G < 0 || (mode != 0 && mode != 1))
+        return -1;
+    if (mode == 1 && !(threshold >= 0.0f && threshold <= 3.0e38f))
+        return -1;
+    for (int b = 0; b < B; ++b)
+        for (int g = 0; g < G; ++g) {
+            size_t i = (size_t)b * G + g;
+            int selected = 0;
+            if (mask[i] != 0) {
+                double rank = 0.0;
+                for (int h = 0; h < G; ++h) {
+                    size_t j = (size_t)b * G + h;
+                    if (mask[j] != 0 && (conf32[j] > conf32[i] || (conf32[j] == conf32[i] && h < g)))
+                        rank += 1.0;
+                }
+                selected = mode == 0 ? (conf32[i] > threshold || rank == 0.0) : rank < floor((double)threshold);
+            }
+            out_mask[i] = (uint8_t)(mask[i] != 0 && !selected);
+        }
+    return 0;
+}

@@ -14,6 +14,7 @@ from typing import Optional
 
 F32, BF16, FP8_E4M3 = 0, 1, 2
 TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
+UNMASK_THRESH, UNMASK_TOPK = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdd.so")
@@ -55,13 +56,17 @@ def lib():
     L.dd_verify_remask.argtypes = [vp, vp, vp, i, C.c_float, C.c_uint64, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_verify_remask_workspace_bytes.restype = sz
     L.dd_verify_remask_workspace_bytes.argtypes = [i, i, i, i]
+    L.dd_unmask.restype = i
+    L.dd_unmask.argtypes = [vp, vp, i, C.c_float, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.dd_unmask_workspace_bytes.restype = sz
+    L.dd_unmask_workspace_bytes.argtypes = [i, i, i, i]
     _lib = L
     return L
 
 
 EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attention_workspace_bytes",
            "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
-           "dd_verify_remask", "dd_verify_remask_workspace_bytes")
+           "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -199,3 +204,32 @@ def dd_verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed
     if rc != 0:
         raise DDError(rc, "dd_verify_remask")
     return out_mask, out_tokens, out_scores
+
+
+def dd_unmask_workspace_bytes(B, G, V, logit_dtype) -> int:
+    return lib().dd_unmask_workspace_bytes(B, G, V, logit_dtype)
+
+
+def dd_unmask(logits_d, mask, mode: int, threshold: float, B: int, G: int, x_tokens=None, out_mask=None,
+              out_tokens=None, out_conf=None, logit_dtype: Optional[int] = None):
+    """One drafter unmasking step.  logits_d [B*G, V]; mask [B*G] u8 (1 = still masked); x_tokens [B*G] i32
+    (optional, updated in place where a position is revealed).  Returns (out_mask u8, out_tokens i32, out_conf f32)."""
+    torch = _torch()
+    P, V = logits_d.shape
+    if P != B * G:
+        raise ValueError("logits_d must have B*G rows")
+    dt = _dtype_tag(logits_d, "logits_d") if logit_dtype is None else logit_dtype
+    dev = logits_d.device
+    if out_mask is None:
+        out_mask = torch.empty(P, dtype=torch.uint8, device=dev)
+    if out_tokens is None:
+        out_tokens = torch.empty(P, dtype=torch.int32, device=dev)
+    if out_conf is None:
+        out_conf = torch.empty(P, dtype=torch.float32, device=dev)
+    ws, wsn = _workspace(dd_unmask_workspace_bytes(B, G, V, dt), dev)
+    rc = lib().dd_unmask(_dev(logits_d, "logits_d"), _dev(mask, "mask"), int(mode), float(threshold),
+                         _dev(x_tokens, "x_tokens"), _dev(out_mask, "out_mask"), _dev(out_tokens, "out_tokens"),
+                         _dev(out_conf, "out_conf"), B, G, V, dt, _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_unmask")
+    return out_mask, out_tokens, out_conf

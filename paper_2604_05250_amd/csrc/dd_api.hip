@@ -189,4 +189,34 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
 }
 
+size_t dd_unmask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)
+{
+    return dd_verify_remask_workspace_bytes(B, G, V, logit_dtype);
+}
+
+int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, float threshold,
+              int32_t *x_tokens, uint8_t *out_mask, int32_t *out_tokens, float *out_conf,
+              int B, int G, int V, dd_dtype logit_dtype,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (mode != DD_UNMASK_THRESH && mode != DD_UNMASK_TOPK) return DD_ERR_MODE;
+    if (mode == DD_UNMASK_TOPK && !(threshold >= 0.0f && threshold <= 3.0e38f)) return DD_ERR_SHAPE;
+    if (logit_dtype != DD_F32 && logit_dtype != DD_BF16) return DD_ERR_DTYPE;
+    if (B < 0 || G < 0 || V < 1) return DD_ERR_SHAPE;
+    if ((double)B * G >= 2147483648.0) return DD_ERR_SHAPE;
+    const int eb = logit_dtype == DD_BF16 ? 2 : 4;
+    if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
+    if (B == 0 || G == 0) return DD_OK;
+    if (!logits_d || !mask || !out_mask || !out_tokens || !out_conf) return DD_ERR_NULL;
+    if (out_mask == mask) return DD_ERR_SHAPE;             // the selection reads every mask byte of a sequence
+    if (misaligned16(logits_d)) return DD_ERR_ALIGN;
+    const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(B * G, V, eb));
+    if (rc != DD_OK) return rc;
+    const hipError_t e = dd::launch_verify(nullptr, logits_d, mask,
+                                           mode == DD_UNMASK_TOPK ? dd::kModeUnmaskTopk : dd::kModeUnmaskThresh,
+                                           threshold, 0, out_mask, out_tokens, out_conf, B, G, V,
+                                           logit_dtype == DD_BF16, workspace, static_cast<hipStream_t>(stream), x_tokens);
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -30,10 +30,14 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipSt
 // Number of workgroups one logit row is split over, and workspace size.
 int verify_splits(int P, int V, int elem_bytes);
 size_t verify_workspace_bytes(int P, int V, int elem_bytes);
+// `mode`: a dd_mode value, or one of the two below for the drafter's unmasking step (logits_v then holds the
+// drafter's logits, logits_d is unused, and x_tokens - optional - receives the tokens of the selected rows).
+constexpr int kModeUnmaskThresh = 100, kModeUnmaskTopk = 101;
 hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
                          int mode, float threshold, uint64_t seed,
                          uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
-                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream);
+                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream,
+                         int32_t *x_tokens = nullptr);
 
 // ---- attention (attention_mfma.hip, attention_f32.hip) -------------------------
 // One description serves the verifier's full attention and the drafter's block attention:

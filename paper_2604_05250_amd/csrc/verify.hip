@@ -403,27 +403,24 @@ __global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restr
 // row, each lane a quarter of the comparisons; the sequence's scores pass through LDS in chunks and are
 // read back 16 bytes at a time (a scalar loop here is bound by the LDS latency of every single read).
 constexpr int kTopkRows = 64, kTopkChunk = 2048;
-__global__ __launch_bounds__(256) void verify_topk_kernel(const float *__restrict__ scores,
-                                                          const uint8_t *__restrict__ mask, int G, int kl_mode,
-                                                          float budget, uint8_t *__restrict__ out_mask)
+// Rank of row g among the rows of its sequence whose mask byte equals `want` (the candidates), ordered by
+// sign * score descending, equal values by row; -1 for a row that is no candidate.  Called by all 256 lanes
+// of a workgroup (it contains barriers); lanes 4r..4r+3 hold row r of the workgroup's 64 and all four
+// return its rank.
+__device__ __forceinline__ int sequence_rank(const float *__restrict__ scores, const uint8_t *__restrict__ mask,
+                                             size_t base, int G, int g, uint8_t want, float sign, float *bad_sh)
 {
-    __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];   // -inf marks a row that is not eligible
-    const int slabs = (G + kTopkRows - 1) / kTopkRows;        // workgroups per sequence
-    const int b = blockIdx.x / slabs, tid = threadIdx.x;
-    const size_t base = (size_t)b * G;
-    const float sign = kl_mode ? 1.0f : -1.0f;
-    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4, sub = tid % 4;
-    const bool mine = g < G;
-    const bool eligible = mine && mask[base + g] == 0;
-    const float bad = eligible ? sign * scores[base + g] : 0.0f;
+    const int tid = threadIdx.x, sub = tid % 4;
+    const bool candidate = g < G && mask[base + g] == want;
+    const float bad = candidate ? sign * scores[base + g] : 0.0f;
     int rank = 0;
     for (int c0 = 0; c0 < G; c0 += kTopkChunk) {             // uniform trip count: every lane reaches the barriers
         const int n = min(kTopkChunk, G - c0), n16 = (n + 15) & ~15;
         __syncthreads();
-        for (int j = tid; j < n16; j += 256)
-            bad_sh[j] = (j < n && mask[base + c0 + j] == 0) ? sign * scores[base + c0 + j] : kNegInf;
+        for (int j = tid; j < n16; j += 256)                 // -inf marks a row that is no candidate
+            bad_sh[j] = (j < n && mask[base + c0 + j] == want) ? sign * scores[base + c0 + j] : kNegInf;
         __syncthreads();
-        if (eligible) {
+        if (candidate) {
 #pragma unroll 4
             for (int j = 4 * sub; j < n16; j += 16) {
                 const float4 o = *reinterpret_cast<const float4 *>(&bad_sh[j]);
@@ -437,7 +434,42 @@ __global__ __launch_bounds__(256) void verify_topk_kernel(const float *__restric
     }
     rank += __shfl_xor(rank, 1);
     rank += __shfl_xor(rank, 2);
-    if (mine && sub == 0) out_mask[base + g] = (uint8_t)(mask[base + g] != 0 || (eligible && (float)rank < budget));
+    return candidate ? rank : -1;
+}
+
+__global__ __launch_bounds__(256) void verify_topk_kernel(const float *__restrict__ scores,
+                                                          const uint8_t *__restrict__ mask, int G, int kl_mode,
+                                                          float budget, uint8_t *__restrict__ out_mask)
+{
+    __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];
+    const int slabs = (G + kTopkRows - 1) / kTopkRows;        // workgroups per sequence
+    const int b = blockIdx.x / slabs, tid = threadIdx.x;
+    const size_t base = (size_t)b * G;
+    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4;
+    const int rank = sequence_rank(scores, mask, base, G, g, 0, kl_mode ? 1.0f : -1.0f, bad_sh);
+    if (g < G && tid % 4 == 0) out_mask[base + g] = (uint8_t)(mask[base + g] != 0 || (rank >= 0 && (float)rank < budget));
+}
+
+// Drafter unmasking (Alg. 1, drafting phase): of the positions that still hold [MASK], those selected by
+// confidence are decoded to the drafter's most likely token.  mode 0: confidence above the threshold, and
+// always the most confident one of the sequence; mode 1: the k most confident ones.
+__global__ __launch_bounds__(256) void unmask_select_kernel(const float *__restrict__ conf,
+                                                            const uint8_t *__restrict__ mask,
+                                                            const int32_t *__restrict__ tokens, int G, int mode,
+                                                            float threshold, uint8_t *__restrict__ out_mask,
+                                                            int32_t *__restrict__ x)
+{
+    __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];
+    const int slabs = (G + kTopkRows - 1) / kTopkRows;
+    const int b = blockIdx.x / slabs, tid = threadIdx.x;
+    const size_t base = (size_t)b * G;
+    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4;
+    const int rank = sequence_rank(conf, mask, base, G, g, 1, 1.0f, bad_sh);
+    if (g < G && tid % 4 == 0) {
+        const bool take = rank >= 0 && (mode == 0 ? (rank == 0 || conf[base + g] > threshold) : (float)rank < threshold);
+        out_mask[base + g] = (uint8_t)(mask[base + g] != 0 && !take);
+        if (take && x) x[base + g] = tokens[base + g];
+    }
 }
 
 int env_int(const char *name, int dflt)
@@ -494,7 +526,8 @@ static hipError_t launch_row_kernel(int threads, dim3 grid, hipStream_t stream, 
 hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
                          int mode, float threshold, uint64_t seed,
                          uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
-                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream)
+                         int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream,
+                         int32_t *x_tokens)
 {
     const int P = B * G;
     if (P == 0) return hipSuccess;
@@ -532,6 +565,11 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     if (e != hipSuccess) return e;
     if (mode == 3)
         e = launch(verify_klprob_kernel, dim3(B), dim3(256), stream, (const float *)out_scores, mask, G, seed, out_mask);
+    if (mode == kModeUnmaskThresh || mode == kModeUnmaskTopk)
+        // the pass above ran as for the Trust rule on the drafter's logits: confidence and argmax of every row
+        return launch(unmask_select_kernel, dim3((unsigned)((long)((G + kTopkRows - 1) / kTopkRows) * B)), dim3(256),
+                      stream, (const float *)out_scores, mask, (const int32_t *)out_tokens, G, mode - kModeUnmaskThresh,
+                      mode == kModeUnmaskTopk ? floorf(threshold) : threshold, out_mask, x_tokens);
     if (mode == 5 || mode == 6)
         e = launch(verify_topk_kernel, dim3((unsigned)((long)((G + kTopkRows - 1) / kTopkRows) * B)), dim3(256), stream,
                    (const float *)out_scores, mask, G, kl ? 1 : 0, floorf(threshold), out_mask);

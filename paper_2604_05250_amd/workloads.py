@@ -30,6 +30,7 @@ import numpy as np
 F32, BF16, FP8_E4M3 = 0, 1, 2
 # remask modes: numerically equal to dd_mode in include/dd.h
 TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
+UNMASK_THRESH, UNMASK_TOPK = 0, 1
 MODE_NAMES = {TRUST: "trust", KL_THRESH: "kl_thresh", CONF_THRESH: "conf_thresh",
               KL_PROB: "kl_prob", CONF_PROB: "conf_prob", KL_TOPK: "kl_topk", CONF_TOPK: "conf_topk"}
 

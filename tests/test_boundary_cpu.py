@@ -84,6 +84,22 @@ def test_verify_argument_validation():
     assert call(ws=FAKE, wsn=need - 1) == -5
 
 
+def test_unmask_argument_validation():
+    L = dd.lib()
+
+    def call(ld=FAKE, mask=FAKE, mode=dd.UNMASK_THRESH, tau=0.5, x=None, om=FAKE + 4096, ot=FAKE, oc=FAKE, B=2, G=8,
+             V=1024, dt=dd.BF16, ws=None, wsn=0):
+        return L.dd_unmask(ld, mask, mode, C.c_float(tau), x, om, ot, oc, B, G, V, dt, ws, wsn, None)
+    assert call(mode=2) == -4 and call(mode=-1) == -4
+    assert call(mode=dd.UNMASK_TOPK, tau=-1.0) == -2 and call(mode=dd.UNMASK_TOPK, tau=float("nan")) == -2
+    assert call(dt=dd.FP8_E4M3) == -3 and call(B=-1) == -2 and call(V=0) == -2 and call(V=1001) == -6
+    assert call(ld=None) == -1 and call(mask=None) == -1 and call(om=None) == -1 and call(oc=None) == -1
+    assert call(om=FAKE) == -2                             # out_mask must not alias mask
+    assert call() == -5                                    # everything valid except the missing workspace
+    assert call(B=0) == 0 and call(G=0) == 0
+    assert L.dd_unmask_workspace_bytes(2, 8, 1024, dd.BF16) == L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     q = torch.zeros(1, 1, 4, 64)

@@ -283,3 +283,81 @@ def test_cfg3_budgeted_kl():
     kl, _, tok = oracle.verify_scores(inp["logits_d"], inp["logits_v"], cfg.logit_dtype, rows=rows)
     assert np.array_equal(ot[rows], tok)
     assert_scores_close(osc[rows], kl, "cfg3 budgeted KL (sampled rows)")
+
+
+# ------------------------------------------------------------------ drafter unmasking step (dd_unmask)
+def check_unmask(inp, mask, mode, thr, B, G, dtype, what, x0=None):
+    import torch
+    x_dev = None if x0 is None else to_dev(x0.copy())
+    om, ot, oc = dd.dd_unmask(to_dev(inp["logits_d"]), to_dev(mask), mode, thr, B, G, x_tokens=x_dev, logit_dtype=dtype)
+    torch.cuda.synchronize()
+    om, ot, oc = om.cpu().numpy(), ot.cpu().numpy(), oc.cpu().numpy()
+    ora = oracle.unmask(inp["logits_d"], mask, mode, thr, B, G, dtype, x_tokens=x0)
+    assert np.array_equal(ot, ora["out_tokens"]), f"{what}: argmax tokens differ"
+    assert_scores_close(oc, ora["conf64"], what)
+    # the selection itself, applied to the GPU's own fp32 confidences: exact
+    assert np.array_equal(om, oracle.unmask_decide(oc, mask, mode, thr, B, G)), f"{what}: selection rule"
+    # against the oracle's confidences: exact except where a confidence is within the score tolerance of what decides
+    c = ora["conf64"].reshape(B, G)
+    m2 = mask.reshape(B, G)
+    exempt = np.zeros((B, G), bool)
+    for b in range(B):
+        cand = np.flatnonzero(m2[b])
+        if len(cand) == 0:
+            continue
+        srt = np.sort(c[b][cand])[::-1]
+        edges = [srt[0]]
+        if mode == wl.UNMASK_THRESH:
+            edges.append(thr)
+        else:
+            k = int(thr)
+            if 0 < k < len(cand):
+                edges.append(srt[k - 1])
+        for e in edges:
+            exempt[b] |= np.abs(c[b] - e) <= 2e-3 * abs(e) + 2e-6
+    diff = (om != ora["out_mask"]) & ~exempt.reshape(-1)
+    assert not diff.any(), f"{what}: selections differ at rows {np.nonzero(diff)[0][:8]}"
+    assert (om[mask == 0] == 0).all() and (om <= mask).all()          # decoded stays decoded; nothing gets masked
+    if x0 is not None:
+        x = x_dev.cpu().numpy()
+        sel = (mask != 0) & (om == 0)
+        assert np.array_equal(x[sel], ot[sel]) and np.array_equal(x[~sel], x0[~sel])
+    return om
+
+
+@pytest.mark.parametrize("mode", [wl.UNMASK_THRESH, wl.UNMASK_TOPK])
+def test_unmask_small_and_fused_paths(mode):
+    for (B, G, V, dtype, frac) in ((3, 50, 4096, wl.BF16, 0.4), (4, 300, 1000, wl.BF16, 0.5), (1, 64, 1024, wl.F32, 0.2),
+                                   (2, 2500, 520, wl.F32, 0.7), (2, 16, 126464, wl.BF16, 0.0)):
+        cfg = wl.custom_config(B=B, G=G, V=V, logit_dtype=dtype, sigma_d=3.0, sigma_n=1.0, decoded_frac=frac)
+        inp = wl.verify_inputs(cfg, seed=G + 1)
+        mask = inp["mask"]
+        x0 = np.full(cfg.P, 126336, np.int32)
+        conf = oracle.verify_scores(None, inp["logits_d"], dtype)[1]
+        thrs = (0.0, float(np.median(conf)), 2.0) if mode == wl.UNMASK_THRESH else (0.0, 1.0, 7.0, float(G // 3), float(10 * G))
+        for thr in thrs:
+            om = check_unmask(inp, mask, mode, thr, B, G, dtype, f"unmask mode {mode} thr {thr} B{B} G{G} V{V}", x0=x0)
+            if mode == wl.UNMASK_THRESH and thr == 2.0:               # nothing exceeds: exactly one per unfinished sequence
+                assert ((mask.reshape(B, G) != 0).sum(1) - om.reshape(B, G).sum(1) == (mask.reshape(B, G).any(1))).all()
+
+
+def test_unmask_ties_and_finished_sequences():
+    cfg = wl.custom_config(B=3, G=96, V=2048, logit_dtype=wl.BF16, sigma_d=3.0, sigma_n=1.0)
+    inp = wl.verify_inputs(cfg, seed=8)
+    a = inp["logits_d"].reshape(cfg.B, cfg.G, -1)
+    a[:, 8:, :] = a[:, np.arange(8, cfg.G) % 8, :]                    # 12 copies of 8 distinct rows: exact ties
+    mask = np.ones(cfg.P, np.uint8); mask[3::7] = 0
+    mask.reshape(cfg.B, cfg.G)[1] = 0                                  # sequence 1 is finished
+    for k in (1, 5, 13, 40):
+        om = check_unmask(inp, mask, wl.UNMASK_TOPK, float(k), cfg.B, cfg.G, wl.BF16, f"unmask ties k={k}")
+        assert not om.reshape(cfg.B, cfg.G)[1].any()
+    check_unmask(inp, mask, wl.UNMASK_THRESH, 0.05, cfg.B, cfg.G, wl.BF16, "unmask ties threshold")
+
+
+def test_unmask_block_of_cfg3():
+    # one draft step of cfg3: the drafter's logits of the active block (64 positions per sequence)
+    cfg = wl.CONFIGS[3]
+    blk = wl.custom_config(B=cfg.B, G=cfg.bl, V=cfg.V, logit_dtype=cfg.logit_dtype, sigma_d=cfg.sigma_d, sigma_n=cfg.sigma_n,
+                           decoded_frac=0.25)
+    inp = wl.verify_inputs(blk, seed=0)
+    check_unmask(inp, inp["mask"], wl.UNMASK_THRESH, 0.02, blk.B, blk.G, blk.logit_dtype, "cfg3 block unmask")

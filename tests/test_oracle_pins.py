@@ -329,6 +329,66 @@ def test_budgeted_rules():
         oracle.remask_decide(d, m0, KL_TOPK, -1.0, 0, 1, G)
 
 
+def test_unmask_step_rules():
+    from oracle import UNMASK_THRESH, UNMASK_TOPK
+    # hand-checked: candidates are the positions that still hold [MASK]
+    conf = np.array([0.9, 0.2, 0.6, 0.6, 0.95, 0.1,   0.3, 0.3, 0.2, 0.99, 0.1, 0.3], np.float32)
+    mask = np.array([1, 1, 1, 1, 0, 1,                  1, 1, 1, 0, 0, 0], np.uint8)
+    t = oracle.unmask_decide(conf, mask, UNMASK_THRESH, 0.5, 2, 6)
+    # sequence 0: 0.9, 0.6, 0.6 exceed 0.5; sequence 1: nothing exceeds, the first of the tied 0.3 is taken anyway
+    assert t.tolist() == [0, 1, 0, 0, 0, 1,   0, 1, 1, 0, 0, 0]
+    k = oracle.unmask_decide(conf, mask, UNMASK_TOPK, 2.5, 2, 6)        # k = 2
+    assert k.tolist() == [0, 1, 0, 1, 0, 1,   0, 0, 1, 0, 0, 0]        # 0.9 and the first 0.6 | both masked 0.3
+    # decoded positions never change; a sequence without masked positions stays as it is
+    done = np.zeros(12, np.uint8)
+    assert not oracle.unmask_decide(conf, done, UNMASK_THRESH, 0.0, 2, 6).any()
+    # threshold extremes: +inf reveals exactly the most confident candidate per sequence, -inf all of them
+    B, G = 5, 130
+    rng = np.random.default_rng(4)
+    cf = (rng.integers(1, 50, B * G) / 50.0).astype(np.float32)
+    mk = (rng.random(B * G) < 0.6).astype(np.uint8)
+    mk.reshape(B, G)[3] = 0
+    hi = oracle.unmask_decide(cf, mk, UNMASK_THRESH, np.inf, B, G).reshape(B, G)
+    lo = oracle.unmask_decide(cf, mk, UNMASK_THRESH, -np.inf, B, G)
+    assert not lo.any()
+    for b in range(B):
+        cand = np.flatnonzero(mk.reshape(B, G)[b])
+        revealed = np.flatnonzero((mk.reshape(B, G)[b] != 0) & (hi[b] == 0))
+        if len(cand) == 0:
+            assert len(revealed) == 0
+        else:
+            best = cand[np.argmax(cf.reshape(B, G)[b][cand])]               # np.argmax: first of equal maxima
+            assert revealed.tolist() == [best]
+    # fixed number per step against a stable argsort; nested in k; threshold rule = union of "above tau" and the best one
+    prev = mk
+    for kk in (0, 1, 3, 40, 130, 500):
+        got = oracle.unmask_decide(cf, mk, UNMASK_TOPK, float(kk), B, G).reshape(B, G)
+        want = mk.copy().reshape(B, G)
+        for b in range(B):
+            cand = np.flatnonzero(mk.reshape(B, G)[b])
+            order = cand[np.argsort(-cf.reshape(B, G)[b][cand], kind="stable")]
+            want[b, order[:kk]] = 0
+        assert np.array_equal(got, want), kk
+        assert (got.reshape(-1) <= prev).all()                              # a larger k never reveals less
+        prev = got.reshape(-1)
+    tau = 0.7
+    th = oracle.unmask_decide(cf, mk, UNMASK_THRESH, tau, B, G)
+    one = oracle.unmask_decide(cf, mk, UNMASK_TOPK, 1.0, B, G)
+    assert np.array_equal(th, ((mk != 0) & ~(cf > np.float32(tau)) & (one != 0)).astype(np.uint8))
+    # the whole step on logits: confidence = library softmax maximum, tokens written only where revealed
+    cfg = wl.CONFIGS[1]
+    inp = wl.verify_inputs(cfg, seed=1)
+    m = (np.arange(cfg.P) % 4 != 0).astype(np.uint8)
+    x = np.full(cfg.P, -7, np.int32)
+    out = oracle.unmask(inp["logits_d"], m, UNMASK_TOPK, 5.0, cfg.B, cfg.G, F32, x_tokens=x)
+    p = sp.softmax(inp["logits_d"].astype(np.float64), axis=1)
+    assert np.allclose(out["conf64"], p.max(1), rtol=1e-12)
+    assert np.array_equal(out["out_tokens"], p.argmax(1))
+    sel = (m != 0) & (out["out_mask"] == 0)
+    assert sel.sum() == 5 * cfg.B
+    assert np.array_equal(out["x_tokens"][sel], p.argmax(1)[sel]) and (out["x_tokens"][~sel] == -7).all()
+
+
 # ------------------------------------------------------------------ attention
 def _rand_qkv(rng, B, H, Hkv, N, d, Nq=None):
     Nq = N if Nq is None else Nq
