@@ -210,17 +210,28 @@ def main():
     ver_gbps = verify_bytes / (t_ver * 1e-3) / 1e9
     blk_gbps = block_bytes / (t_block / cfg.K * 1e-3) / 1e9
 
+    def attn_kernel_name(c):
+        """The kernel the library's size rule picks for this call (the rule itself lives in the library)."""
+        group = c.H // c.Hkv
+        wide_tiles = c.B * c.Hkv * -(-group * c.N // 256)
+        fp8 = c.qk_dtype == wl.FP8_E4M3
+        if wide_tiles >= 192 and c.N >= 512 and (not fp8 or c.d == 128):
+            return f"attn_wide_kernel<{c.d}, {'true' if fp8 else 'false'}>"
+        if not fp8 and c.B * c.Hkv * -(-group * c.N // 128) < 256:
+            return f"attn_stream_kernel<{c.d}>"
+        return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false>"
+
     # the peak the attention call is priced against: each contraction at the peak of its own operand type
     if cfg.qk_dtype == wl.F32:
         attn_kernel, attn_bound, attn_peak = "attn_f32_kernel", "alu", PEAK_FP32_VALU_TFLOPS
         attn_peak_note = "fp32 inputs: vector ALUs (no fp32 MFMA path is used), 157.3 TFLOP/s"
     elif cfg.qk_dtype == wl.FP8_E4M3:
-        attn_kernel, attn_bound = "attn_wide_kernel<128, fp8> (large shapes) / attn_mfma_kernel", "mfma"
+        attn_kernel, attn_bound = attn_kernel_name(cfg), "mfma"
         attn_peak = 2.0 / (1.0 / PEAK_FP8_TFLOPS + 1.0 / PEAK_BF16_TFLOPS)
         attn_peak_note = ("half of the FLOPs (S = Q K^T) run as fp8 MFMA (5.0 PFLOP/s), half (O = P V) as bf16 MFMA "
                           "(2.5 PFLOP/s): time-weighted peak 3.33 PFLOP/s")
     else:
-        attn_kernel, attn_bound, attn_peak = "attn_wide_kernel / attn_stream_kernel / attn_mfma_kernel by size", "mfma", PEAK_BF16_TFLOPS
+        attn_kernel, attn_bound, attn_peak = attn_kernel_name(cfg), "mfma", PEAK_BF16_TFLOPS
         attn_peak_note = "dense bf16 MFMA, 2.5 PFLOP/s"
 
     out = {
@@ -243,7 +254,9 @@ def main():
                      "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
                      "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),
                      "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
-        "roofline_verify": {"kernel": "verify_partial_kernel + verify_finalize_kernel (dd_verify_remask)",
+        "roofline_verify": {"kernel": ("verify_row_kernel" if cfg.P >= 192 else "verify_partial_kernel + verify_finalize_kernel")
+                                      + {wl.KL_PROB: " + verify_klprob_kernel", wl.KL_TOPK: " + verify_topk_kernel",
+                                         wl.CONF_TOPK: " + verify_topk_kernel"}.get(mode, "") + " (dd_verify_remask)",
                             "bound": "hbm", "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": round(ver_gbps / PEAK_HBM_GBPS, 4),
                             "traffic": PROFILED_TRAFFIC_BYTES["verify"].get(args.config),
