@@ -60,6 +60,7 @@ def parse():
     ap.add_argument("--verify-threshold", type=float, default=0.0)
     ap.add_argument("--unmask-threshold", type=float, default=0.9,
                     help="confidence threshold of the optional 'unmask' part (add it to --parts)")
+    ap.add_argument("--no-graph", action="store_true", help="skip the additional HIP-graph replay of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -197,6 +198,24 @@ def main():
         assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
     t_block, t_attn, t_ver = (max(t, 1e-9) for t in (t_block, t_attn, t_ver))
 
+    # the same steps replayed as HIP graphs (one per input set): what the cycle costs without the host in the loop
+    graph_ms = None
+    if not args.no_graph:
+        from paper_2604_05250_amd.step import capture_step
+        graphs = [capture_step(lambda i=i: step(i)) for i in range(n_sets)]
+        for i in range(args.warmup):
+            graphs[i % n_sets].replay()
+        torch.cuda.synchronize()
+        g_begin, g_end = ev(), ev()
+        g_begin.record()
+        for i in range(args.steps):
+            graphs[(args.warmup + i) % n_sets].replay()
+        g_end.record()
+        torch.cuda.synchronize()
+        graph_ms = g_begin.elapsed_time(g_end) / args.steps
+        if "verify" in parts:
+            assert torch.isfinite(out_sc).all().item(), "non-finite verification scores after graph replay"
+
     if args.calib_copy_mb > 0:
         src = torch.empty(args.calib_copy_mb << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -249,6 +268,10 @@ def main():
         "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
         "block_attention_GBps": round(blk_gbps, 1),
+        "graph_replay": None if graph_ms is None else {
+            "ms_per_step": round(graph_ms, 4),
+            "note": "the same steps captured once per input set and replayed as HIP graphs; ms_per_step above is the eager "
+                    "sequence of calls through the Python binding"},
         "roofline": {"kernel": attn_kernel, "bound": attn_bound,
                      "achieved": round(attn_tflops, 3), "peak": round(attn_peak, 1), "unit": "TFLOP/s",
                      "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
