@@ -114,6 +114,15 @@ __device__ __forceinline__ void qk_next(floatx16 &s, const KT kf, const QT qfrag
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
 }
 
+// A wave-uniform pointer that the compiler happens to hold in vector registers, as a scalar register pair
+// (a no-op when it already is one).
+__device__ __forceinline__ const uint8_t *scalar_ptr(const uint8_t *p)
+{
+    const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return reinterpret_cast<const uint8_t *>(((unsigned long long)hi << 32) | lo);
+}
+
 // s_waitcnt immediate: wait until at most n vector-memory operations are outstanding, nothing else
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
@@ -130,7 +139,12 @@ using T_ = std::true_type;
 using F_ = std::false_type;
 
 // FP8: Q and K are fp8 e4m3 (with per-head scales folded into the exponent's factor), V and O bf16.
-template <int D, bool FP8>
+// BLOCK: the drafter's form of the call (Sec. 2.3) - the rows are the active block's queries, the key stream
+// is cache rows [0, block_start), the block tensors' rows, cache rows [block_start + block_len, N) (each
+// part a whole number of 64-row tiles by the same overlap rule, so each part is empty or at least 64 rows:
+// the launcher checks), a workgroup takes one row tile and one of `splits` ranges of the tile list, and
+// with splits > 1 writes its unnormalised state for the merge kernel instead of O.
+template <int D, bool FP8, bool BLOCK>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_wide_kernel(const AttnKernelArgs a)
 {
@@ -179,22 +193,41 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // w, w + G, w + 2G ...: at any time the G workgroups are on consecutive tiles, so neighbours work on the
     // same K/V, and neighbours are placed on the same XCD (own L2 each).
     const int tiles_total = a.B * a.Hkv * a.row_tiles;
-    const int t_stride = gridDim.x;
-    int t_cur;
+    int t_stride = gridDim.x;
+    int t_cur, split = 0;
     {
         const int G = gridDim.x, per = G >> 3, rem = G & 7;
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         t_cur = xcd * per + min(xcd, rem) + slot;
     }
+    if (BLOCK) {                                     // one (row tile, key split) per workgroup, no second tile
+        split = t_cur % a.splits;
+        t_cur /= a.splits;
+        t_stride = tiles_total;
+    }
     const int rows_total = a.group * a.Nq;           // query rows per (batch, kv head); contiguous in memory
     const int nkeys = a.N;
-    const int nt_even = ((nkeys + TKW - 1) / TKW + 1) & ~1;   // tiles per pass, padded to an even count
-    struct Tile { const uint8_t *k, *v; size_t row_base; int v0, bh0, kvs; };
+    // Key stream as a list of 64-row tiles.  Not BLOCK: one part, rows [0, N).  BLOCK: up to three parts.
+    const int len_a = BLOCK && a.block_len ? a.block_start : nkeys;
+    const int len_b = BLOCK ? a.block_len : 0;
+    const int len_c = BLOCK && a.block_len ? nkeys - a.block_start - a.block_len : 0;
+    const int nt_a = (len_a + TKW - 1) / TKW, nt_b = (len_b + TKW - 1) / TKW, nt_c = (len_c + TKW - 1) / TKW;
+    const int nt_all = nt_a + nt_b + nt_c;
+    const int nt_per_split = BLOCK ? (nt_all + a.splits - 1) / a.splits : nt_all;
+    const int t_first = split * nt_per_split;                               // this workgroup's tiles of the list
+    const int nt_local = min(nt_all, t_first + nt_per_split) - t_first;
+    const int nt_even = (nt_local + 1) & ~1;         // tiles per pass, padded to an even count
+    struct Tile { const uint8_t *k, *v, *kb, *vb; size_t row_base; int v0, bh0, kvs; };
     auto tile_of = [&](int t) __attribute__((always_inline)) {
         const int rt = t % a.row_tiles, bk = t / a.row_tiles, kvh = bk % a.Hkv, b = bk / a.Hkv;
         Tile r;
         r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.N * (size_t)KROWB;
         r.v = static_cast<const uint8_t *>(a.V) + (size_t)bk * a.N * (size_t)ROWB;
+        r.kb = r.vb = nullptr;
+        if (BLOCK && a.block_len) {
+            r.kb = static_cast<const uint8_t *>(a.Kblk) + (size_t)bk * a.block_len * (size_t)KROWB;
+            r.vb = static_cast<const uint8_t *>(a.Vblk) + (size_t)bk * a.block_len * (size_t)ROWB;
+        }
         r.bh0 = b * a.H + kvh * a.group;             // first query head of the group
         r.row_base = (size_t)r.bh0 * a.Nq;           // row of virtual row 0 in Q and O
         r.v0 = rt * kRowsWGWide;                     // first virtual row of the tile
@@ -219,13 +252,36 @@ void attn_wide_kernel(const AttnKernelArgs a)
     const int dma_krow0 = wave * KDMA_ROWS + lane / KCH;
     const unsigned dma_koff = dma_krow0 * KROWB + ((lane % KCH) ^ (dma_krow0 & 7)) * 16;
     const unsigned dma_voff = dma_row0 * ROWB + ((lane % CH) ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
-    const int last_start = nkeys - TKW;                                    // >= 0: checked by the launcher
-    auto tile_start = [&](int tile) __attribute__((always_inline)) { return min(tile * TKW, last_start); };
+    // Tile `tile` of this workgroup's pass: where its 64 rows start in memory (K and V side), and how many of
+    // its leading rows are masked (`shift`): the rows a last tile shares with its predecessor, or all 64 of
+    // a stand-in tile past the end of the pass.  All of it is scalar arithmetic.
+    struct TileAt { const uint8_t *k, *v; int shift; };
+    auto tile_at = [&](const Tile &t, int tile) __attribute__((always_inline)) {
+        // (every captured value is copied before any choice is made between them: the compiler otherwise
+        // turns "choose one of several loaded values" into a load through a chosen address, which pins the
+        // captured variables in scratch memory)
+        const int la = len_a, lb = len_b, lc = len_c, na = nt_a, nb = nt_b, nl = nt_local, tf = t_first;
+        const int c_row0 = a.block_start + a.block_len;
+        const uint8_t *const ck = t.k, *const cv = t.v, *const bk = t.kb, *const bv = t.vb;
+        const bool standin = tile >= nl;
+        int T = tf + min(tile, nl - 1);                                      // position in the list
+        const bool in_c = BLOCK && T >= na + nb, in_b = BLOCK && !in_c && T >= na;
+        T -= in_c ? na + nb : in_b ? na : 0;                                 // position in its part
+        const int len = in_c ? lc : in_b ? lb : la;
+        const int row0 = in_c ? c_row0 : 0;
+        const uint8_t *kp = in_b ? bk : ck, *vp = in_b ? bv : cv;
+        const int start = min(T * TKW, len - TKW);                           // len >= 64: checked by the launcher
+        TileAt r;
+        r.k = kp + (size_t)(row0 + start) * KROWB;
+        r.v = vp + (size_t)(row0 + start) * ROWB;
+        r.shift = standin ? TKW : T * TKW - start;
+        return r;
+    };
     // one load (index i) of the tile whose first row is at `glob`
     auto dma_one = [&](uint4 *dst, const uint8_t *glob, unsigned lane_off, int i) __attribute__((always_inline)) {
         static_assert(4 * DMA_ROWS * ROWB == 4096 && 4 * KDMA_ROWS * KROWB == 4096, "loads of a wave are 4 KB apart");
         const int mid = 4096 + 8192 * (i >> 1);
-        const uint8_t *sbase = glob + mid;                                 // uniform: a scalar register pair
+        const uint8_t *sbase = scalar_ptr(glob + mid);                     // uniform: a scalar register pair
         const unsigned d = lds_addr(dst) + wave * 1024 + mid;
         // Written as assembly so that the address stays "scalar base + 32-bit lane offset + immediate" (the
         // compiler prefers to carry a 64-bit address per lane and per load).  It therefore knows nothing of
@@ -266,7 +322,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 off[par] = drow * KROWB + (dpos ^ ((par * KDMA_ROWS + drow) & 7)) * 16;
             static_for<NQDMA>([&](auto ic) __attribute__((always_inline)) {
                 constexpr int i = decltype(ic)::value, mid = 4096 + 8192 * (i / 8), imm = i * 1024 - mid;
-                const uint8_t *sbase = qg + mid;
+                const uint8_t *sbase = scalar_ptr(qg + mid);
                 const unsigned d = dst + mid, o = off[(i * KDMA_ROWS / 4) & 1];
                 if constexpr (imm >= 0)
                     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2 offset:%3"
@@ -319,6 +375,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     };
     float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
     float thr[QB] = {-INFINITY, -INFINITY};          // raw scores above (mc + slack) / c raise the maximum in use
+    float mc_done[QB] = {-INFINITY, -INFINITY};      // the finished tile's maximum in use (BLOCK: part of its state)
     intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
 
@@ -394,6 +451,30 @@ void attn_wide_kernel(const AttnKernelArgs a)
         char *region = reinterpret_cast<char *>(QO) + wave * QOW;
         int ln = lane;
         asm volatile("" : "+v"(ln));
+        if constexpr (BLOCK) {
+            if (a.splits > 1) {
+                // one of several key ranges: the unnormalised state (O, maximum in use, row sum) goes to the
+                // merge kernel, row r of the call at [(r * splits + split)]
+#pragma unroll
+                for (int q = 0; q < QB; ++q) {
+                    const int v = t.v0 + wave * kRowsWave + q * 32 + (ln & 31);
+                    if (v >= rows_total) continue;
+                    const size_t slot = (t.row_base + v) * (size_t)a.splits + split;
+                    float *po = a.part_o + slot * D + (ln >> 5) * 4;
+#pragma unroll
+                    for (int i = 0; i < DC; ++i)
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4)
+                            *reinterpret_cast<float4 *>(po + i * 32 + q4 * 8) =
+                                make_float4(acc[q][i][4 * q4], acc[q][i][4 * q4 + 1], acc[q][i][4 * q4 + 2], acc[q][i][4 * q4 + 3]);
+                    if ((ln >> 5) == 0) {
+                        a.part_ml[slot * 2] = mc_done[q];
+                        a.part_ml[slot * 2 + 1] = acc_l[q][0];
+                    }
+                }
+                return;
+            }
+        }
         char *wbase = region + (ln & 31) * OPITCH + (ln >> 5) * 8;
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
@@ -465,7 +546,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
         // rows of unit u's tile that lie before its nominal start repeat keys of the previous tile
-        const int lim = (u >> 1) * TKW - tile_start(u >> 1) - 32 * (u & 1);
+        const int lim = tile_at(cur, u >> 1).shift - 32 * (u & 1);
         if (__builtin_expect(lim > 0, 0)) {                  // uniform branch: those score -inf
             int k0 = 4 * hh;
             asm volatile("" : "+v"(k0));
@@ -474,6 +555,16 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     if (k0 + 8 * (r >> 2) + (r & 3) < lim) s_cur[q][r] = -INFINITY;
+            // A key range that starts with a wholly masked unit (BLOCK: a split may begin at a part's
+            // overlapping last tile) has no maximum yet: give it a finite one, so that its weights are 0, not NaN.
+            if (BLOCK && lim >= 32) {
+#pragma unroll
+                for (int q = 0; q < QB; ++q)
+                    if (mc[q] == -INFINITY) {
+                        mc[q] = 0.f;
+                        thr[q] = kSlack / c[q];
+                    }
+            }
         }
         float corr[QB], tpart[QB], pe[32];
         bool changed = false;
@@ -611,7 +702,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         constexpr int PAR = decltype(par)::value, KIND = decltype(kind)::value;
         static_assert(KIND == 0 || (KIND == 1 && PAR == 0) || (KIND == 2 && PAR == 1), "stage kinds");
         constexpr bool last = KIND == 2;
-        if (last && has_next) {
+        if (!BLOCK && last && has_next) {
             // the Q rows were requested a stage ago and deliberately not waited for at its barrier
 #ifdef DDW_TIMING2
             const unsigned long long ta = __builtin_readcyclecounter();
@@ -627,10 +718,12 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
         const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
-             kbuf(I_<PAR>{}), (KIND == 0 ? cur.k : nxt.k) + (size_t)tile_start(ktile) * KROWB,
-             vbuf(I_<1 - PAR>{}), (last ? nxt.v : cur.v) + (size_t)tile_start(vtile) * ROWB, F_{}, false, cur);
-        if (KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
+             kbuf(I_<PAR>{}), tile_at(KIND == 0 || BLOCK ? cur : nxt, ktile).k,
+             vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur);
+        if (!BLOCK && KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
+            mc_done[0] = mc[0];
+            mc_done[1] = mc[1];
             mc[0] = mc[1] = -INFINITY;                       // the second step starts the next tile's softmax
             thr[0] = thr[1] = -INFINITY;
             c[0] = c_next[0];
@@ -642,7 +735,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // order, so the requests issued after those loads - the next tile's Q rows, the finished tile's
         // output rows - can stay in flight: wait until only that many are outstanding.
         constexpr int NST = kRowsWave / (64 / (ROWB / 16));  // output stores per wave
-        if (KIND == 1 && has_next) wait_loads_and_sync(I_<NQDMA>{});
+        if (!BLOCK && KIND == 1 && has_next) wait_loads_and_sync(I_<NQDMA>{});
         else if (last && cur.v0 + kRowsWGWide <= rows_total) {
 #ifdef DDW_TIMING2
             const unsigned long long ta = __builtin_readcyclecounter();
@@ -657,9 +750,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // ---- prologue of the first row tile: Q rows and K tiles 0, 1 and V tile 0 go straight to LDS
     dma_q(cur);
-    dma_tile(K0, cur.k, dma_koff, I_<NDMA_K>{});
-    dma_tile(V0, cur.v, dma_voff, I_<NDMA>{});
-    dma_tile(K1, cur.k + (size_t)tile_start(1) * KROWB, dma_koff, I_<NDMA_K>{});
+    dma_tile(K0, tile_at(cur, 0).k, dma_koff, I_<NDMA_K>{});
+    dma_tile(V0, tile_at(cur, 0).v, dma_voff, I_<NDMA>{});
+    dma_tile(K1, tile_at(cur, 1).k, dma_koff, I_<NDMA_K>{});
     wait_loads_and_sync(I_<0>{});
     install_q(cur);
     c[0] = c_next[0];
@@ -688,8 +781,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
     const unsigned long long t_loop = __builtin_readcyclecounter();
 #endif
     for (;;) {
-        has_next = t_cur + t_stride < tiles_total;
-        if (has_next) nxt = tile_of(t_cur + t_stride);
+        has_next = !BLOCK && t_cur + t_stride < tiles_total;
+        if (!BLOCK && has_next) nxt = tile_of(t_cur + t_stride);
         int sp = 0;
 #ifdef DDW_TIMING2
         const unsigned long long t0 = __builtin_readcyclecounter();
@@ -710,7 +803,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         const unsigned long long t3 = __builtin_readcyclecounter();
         tacc[0] += t1 - t0; tacc[1] += t2 - t1; tacc[2] += t3 - t2;
 #endif
-        if (!has_next) break;
+        if (BLOCK || !has_next) break;
         cur = nxt;
         t_cur += t_stride;
     }
@@ -748,10 +841,60 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)wgs), block(kAttnThreads);
     if (a.qk_dtype == 2) {
         if (a.d != 128) return hipErrorInvalidValue;      // 64-byte fp8 rows are not worth a variant
-        return launch(attn_wide_kernel<128, true>, grid, block, stream, k);
+        return launch(attn_wide_kernel<128, true, false>, grid, block, stream, k);
     }
-    if (a.d == 128) return launch(attn_wide_kernel<128, false>, grid, block, stream, k);
-    return launch(attn_wide_kernel<64, false>, grid, block, stream, k);
+    if (a.d == 128) return launch(attn_wide_kernel<128, false, false>, grid, block, stream, k);
+    return launch(attn_wide_kernel<64, false, false>, grid, block, stream, k);
+}
+
+// The drafter's call on the wide kernel: worth it when a kv head has a few hundred query rows (GQA groups
+// times the block length), which makes the call compute bound.  Every part of the key stream must be empty
+// or at least one tile long.
+bool attn_wide_block_fits(const AttnArgs &a)
+{
+    if (a.qk_dtype == 0 || a.v_dtype != 1 || (a.qk_dtype == 2 && a.d != 128)) return false;
+    if ((long)(a.H / a.Hkv) * a.Nq < 192) return false;
+    const bool spliced = a.Kblk != nullptr;
+    const int la = spliced ? a.block_start : a.N, lb = spliced ? a.block_len : 0;
+    const int lc = spliced ? a.N - a.block_start - a.block_len : 0;
+    auto ok = [](int len) { return len == 0 || len >= TKW; };
+    return la + lb + lc >= TKW && ok(la) && ok(lb) && ok(lc);
+}
+
+// Key splits of that form: until there is about one workgroup per compute unit, at least two tiles each.
+int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N)
+{
+    const long tiles = (long)B * Hkv * (((long)(H / Hkv) * block_len + kRowsWGWide - 1) / kRowsWGWide);
+    long s = (256 + tiles - 1) / tiles;
+    const long max_s = N / (2 * TKW) > 1 ? N / (2 * TKW) : 1;
+    if (s > max_s) s = max_s;
+    if (s > 16) s = 16;
+    return (int)(s < 1 ? 1 : s);
+}
+
+hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
+{
+    AttnKernelArgs k;
+    fill_kernel_args(a, k, kRowsWGWide, TKW);
+    if (a.Kblk == nullptr) k.block_len = 0;                // no row is taken from the block tensors
+    // the kernel splits the LIST of tiles (not the key range) evenly; drop splits that would be empty
+    const int spliced = a.Kblk != nullptr;
+    const int la = spliced ? a.block_start : a.N, lb = spliced ? a.block_len : 0, lc = spliced ? a.N - a.block_start - a.block_len : 0;
+    const int nt = (la + TKW - 1) / TKW + (lb + TKW - 1) / TKW + (lc + TKW - 1) / TKW;
+    int splits = a.splits < nt ? a.splits : nt;
+    const int per = (nt + splits - 1) / splits;
+    splits = (nt + per - 1) / per;
+    k.splits = splits;
+    const size_t rows = (size_t)a.B * a.H * a.Nq;
+    k.part_ml = k.part_o ? k.part_o + rows * (size_t)splits * a.d : nullptr;
+    const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles * splits)), block(kAttnThreads);
+    const hipError_t e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true>, grid, block, stream, k)
+                       : a.d == 128     ? launch(attn_wide_kernel<128, false, true>, grid, block, stream, k)
+                                        : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k);
+    if (e != hipSuccess || splits == 1) return e;
+    AttnArgs c = a;
+    c.splits = splits;
+    return launch_attention_combine(c, stream);
 }
 
 }  // namespace dd

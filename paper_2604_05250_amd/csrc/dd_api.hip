@@ -124,7 +124,10 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
 {
     if (check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, (const float *)16, (const float *)16) != DD_OK) return 0;
     if (block_len < 1 || block_len > N) return 0;
-    return dd::attn_partial_bytes(B, H, block_len, d, dd::attn_block_splits(block_len, B, H, Hkv, N, d));
+    // which kernel serves the call also depends on block_start: enough for either plan
+    const size_t narrow = dd::attn_partial_bytes(B, H, block_len, d, dd::attn_block_splits(block_len, B, H, Hkv, N, d));
+    const size_t wide = dd::attn_partial_bytes(B, H, block_len, d, dd::attn_wide_block_splits(block_len, B, H, Hkv, N));
+    return narrow > wide ? narrow : wide;
 }
 
 int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, void *O,
@@ -141,16 +144,23 @@ int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, 
     if (misaligned16(Qblk) || misaligned16(Kc) || misaligned16(Vc) || misaligned16(O) ||
         misaligned16(Kblk) || misaligned16(Vblk))
         return DD_ERR_ALIGN;
-    const int splits = dd::attn_block_splits(block_len, B, H, Hkv, N, d);
-    rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));
-    if (rc != DD_OK) return rc;
     dd::AttnArgs a{};
     a.Q = Qblk; a.K = Kc; a.V = Vc; a.Kblk = Kblk; a.Vblk = Vblk; a.O = O;
     a.q_scale = q_scale; a.k_scale = k_scale;
     a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = block_len; a.N = N; a.d = d;
     a.block_start = block_start; a.block_len = block_len;
     a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
-    a.splits = splits; a.workspace = workspace;
+    a.workspace = workspace;
+    // DD_TUNE_BLOCK_WIDE=0 keeps calls with many rows per kv head off the wide kernel (read per call: tests switch it)
+    const char *wenv = getenv("DD_TUNE_BLOCK_WIDE");
+    const bool wide = !(wenv && wenv[0] == '0') && dd::attn_wide_block_fits(a);
+    const int splits = wide ? dd::attn_wide_block_splits(block_len, B, H, Hkv, N)
+                            : dd::attn_block_splits(block_len, B, H, Hkv, N, d);
+    rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));
+    if (rc != DD_OK) return rc;
+    a.splits = splits;
+    if (wide)
+        return dd::launch_attention_wide_block(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
     const hipError_t e = (qk_dtype == DD_F32) ? dd::launch_attention_f32(a, static_cast<hipStream_t>(stream))
                                               : dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;

@@ -67,6 +67,11 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream);   // bf
 hipError_t launch_attention_f32(const AttnArgs &a, hipStream_t stream);    // fp32 inputs
 hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream);   // bf16 verifier form, 64 rows per wave
 hipError_t launch_attention_stream(const AttnArgs &a, hipStream_t stream);  // bf16 drafter form, few query rows
+// drafter form on the wide kernel (a few hundred query rows per kv head): whether the call qualifies, the
+// key splits it then uses (a.splits must hold them), the launch (+ merge kernel)
+bool attn_wide_block_fits(const AttnArgs &a);
+int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N);
+hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream);
 bool attn_stream_fits(const AttnArgs &a);
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream);
 

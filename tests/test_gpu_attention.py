@@ -280,6 +280,34 @@ def test_block_each_kernel(monkeypatch, stream, B, H, Hkv, N, d, bl, bs):
         assert_attention_close(got, ref, wl.BF16, f"block kernel stream={stream} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} fresh={fresh}")
 
 
+# A drafter call with a few hundred query rows per kv head (GQA group x block length >= 192) runs on the wide
+# kernel when every part of its key stream (cache before the block, block tensors, cache after it) is empty or at
+# least 64 rows long; DD_TUNE_BLOCK_WIDE=0 keeps it on the other kernels.
+WIDE_BLOCK = [
+    # (B, H, Hkv, N, d, bl, block_start, qk): block at the start / end / inside, ragged parts (overlapping last
+    # tiles), key splits that begin at an overlapping tile (N=321, bs=193), 192 and 320 rows per kv head, fp8, d=64
+    (1, 4, 1, 512, 128, 64, 0, wl.BF16), (1, 4, 1, 512, 128, 64, 448, wl.BF16), (2, 8, 2, 640, 128, 64, 200, wl.BF16),
+    (1, 3, 1, 300, 128, 64, 100, wl.BF16), (1, 4, 1, 321, 128, 64, 193, wl.BF16), (1, 4, 1, 385, 128, 64, 129, wl.BF16),
+    (1, 4, 1, 1000, 128, 80, 700, wl.BF16), (2, 8, 2, 640, 128, 64, 256, wl.FP8_E4M3), (1, 16, 4, 2048, 128, 64, 1536, wl.FP8_E4M3),
+    (1, 8, 2, 400, 64, 64, 64, wl.BF16), (1, 4, 1, 4096, 128, 128, 2000, wl.BF16),
+]
+
+
+@pytest.mark.parametrize("wide", ["1", "0"])
+@pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", WIDE_BLOCK)
+def test_block_many_rows_each_kernel(monkeypatch, wide, B, H, Hkv, N, d, bl, bs, qk):
+    monkeypatch.setenv("DD_TUNE_BLOCK_WIDE", wide)
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=wl.BF16, bl=bl, prompt=0, G=N)
+    cache = wl.cache_inputs(cfg, seed=bs + N)
+    blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+    for fresh in (True, False):
+        Kb, Vb = (blk["Kblk"], blk["Vblk"]) if fresh else (None, None)
+        got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, Kb, Vb, blk["q_scale"], cache["k_scale"])
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, qk, wl.BF16, Kb, Vb,
+                                            blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, qk, f"block wide={wide} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk} fresh={fresh}")
+
+
 @pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", BLOCK_SMALL)
 def test_block_small_shapes(B, H, Hkv, N, d, bl, bs, qk):
     vd = wl.F32 if qk == wl.F32 else wl.BF16
