@@ -32,7 +32,7 @@ LLC_ROTATE_BYTES = 600e6      # rotate input sets until their total exceeds 2x t
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a 1 GiB copy (0.5 and 1.0); figures and commands: profiles/step_kernels_<workload>.md
 PROFILED_TRAFFIC_BYTES = {
-    "attention": {2: 17.0e6, 3: 272.1e6, 4: 135.5e6, 5: 503.9e6},
+    "attention": {2: 17.0e6, 3: 272.1e6, 4: 135.5e6, 5: 503.7e6},
     "verify": {2: 130.1e6, 3: 1038.4e6, 4: 259.8e6, 5: 2495.1e6},
 }
 
