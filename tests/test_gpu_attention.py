@@ -210,6 +210,35 @@ def test_cfg2_bidir_each_kernel(monkeypatch, wide, stream):
     _bidir_full_size(2, 0, full=True)
 
 
+@pytest.mark.parametrize("wide", ["0", "1"])
+def test_bidir_long_sequence(monkeypatch, wide):
+    # 16384 positions: byte offsets inside one head pass 4 MB, 256 key tiles per pass; sampled rows against the oracle
+    monkeypatch.setenv("DD_TUNE_ATTN_WIDE", wide)
+    monkeypatch.setenv("DD_TUNE_BIDIR_STREAM", "0")
+    cfg = wl.custom_config(B=1, H=4, Hkv=2, N=16384, d=128, prompt=0, G=16384)
+    inp = wl.attention_inputs(cfg, seed=21)
+    got = gpu_bidir(inp, cfg)
+    assert np.isfinite(got).all()
+    rows = sample_rows(np.random.default_rng(21), cfg.B, cfg.H, cfg.N, 40)
+    ref = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], wl.BF16, wl.BF16, rows=rows)
+    sel = np.stack([got[b, h, i] for b, h, i in rows])
+    assert_attention_close(sel, ref, wl.BF16, f"N=16384 bidir wide={wide}")
+
+
+def test_block_long_cache():
+    # 65536 cached positions, the block near the end: the key range is split 16 ways
+    cfg = wl.custom_config(B=1, H=4, Hkv=4, N=65536, d=128, bl=64, prompt=0, G=65536)
+    cache = wl.cache_inputs(cfg, seed=9)
+    bs = 65536 - 64 - 37
+    blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+    got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, blk["Kblk"], blk["Vblk"])
+    rows = sample_rows(np.random.default_rng(5), cfg.B, cfg.H, cfg.bl, 24)
+    ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, wl.BF16, wl.BF16, blk["Kblk"], blk["Vblk"],
+                                        rows=rows)
+    sel = np.stack([got[b, h, i] for b, h, i in rows])
+    assert_attention_close(sel, ref, wl.BF16, "N=65536 block")
+
+
 # ------------------------------------------------------------------ block attention over the cache
 def _block_case(cfg, seed, step, full_rows=True, n_rows=256):
     cache = wl.cache_inputs(cfg, seed)
