@@ -205,6 +205,26 @@ int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, fl
               void *workspace, size_t workspace_bytes, void *stream);
 size_t dd_unmask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype);
 
+/*
+ * Every per-position quantity the verification rules of Sec. 3.2 draw on, from one pass over the two logit
+ * matrices and with no rule applied: what a caller needs to evaluate several rules A (or the rule ablation of
+ * Sec. 4) on the same verifier output without reading the logits once per rule.  For P positions, softmax at
+ * temperature 1 over the whole vocabulary:
+ *     out_kl[i]     = KL(p_D(.|i) || p_V(.|i))                        (Eq. 5, natural log)
+ *     out_conf_v[i] = max_x p_V(x | i),  out_tok_v[i] = lowest x attaining it      (Eq. 7; the token Alg. 1 keeps)
+ *     out_conf_d[i] = max_x p_D(x | i),  out_tok_d[i] = lowest x attaining it      (the drafter's proposal)
+ *
+ *   logits_d, logits_v [P,V] logit_dtype (DD_F32 or DD_BF16), rows dense, V * element size a multiple of 16
+ *   out_kl, out_conf_v [P] f32, out_tok_v [P] i32: required;  out_conf_d [P] f32, out_tok_d [P] i32: each may be NULL
+ * Workspace, alignment, stream and error behaviour as for dd_verify_remask (P rows, no sequence structure);
+ * P == 0 is a no-op.  The numbers are the ones dd_verify_remask reports as out_scores/out_tokens in its KL and
+ * confidence modes: the same kernels produce them.
+ */
+int dd_verify_scores(const void *logits_d, const void *logits_v,
+                     float *out_kl, float *out_conf_v, int32_t *out_tok_v, float *out_conf_d, int32_t *out_tok_d,
+                     int P, int V, dd_dtype logit_dtype, void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_verify_scores_workspace_bytes(int P, int V, dd_dtype logit_dtype);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,13 +60,18 @@ def lib():
     L.dd_unmask.argtypes = [vp, vp, i, C.c_float, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_unmask_workspace_bytes.restype = sz
     L.dd_unmask_workspace_bytes.argtypes = [i, i, i, i]
+    L.dd_verify_scores.restype = i
+    L.dd_verify_scores.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
+    L.dd_verify_scores_workspace_bytes.restype = sz
+    L.dd_verify_scores_workspace_bytes.argtypes = [i, i, i]
     _lib = L
     return L
 
 
 EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attention_workspace_bytes",
            "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
-           "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes")
+           "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
+           "dd_verify_scores", "dd_verify_scores_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -233,3 +238,32 @@ def dd_unmask(logits_d, mask, mode: int, threshold: float, B: int, G: int, x_tok
     if rc != 0:
         raise DDError(rc, "dd_unmask")
     return out_mask, out_tokens, out_conf
+
+
+def dd_verify_scores_workspace_bytes(P, V, logit_dtype) -> int:
+    return lib().dd_verify_scores_workspace_bytes(P, V, logit_dtype)
+
+
+def dd_verify_scores(logits_d, logits_v, drafter: bool = True, logit_dtype: Optional[int] = None):
+    """Divergence, both confidences and both argmax tokens of every row in one pass.  logits_d, logits_v [P, V].
+    Returns (kl f32, conf_v f32, tok_v i32, conf_d f32 | None, tok_d i32 | None)."""
+    torch = _torch()
+    P, V = logits_v.shape
+    if tuple(logits_d.shape) != (P, V):
+        raise ValueError("logits_d and logits_v must have the same shape")
+    dt = _dtype_tag(logits_v, "logits_v") if logit_dtype is None else logit_dtype
+    if logit_dtype is None and _dtype_tag(logits_d, "logits_d") != dt:
+        raise ValueError("logits_d and logits_v must have the same dtype")
+    dev = logits_v.device
+    kl = torch.empty(P, dtype=torch.float32, device=dev)
+    conf_v = torch.empty(P, dtype=torch.float32, device=dev)
+    tok_v = torch.empty(P, dtype=torch.int32, device=dev)
+    conf_d = torch.empty(P, dtype=torch.float32, device=dev) if drafter else None
+    tok_d = torch.empty(P, dtype=torch.int32, device=dev) if drafter else None
+    ws, wsn = _workspace(dd_verify_scores_workspace_bytes(P, V, dt), dev)
+    rc = lib().dd_verify_scores(_dev(logits_d, "logits_d"), _dev(logits_v, "logits_v"), _dev(kl, "out_kl"),
+                                _dev(conf_v, "out_conf_v"), _dev(tok_v, "out_tok_v"), _dev(conf_d, "out_conf_d"),
+                                _dev(tok_d, "out_tok_d"), P, V, dt, _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_verify_scores")
+    return kl, conf_v, tok_v, conf_d, tok_d

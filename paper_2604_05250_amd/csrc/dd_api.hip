@@ -229,4 +229,32 @@ int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, fl
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
 }
 
+size_t dd_verify_scores_workspace_bytes(int P, int V, dd_dtype logit_dtype)
+{
+    return dd_verify_remask_workspace_bytes(1, P, V, logit_dtype);
+}
+
+int dd_verify_scores(const void *logits_d, const void *logits_v,
+                     float *out_kl, float *out_conf_v, int32_t *out_tok_v, float *out_conf_d, int32_t *out_tok_d,
+                     int P, int V, dd_dtype logit_dtype, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (logit_dtype != DD_F32 && logit_dtype != DD_BF16) return DD_ERR_DTYPE;
+    if (P < 0 || V < 1) return DD_ERR_SHAPE;
+    const int eb = logit_dtype == DD_BF16 ? 2 : 4;
+    if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
+    if (P == 0) return DD_OK;
+    if (!logits_d || !logits_v || !out_kl || !out_conf_v || !out_tok_v) return DD_ERR_NULL;
+    if (misaligned16(logits_v) || misaligned16(logits_d)) return DD_ERR_ALIGN;
+    const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(P, V, eb));
+    if (rc != DD_OK) return rc;
+    dd::VerifyExtra ex;
+    ex.conf_v = out_conf_v;
+    ex.conf_d = out_conf_d;
+    ex.tok_d = out_tok_d;
+    const hipError_t e = dd::launch_verify(logits_d, logits_v, nullptr, dd::kModeScores, 0.0f, 0, nullptr, out_tok_v,
+                                           out_kl, 1, P, V, logit_dtype == DD_BF16, workspace,
+                                           static_cast<hipStream_t>(stream), nullptr, &ex);
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -33,11 +33,19 @@ size_t verify_workspace_bytes(int P, int V, int elem_bytes);
 // `mode`: a dd_mode value, or one of the two below for the drafter's unmasking step (logits_v then holds the
 // drafter's logits, logits_d is unused, and x_tokens - optional - receives the tokens of the selected rows).
 constexpr int kModeUnmaskThresh = 100, kModeUnmaskTopk = 101;
+// kModeScores: no rule and no mask; out_scores gets the divergence, out_tokens the verifier's argmax, and the
+// fields of `extra` the remaining per-position quantities (conf_v required, the drafter's two optional).
+constexpr int kModeScores = 200;
+struct VerifyExtra {
+    float *conf_v = nullptr;
+    float *conf_d = nullptr;
+    int32_t *tok_d = nullptr;
+};
 hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
                          int mode, float threshold, uint64_t seed,
                          uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
                          int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream,
-                         int32_t *x_tokens = nullptr);
+                         int32_t *x_tokens = nullptr, const VerifyExtra *extra = nullptr);
 
 // ---- attention (attention_mfma.hip, attention_f32.hip) -------------------------
 // One description serves the verifier's full attention and the drafter's block attention:

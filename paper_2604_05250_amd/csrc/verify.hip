@@ -36,7 +36,8 @@ struct __align__(32) VerifyPartial {
     float ref_d, s_d, a;   // drafter reference, sum e^{l_D-ref}, sum e^{l_D-ref} (l_D - l_V)
     float best_v, s_v;     // verifier maximum, sum e^{l_V-best}
     int idx;               // lowest index attaining best_v
-    int pad0, pad1;
+    int idx_d;             // lowest index attaining ref_d (the drafter's most likely token)
+    int pad1;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -99,7 +100,7 @@ template <> struct VecTraits<false> {
 struct LaneState {
     float ref_d = kNegInf, s_d = 0.f, a = 0.f;   // ref_d is wave-uniform
     float best_v = kNegInf, s_v = 0.f;           // best_v, idx_v are wave-uniform
-    int idx_v = INT_MAX;
+    int idx_v = INT_MAX, idx_d = INT_MAX;        // idx_d: where the drafter reference was found (wave-uniform)
 };
 
 // Fold one 16-byte vector of verifier logits (and the matching drafter vector) into the state.
@@ -137,10 +138,17 @@ __device__ __forceinline__ void consume(const uint4 &rv, const uint4 &rd, bool v
         if (!valid) dmax = kNegInf;
         if (__any(dmax > st.ref_d + kLazyMargin)) {
             const float wmax = wave_max(dmax);
+            int cand = INT_MAX;
+            if (valid && dmax == wmax) {
+#pragma unroll
+                for (int e = E - 1; e >= 0; --e)
+                    if (xd[e] == wmax) cand = elem_base + e;
+            }
             const float c = rescale_factor(st.ref_d, wmax);
             st.s_d *= c;
             st.a *= c;
             st.ref_d = wmax;
+            st.idx_d = wave_min(cand);
         }
     }
     if (valid) {
@@ -166,7 +174,7 @@ __device__ __forceinline__ void consume(const uint4 &rv, const uint4 &rd, bool v
 
 struct WaveState {
     float ref_d, s_d, a, best_v, s_v;
-    int idx;
+    int idx, idx_d;
 };
 
 // associative merge of two partial states (b comes after a in index order)
@@ -180,6 +188,7 @@ __device__ __forceinline__ WaveState merge(const WaveState &x, const WaveState &
     r.idx = take_y ? y.idx : x.idx;
     const float md = fmaxf(x.ref_d, y.ref_d);
     const float cx = rescale_factor(x.ref_d, md), cy = rescale_factor(y.ref_d, md);
+    r.idx_d = ((y.ref_d > x.ref_d) || (y.ref_d == x.ref_d && y.idx_d < x.idx_d)) ? y.idx_d : x.idx_d;
     r.ref_d = md;
     r.s_d = x.s_d * cx + y.s_d * cy;
     r.a = x.a * cx + y.a * cy;
@@ -239,6 +248,7 @@ __device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const
     w.best_v = st.best_v;
     w.s_v = wave_sum(st.s_v);
     w.idx = st.idx_v;
+    w.idx_d = st.idx_d;
     if ((tid & 63) == 0) ws[tid >> 6] = w;
     __syncthreads();
     if (tid != 0) return false;
@@ -266,7 +276,7 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *_
         VerifyPartial p;
         p.ref_d = r.ref_d; p.s_d = r.s_d; p.a = r.a;
         p.best_v = r.best_v; p.s_v = r.s_v; p.idx = r.idx;
-        p.pad0 = 0; p.pad1 = 0;
+        p.idx_d = r.idx_d; p.pad1 = 0;
         part[(size_t)row * S + split] = p;
     }
 }
@@ -298,12 +308,19 @@ __device__ __forceinline__ double row_uniform(uint64_t seed, uint64_t row)
 __device__ __forceinline__ void finish_row(int row, double md, double sd, double a, double mv, double sv, int idx,
                                            const uint8_t *__restrict__ mask, int mode, float threshold, uint64_t seed,
                                            int kl_mode, uint8_t *__restrict__ out_mask,
-                                           int32_t *__restrict__ out_tokens, float *__restrict__ out_scores)
+                                           int32_t *__restrict__ out_tokens, float *__restrict__ out_scores,
+                                           int idx_d = 0, const VerifyExtra ex = VerifyExtra{})
 {
     const double score = kl_mode ? a / sd - (md + log(sd)) + (mv + log(sv)) : 1.0 / sv;
     const float s32 = (float)score;
     out_scores[row] = s32;
     out_tokens[row] = idx;
+    if (mode == kModeScores) {                   // every per-position quantity, no rule: c = e^{max - lse} = 1 / sum
+        ex.conf_v[row] = (float)(1.0 / sv);
+        if (ex.conf_d) ex.conf_d[row] = (float)(1.0 / sd);
+        if (ex.tok_d) ex.tok_d[row] = idx_d;
+        return;
+    }
     const uint8_t m = mask[row];
     bool remask = false;
     switch (mode) {
@@ -321,20 +338,24 @@ __global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartia
                                                               float threshold, uint64_t seed, int kl_mode,
                                                               uint8_t *__restrict__ out_mask,
                                                               int32_t *__restrict__ out_tokens,
-                                                              float *__restrict__ out_scores)
+                                                              float *__restrict__ out_scores, VerifyExtra ex)
 {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= P) return;
     const VerifyPartial *p = part + (size_t)row * S;
     float mv = kNegInf, md = kNegInf;
-    int idx = INT_MAX;
+    int idx = INT_MAX, idx_d = INT_MAX;
     for (int s = 0; s < S; ++s) {
         const float b = p[s].best_v;
         if (b > mv || (b == mv && p[s].idx < idx)) {
             mv = b;
             idx = p[s].idx;
         }
-        md = fmaxf(md, p[s].ref_d);
+        const float rd = p[s].ref_d;
+        if (kl_mode && (rd > md || (rd == md && p[s].idx_d < idx_d))) {
+            md = rd;
+            idx_d = p[s].idx_d;
+        }
     }
     double sv = 0.0, sd = 0.0, a = 0.0;
     for (int s = 0; s < S; ++s) {
@@ -345,7 +366,8 @@ __global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartia
             a += (double)p[s].a * c;
         }
     }
-    finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores);
+    finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores,
+               idx_d, ex);
 }
 
 // One workgroup per row: stream the whole row and finish it in the same kernel (no partial states,
@@ -357,14 +379,14 @@ __global__ __launch_bounds__(THREADS) void verify_row_kernel(const uint4 *__rest
                                                              float threshold, uint64_t seed,
                                                              uint8_t *__restrict__ out_mask,
                                                              int32_t *__restrict__ out_tokens,
-                                                             float *__restrict__ out_scores)
+                                                             float *__restrict__ out_scores, VerifyExtra ex)
 {
     const int row = blockIdx.x;
     const size_t rbase = (size_t)row * (size_t)nvec;
     WaveState r;
     if (reduce_range<BF16, KL, THREADS>(logits_v + rbase, KL ? logits_d + rbase : nullptr, 0, nvec, r))
         finish_row(row, (double)r.ref_d, (double)r.s_d, (double)r.a, (double)r.best_v, (double)r.s_v, r.idx,
-                   mask, mode, threshold, seed, KL ? 1 : 0, out_mask, out_tokens, out_scores);
+                   mask, mode, threshold, seed, KL ? 1 : 0, out_mask, out_tokens, out_scores, r.idx_d, ex);
 }
 
 // Eq. 6: one workgroup per sequence sums the divergences of its eligible rows, then draws
@@ -514,26 +536,27 @@ size_t verify_workspace_bytes(int P, int V, int elem_bytes)
 template <bool BF16, bool KL>
 static hipError_t launch_row_kernel(int threads, dim3 grid, hipStream_t stream, const uint4 *ld, const uint4 *lv,
                                     int nvec, const uint8_t *mask, int mode, float threshold, uint64_t seed,
-                                    uint8_t *out_mask, int32_t *out_tokens, float *out_scores)
+                                    uint8_t *out_mask, int32_t *out_tokens, float *out_scores, VerifyExtra ex)
 {
     if (threads == 256)
         return launch(verify_row_kernel<BF16, KL, 256>, grid, dim3(256), stream, ld, lv, nvec, mask, mode,
-                      threshold, seed, out_mask, out_tokens, out_scores);
+                      threshold, seed, out_mask, out_tokens, out_scores, ex);
     return launch(verify_row_kernel<BF16, KL, 512>, grid, dim3(512), stream, ld, lv, nvec, mask, mode,
-                  threshold, seed, out_mask, out_tokens, out_scores);
+                  threshold, seed, out_mask, out_tokens, out_scores, ex);
 }
 
 hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8_t *mask,
                          int mode, float threshold, uint64_t seed,
                          uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
                          int B, int G, int V, int logit_is_bf16, void *workspace, hipStream_t stream,
-                         int32_t *x_tokens)
+                         int32_t *x_tokens, const VerifyExtra *extra)
 {
     const int P = B * G;
     if (P == 0) return hipSuccess;
     const int eb = logit_is_bf16 ? 2 : 4;
     const int nvec = (int)((long)V * eb / 16);
-    const bool kl = (mode == 1 || mode == 3 || mode == 5);
+    const bool kl = (mode == 1 || mode == 3 || mode == 5 || mode == kModeScores);
+    const VerifyExtra ex = extra ? *extra : VerifyExtra{};
     const uint4 *ld = static_cast<const uint4 *>(logits_d);
     const uint4 *lv = static_cast<const uint4 *>(logits_v);
     hipError_t e;
@@ -541,11 +564,11 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     if (fused != 0) {
         const dim3 grid((unsigned)P);
         if (logit_is_bf16)
-            e = kl ? launch_row_kernel<true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores)
-                   : launch_row_kernel<true, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores);
+            e = kl ? launch_row_kernel<true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex)
+                   : launch_row_kernel<true, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex);
         else
-            e = kl ? launch_row_kernel<false, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores)
-                   : launch_row_kernel<false, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores);
+            e = kl ? launch_row_kernel<false, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex)
+                   : launch_row_kernel<false, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex);
     } else {
         const int S = verify_splits(P, V, eb);
         const int chunk = (nvec + S - 1) / S;
@@ -560,7 +583,8 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
         }
         if (e != hipSuccess) return e;
         e = launch(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), stream,
-                   (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores);
+                   (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores,
+                   ex);
     }
     if (e != hipSuccess) return e;
     if (mode == 3)

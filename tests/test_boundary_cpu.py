@@ -100,6 +100,20 @@ def test_unmask_argument_validation():
     assert L.dd_unmask_workspace_bytes(2, 8, 1024, dd.BF16) == L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)
 
 
+def test_verify_scores_argument_validation():
+    L = dd.lib()
+
+    def call(ld=FAKE, lv=FAKE, okl=FAKE, ocv=FAKE, otv=FAKE, ocd=None, otd=None, P=16, V=1024, dt=dd.BF16, ws=None,
+             wsn=0):
+        return L.dd_verify_scores(ld, lv, okl, ocv, otv, ocd, otd, P, V, dt, ws, wsn, None)
+    assert call(dt=dd.FP8_E4M3) == -3 and call(P=-1) == -2 and call(V=0) == -2 and call(V=1001) == -6
+    assert call(ld=None) == -1 and call(lv=None) == -1 and call(okl=None) == -1 and call(ocv=None) == -1
+    assert call(otv=None) == -1 and call(lv=FAKE + 4) == -6
+    assert call() == -5                                    # the drafter's outputs are optional; the workspace is not
+    assert call(P=0) == 0
+    assert L.dd_verify_scores_workspace_bytes(16, 1024, dd.BF16) == L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     q = torch.zeros(1, 1, 4, 64)

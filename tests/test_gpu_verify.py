@@ -361,3 +361,80 @@ def test_unmask_block_of_cfg3():
                            decoded_frac=0.25)
     inp = wl.verify_inputs(blk, seed=0)
     check_unmask(inp, inp["mask"], wl.UNMASK_THRESH, 0.02, blk.B, blk.G, blk.logit_dtype, "cfg3 block unmask")
+
+
+# ---- dd_verify_scores: every per-position quantity of Sec. 3.2 from one pass -----------------------------------------
+def check_all_scores(ld, lv, dtype, what, drafter=True):
+    import torch
+    kl, cv, tv, cd, td = dd.dd_verify_scores(to_dev(ld), to_dev(lv), drafter=drafter, logit_dtype=dtype)
+    torch.cuda.synchronize()
+    o_kl, o_cv, o_tv = oracle.verify_scores(ld, lv, dtype)
+    assert np.array_equal(tv.cpu().numpy(), o_tv), f"{what}: verifier tokens differ"
+    assert_scores_close(kl.cpu().numpy(), o_kl, what + " kl")
+    assert_scores_close(cv.cpu().numpy(), o_cv, what + " conf_v")
+    if drafter:
+        _, o_cd, o_td = oracle.verify_scores(None, ld, dtype)         # the drafter's own confidence and argmax
+        assert np.array_equal(td.cpu().numpy(), o_td), f"{what}: drafter tokens differ"
+        assert_scores_close(cd.cpu().numpy(), o_cd, what + " conf_d")
+    else:
+        assert cd is None and td is None
+    return kl.cpu().numpy(), cv.cpu().numpy(), tv.cpu().numpy()
+
+
+@pytest.mark.parametrize("P,V,dtype", [(10, 8200, wl.BF16), (10, 1028, wl.F32), (7, 126464, wl.BF16), (1, 8, wl.BF16),
+                                        (200, 1000, wl.BF16), (300, 33000, wl.BF16), (1100, 520, wl.F32),
+                                        (2100, 4104, wl.BF16)])
+def test_all_scores_one_pass(P, V, dtype):
+    # few rows: every row split over workgroups and merged by the finishing kernel; many rows: one workgroup per row
+    cfg = wl.custom_config(B=1, G=P, V=V, logit_dtype=dtype, sigma_d=3.0, sigma_n=1.0)
+    inp = wl.verify_inputs(cfg, seed=21)
+    kl, cv, tv = check_all_scores(inp["logits_d"], inp["logits_v"], dtype, f"scores P={P} V={V} dtype={dtype}")
+    # the same numbers as the rule-applying entry point reports (same kernels)
+    _, ot, osc = run_gpu(dict(inp, mask=np.zeros(P, np.uint8)), wl.KL_THRESH, 0.5, 0, 1, P, dtype)
+    assert np.array_equal(ot, tv) and np.array_equal(osc, kl)
+    _, _, osc = run_gpu(dict(inp, mask=np.zeros(P, np.uint8)), wl.CONF_THRESH, 0.5, 0, 1, P, dtype, with_drafter=False)
+    assert np.array_equal(osc, cv)
+    check_all_scores(inp["logits_d"], inp["logits_v"], dtype, "scores without the drafter's pair", drafter=False)
+
+
+@pytest.mark.parametrize("P", [8, 256])
+def test_all_scores_drafter_ties_and_extremes(P):
+    # the drafter's most likely token under exact ties (lowest index), maxima in the first and last vector of a
+    # row and on both sides of every split boundary, flat rows, large offsets
+    V = 40960
+    rng = np.random.default_rng(2)
+    base = (rng.standard_normal(V) * 3).astype(np.float32)
+    rows_d = []
+    for i in range(P):
+        r = base.copy()
+        k = i % 8
+        if k == 0: r[[V - 1, 31000, 12]] = 25.0
+        elif k == 1: r[:] = 0.0
+        elif k == 2: r[V - 1] = 40.0
+        elif k == 3: r[0] = 40.0
+        elif k == 4: r[[20479, 20480]] = 30.0
+        elif k == 5: r += np.float32(900.0)
+        elif k == 6: r[[2559, 2560, 5119, 5120, 38400]] = 22.0
+        rows_d.append(r)
+    ld = np.stack(rows_d)
+    lv = np.stack([np.roll(base, i + 1) for i in range(P)]).astype(np.float32)
+    for dtype in (wl.F32, wl.BF16):
+        a = ld if dtype == wl.F32 else wl.f32_to_bf16_bits(ld)
+        b = lv if dtype == wl.F32 else wl.f32_to_bf16_bits(lv)
+        import torch
+        _, _, _, cd, td = dd.dd_verify_scores(to_dev(a), to_dev(b), logit_dtype=dtype)
+        td = td.cpu().numpy()
+        assert td[0] == 12 and td[1] == 0 and td[2] == V - 1 and td[3] == 0 and td[4] == 20479 and td[6] == 2559
+        assert abs(float(cd[1]) - 1.0 / V) < 1e-9
+        check_all_scores(a, b, dtype, f"scores ties P={P} dtype={dtype}")
+
+
+def test_all_scores_identical_models_and_empty():
+    import torch
+    cfg = wl.custom_config(B=1, G=12, V=2048, logit_dtype=wl.BF16)
+    inp = wl.verify_inputs(cfg, seed=4)
+    kl, cv, tv, cd, td = dd.dd_verify_scores(to_dev(inp["logits_v"]), to_dev(inp["logits_v"]), logit_dtype=wl.BF16)
+    assert (kl == 0).all() and torch.equal(cv, cd) and torch.equal(tv, td)        # KL(p || p) = 0 exactly
+    empty = torch.empty(0, 2048, dtype=torch.bfloat16, device="cuda:0")
+    out = dd.dd_verify_scores(empty, empty)
+    assert all(o.numel() == 0 for o in out)
