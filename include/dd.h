@@ -130,6 +130,28 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
+ * The same call when the block is complete (Sec. 2.3: the cache is refreshed at block granularity; cached
+ * activations are reused "with periodic refreshes" after a block's denoising steps): the attention exactly as
+ * dd_block_attention_cached computes it with Kblk/Vblk given, and in the same call
+ *     Kc[b,g,block_start+r,:] <- Kblk[b,g,r,:],   Vc[b,g,block_start+r,:] <- Vblk[b,g,r,:]      0 <= r < block_len
+ * (a copy of the stored bytes: with DD_FP8_E4M3 the block's K already uses the cache's k_scale).  Afterwards a
+ * call with Kblk == NULL on the same cache returns the same O.  Every other cache row is left untouched.
+ * Kblk and Vblk are required and must not overlap Kc / Vc; block_len <= 2^25; everything else (shapes, dtypes, workspace, errors)
+ * as for dd_block_attention_cached.  The copy rides on the kernel that merges the key splits (extra workgroups
+ * of the same launch), or is one small launch of its own when the key range was not split: no workgroup of the
+ * call reads the cache rows it writes.
+ */
+int dd_block_attention_refresh(const void *Qblk, void *Kc, void *Vc, void *O,
+                               int block_start, int block_len,
+                               const void *Kblk, const void *Vblk,
+                               int B, int H, int Hkv, int N, int d,
+                               dd_dtype qk_dtype, dd_dtype v_dtype,
+                               const float *q_scale, const float *k_scale,
+                               void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_block_attention_refresh_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
+
+/*
  * Verification rule of Sec. 3.2 for P = B*G positions (G verified positions per sequence),
  * softmax at temperature 1 over the whole vocabulary, natural logarithm:
  *     c_V,i  = max_x p_V(x | i)                     (Eq. 7)      t_V,i = lowest x attaining it

@@ -148,6 +148,21 @@ def block_attention_cached(Qblk, Kc, Vc, block_start: int, qk_dtype: int, v_dtyp
     return O
 
 
+def block_attention_refresh(Qblk, Kc, Vc, block_start: int, qk_dtype: int, v_dtype: int, Kblk, Vblk,
+                            q_scale=None, k_scale=None, rows=None):
+    """Block completion (Sec. 2.3): the block's rows replace rows [block_start, block_start+bl) of the cache, and the
+    block's queries attend over the refreshed cache.  Written as that definition: new cache arrays first, then the
+    plain cached call on them.  Returns (O, Kc_new, Vc_new); the inputs are not modified."""
+    Kc = _chk(Kc, qk_dtype, "Kc"); Vc = _chk(Vc, v_dtype, "Vc")
+    Kblk = _chk(Kblk, qk_dtype, "Kblk"); Vblk = _chk(Vblk, v_dtype, "Vblk")
+    bl = Kblk.shape[2]
+    Kn, Vn = Kc.copy(), Vc.copy()
+    Kn[:, :, block_start:block_start + bl, :] = Kblk
+    Vn[:, :, block_start:block_start + bl, :] = Vblk
+    O = block_attention_cached(Qblk, Kn, Vn, block_start, qk_dtype, v_dtype, None, None, q_scale, k_scale, rows)
+    return O, Kn, Vn
+
+
 def verify_scores(logits_d, logits_v, dtype: int, rows: Optional[Sequence[int]] = None):
     """(kl, conf, token) per row; logits [P,V] in storage form; logits_d may be None (kl = NaN)."""
     lv = _chk(logits_v, dtype, "logits_v")

@@ -60,6 +60,10 @@ def lib():
     L.dd_unmask.argtypes = [vp, vp, i, C.c_float, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_unmask_workspace_bytes.restype = sz
     L.dd_unmask_workspace_bytes.argtypes = [i, i, i, i]
+    L.dd_block_attention_refresh.restype = i
+    L.dd_block_attention_refresh.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
+    L.dd_block_attention_refresh_workspace_bytes.restype = sz
+    L.dd_block_attention_refresh_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.dd_verify_scores.restype = i
     L.dd_verify_scores.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
     L.dd_verify_scores_workspace_bytes.restype = sz
@@ -71,7 +75,8 @@ def lib():
 EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attention_workspace_bytes",
            "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
            "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
-           "dd_verify_scores", "dd_verify_scores_workspace_bytes")
+           "dd_verify_scores", "dd_verify_scores_workspace_bytes",
+           "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -155,10 +160,13 @@ def dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dty
 
 
 def dd_block_attention_cached(Qblk, Kc, Vc, block_start: int, O=None, Kblk=None, Vblk=None, q_scale=None,
-                              k_scale=None, qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None):
+                              k_scale=None, qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None,
+                              _refresh: bool = False):
     """Drafter attention: the active block's queries over cached K/V.
     Qblk [B,H,bl,d], Kc,Vc [B,Hkv,N,d], optional Kblk,Vblk [B,Hkv,bl,d] -> O [B,H,bl,d]."""
     torch = _torch()
+    fn = lib().dd_block_attention_refresh if _refresh else lib().dd_block_attention_cached
+    name = "dd_block_attention_refresh" if _refresh else "dd_block_attention_cached"
     B, H, bl, d = Qblk.shape
     _, Hkv, N, _ = Kc.shape
     if tuple(Kc.shape) != (B, Hkv, N, d) or tuple(Vc.shape) != (B, Hkv, N, d):
@@ -170,13 +178,25 @@ def dd_block_attention_cached(Qblk, Kc, Vc, block_start: int, O=None, Kblk=None,
     if O is None:
         O = torch.empty((B, H, bl, d), dtype=Vc.dtype, device=Vc.device)
     ws, wsn = _workspace(dd_block_attention_cached_workspace_bytes(bl, B, H, Hkv, N, d, qk, vd), Qblk.device)
-    rc = lib().dd_block_attention_cached(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
-                                         int(block_start), bl, _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"),
-                                         B, H, Hkv, N, d, qk, vd, _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
-                                         _dev(ws, "workspace"), wsn, _stream())
+    rc = fn(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
+            int(block_start), bl, _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"),
+            B, H, Hkv, N, d, qk, vd, _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
+            _dev(ws, "workspace"), wsn, _stream())
     if rc != 0:
-        raise DDError(rc, "dd_block_attention_cached")
+        raise DDError(rc, name)
     return O
+
+
+def dd_block_attention_refresh_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype) -> int:
+    return lib().dd_block_attention_refresh_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype)
+
+
+def dd_block_attention_refresh(Qblk, Kc, Vc, block_start: int, Kblk, Vblk, O=None, q_scale=None, k_scale=None,
+                               qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None):
+    """Drafter attention of a completed block: as dd_block_attention_cached with Kblk/Vblk, and rows
+    [block_start, block_start + bl) of Kc / Vc are overwritten with Kblk / Vblk in the same call."""
+    return dd_block_attention_cached(Qblk, Kc, Vc, block_start, O=O, Kblk=Kblk, Vblk=Vblk, q_scale=q_scale,
+                                     k_scale=k_scale, qk_dtype=qk_dtype, v_dtype=v_dtype, _refresh=True)
 
 
 def dd_verify_remask_workspace_bytes(B, G, V, logit_dtype) -> int:

@@ -437,12 +437,43 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     }
 }
 
+// Block-completion refresh of the cache (Sec. 2.3: the cache is brought up to date when a block is done):
+// the block's K and V rows, dense in [B*Hkv, block_len, d], replace rows block_start.. of every (batch, kv head)
+// of the cache.  Everything in 16-byte chunks; workgroups `first_wg`.. of the launch do the copying.
+struct RefreshArgs {
+    const uint4 *src[2];       // Kblk, Vblk
+    uint4 *dst[2];             // Kc, Vc at row 0 of (batch 0, kv head 0)
+    int per_bh[2];             // chunks of the block per (batch, kv head)
+    long bh_stride[2];         // chunks between consecutive (batch, kv head) in the cache
+    long offset[2];            // chunks from a cache (batch, kv head) base to row block_start
+    int wgs_per_bh;            // copying workgroups per (batch, kv head)
+    int first_wg;              // workgroups below this one merge partial states
+};
+
+__device__ __forceinline__ void refresh_cache_rows(const RefreshArgs &r)
+{
+    const int cw = (int)blockIdx.x - r.first_wg;
+    const int bh = cw / r.wgs_per_bh;
+    const int first = (cw - bh * r.wgs_per_bh) * (int)blockDim.x + (int)threadIdx.x;
+    const int step = r.wgs_per_bh * (int)blockDim.x;
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        const uint4 *src = r.src[w] + (long)bh * r.per_bh[w];
+        uint4 *dst = r.dst[w] + (long)bh * r.bh_stride[w] + r.offset[w];
+        for (int in = first; in < r.per_bh[w]; in += step) dst[in] = src[in];
+    }
+}
+
 // Merge the per-split partial states of each query row: O = sum_s 2^{m_s-M} O_s / sum_s 2^{m_s-M} l_s.
 template <bool OUT_BF16>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml, void *__restrict__ O,
-                                                           long rows, int splits, int d)
+                                                           long rows, int splits, int d, const RefreshArgs refresh)
 {
+    if ((int)blockIdx.x >= refresh.first_wg) {             // workgroup-uniform: these only copy
+        refresh_cache_rows(refresh);
+        return;
+    }
     const int per_row = d / 4;
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const long row = gid / per_row;
@@ -550,22 +581,60 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
                             : launch(attn_mfma_kernel<128, false, true>, grid, block, stream, k);
     else            e = fp8 ? launch(attn_mfma_kernel<64, true, true>, grid, block, stream, k)
                             : launch(attn_mfma_kernel<64, false, true>, grid, block, stream, k);
-    if (e != hipSuccess || k.splits == 1) return e;
-    AttnArgs c = a;
-    c.splits = k.splits;
-    return launch_attention_combine(c, stream);
+    return e != hipSuccess ? e : finish_attention(a, k.splits, stream);
+}
+
+static int elem_bytes(int dtype) { return dtype == 0 ? 4 : dtype == 1 ? 2 : 1; }
+
+// merge workgroups first (none when the key range was not split), then the copying ones
+static hipError_t launch_combine_refresh(const AttnArgs &a, bool merge, hipStream_t stream)
+{
+    const long rows = merge ? (long)a.B * a.H * a.Nq : 0;
+    const float *po = static_cast<const float *>(a.workspace);
+    const float *pml = merge ? po + (size_t)rows * a.splits * a.d : nullptr;
+    const long threads = rows * (a.d / 4);
+    const long merge_wgs = (threads + 255) / 256;
+    RefreshArgs r{};
+    r.first_wg = (int)merge_wgs;
+    long copy_wgs = 0;
+    if (a.K_refresh != nullptr) {
+        const int eb[2] = {elem_bytes(a.qk_dtype), elem_bytes(a.v_dtype)};
+        r.src[0] = static_cast<const uint4 *>(a.Kblk); r.src[1] = static_cast<const uint4 *>(a.Vblk);
+        r.dst[0] = static_cast<uint4 *>(a.K_refresh);  r.dst[1] = static_cast<uint4 *>(a.V_refresh);
+        int most = 0;
+        for (int w = 0; w < 2; ++w) {
+            const long row_chunks = (long)a.d * eb[w] / 16;            // d is 64 or 128: whole chunks
+            r.per_bh[w] = (int)(a.block_len * row_chunks);             // block_len <= N < 2^31 / 32
+            r.bh_stride[w] = (long)a.N * row_chunks;
+            r.offset[w] = (long)a.block_start * row_chunks;
+            most = r.per_bh[w] > most ? r.per_bh[w] : most;
+        }
+        const long nbh = (long)a.B * a.Hkv;
+        long per = (most + 255) / 256;                                 // one K and one V chunk per lane ...
+        const long cap = nbh >= 2048 ? 1 : 2048 / nbh;                 // ... or a few each
+        r.wgs_per_bh = (int)(per < cap ? per : cap);
+        copy_wgs = nbh * r.wgs_per_bh;
+    }
+    if (merge_wgs + copy_wgs == 0) return hipSuccess;
+    const dim3 grid((unsigned)(merge_wgs + copy_wgs)), block(256);
+    if (a.v_dtype == 1)
+        return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
+    return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
 }
 
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream)
 {
-    const long rows = (long)a.B * a.H * a.Nq;
-    const float *po = static_cast<const float *>(a.workspace);
-    const float *pml = po + (size_t)rows * a.splits * a.d;
-    const long threads = rows * (a.d / 4);
-    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-    if (a.v_dtype == 1)
-        return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
-    return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
+    return launch_combine_refresh(a, true, stream);
+}
+
+hipError_t finish_attention(const AttnArgs &a, int splits_used, hipStream_t stream)
+{
+    if (splits_used > 1) {
+        AttnArgs c = a;
+        c.splits = splits_used;
+        return launch_combine_refresh(c, true, stream);
+    }
+    return a.K_refresh != nullptr ? launch_combine_refresh(a, false, stream) : hipSuccess;
 }
 
 }  // namespace dd

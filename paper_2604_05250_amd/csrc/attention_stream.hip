@@ -390,10 +390,7 @@ hipError_t launch_attention_stream(const AttnArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles * k.splits)), block(kAttnThreads);
     const hipError_t e = a.d == 128 ? launch(attn_stream_kernel<128>, grid, block, stream, k)
                                     : launch(attn_stream_kernel<64>, grid, block, stream, k);
-    if (e != hipSuccess || k.splits == 1) return e;
-    AttnArgs c = a;
-    c.splits = k.splits;
-    return launch_attention_combine(c, stream);
+    return e != hipSuccess ? e : finish_attention(a, k.splits, stream);
 }
 
 }  // namespace dd

@@ -891,10 +891,7 @@ hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
     const hipError_t e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true>, grid, block, stream, k)
                        : a.d == 128     ? launch(attn_wide_kernel<128, false, true>, grid, block, stream, k)
                                         : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k);
-    if (e != hipSuccess || splits == 1) return e;
-    AttnArgs c = a;
-    c.splits = splits;
-    return launch_attention_combine(c, stream);
+    return e != hipSuccess ? e : finish_attention(a, splits, stream);
 }
 
 }  // namespace dd

@@ -130,14 +130,19 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
     return narrow > wide ? narrow : wide;
 }
 
-int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, void *O,
-                              int block_start, int block_len, const void *Kblk, const void *Vblk,
-                              int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
-                              const float *q_scale, const float *k_scale,
-                              void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+// the drafter's call, with (refresh) or without the block's rows written back into the cache
+static int block_attention(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                           int block_start, int block_len, const void *Kblk, const void *Vblk,
+                           int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                           const float *q_scale, const float *k_scale,
+                           void *workspace, size_t workspace_bytes, void *stream, bool refresh)
 {
     if (!Qblk || !Kc || !Vc || !O) return DD_ERR_NULL;
     if ((Kblk == nullptr) != (Vblk == nullptr)) return DD_ERR_NULL;
+    if (refresh && !Kblk) return DD_ERR_NULL;
+    if (refresh && block_len > (1 << 25)) return DD_ERR_SHAPE;   // the copy indexes a block's 16-byte chunks with 32 bits
     int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale);
     if (rc != DD_OK) return rc;
     if (block_start < 0 || block_len < 1 || (long)block_start + block_len > N) return DD_ERR_SHAPE;
@@ -151,6 +156,10 @@ int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, 
     a.block_start = block_start; a.block_len = block_len;
     a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
     a.workspace = workspace;
+    if (refresh) {
+        a.K_refresh = const_cast<void *>(Kc);
+        a.V_refresh = const_cast<void *>(Vc);
+    }
     // DD_TUNE_BLOCK_WIDE=0 keeps calls with many rows per kv head off the wide kernel (read per call: tests switch it)
     const char *wenv = getenv("DD_TUNE_BLOCK_WIDE");
     const bool wide = !(wenv && wenv[0] == '0') && dd::attn_wide_block_fits(a);
@@ -164,6 +173,34 @@ int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, 
     const hipError_t e = (qk_dtype == DD_F32) ? dd::launch_attention_f32(a, static_cast<hipStream_t>(stream))
                                               : dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+extern "C" {
+
+int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                              int block_start, int block_len, const void *Kblk, const void *Vblk,
+                              int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                              const float *q_scale, const float *k_scale,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
+                           q_scale, k_scale, workspace, workspace_bytes, stream, false);
+}
+
+size_t dd_block_attention_refresh_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                  dd_dtype qk_dtype, dd_dtype v_dtype)
+{
+    return dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype);
+}
+
+int dd_block_attention_refresh(const void *Qblk, void *Kc, void *Vc, void *O,
+                               int block_start, int block_len, const void *Kblk, const void *Vblk,
+                               int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                               const float *q_scale, const float *k_scale,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
+                           q_scale, k_scale, workspace, workspace_bytes, stream, true);
 }
 
 size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)

@@ -66,6 +66,11 @@ struct AttnArgs {
     int qk_dtype, v_dtype;   // dd_dtype values
     int splits;              // key-range splits (1 = write O directly)
     void *workspace;         // partial states when splits > 1
+    // Block-completion refresh: when set (both or neither; Kblk/Vblk then required) the rows
+    // [block_start, block_start + block_len) of the cache are overwritten with Kblk / Vblk by the same call.
+    // No workgroup of the call reads those cache rows, so the copy may run at any point of it.
+    void *K_refresh = nullptr;   // = K, writable
+    void *V_refresh = nullptr;   // = V, writable
 };
 
 int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d);
@@ -81,6 +86,10 @@ bool attn_wide_block_fits(const AttnArgs &a);
 int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N);
 hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream);
 bool attn_stream_fits(const AttnArgs &a);
+// merge of the partial states (a.splits > 1), carrying the cache refresh on extra workgroups when one is asked for
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream);
+// what every attention launcher ends with: the merge if the key range was split (`splits_used` > 1),
+// else the cache refresh alone if one is asked for, else nothing
+hipError_t finish_attention(const AttnArgs &a, int splits_used, hipStream_t stream);
 
 }  // namespace dd

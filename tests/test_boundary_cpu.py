@@ -61,6 +61,15 @@ def test_attention_argument_validation():
     assert blk(bs=0, bl=64, ws=FAKE, wsn=need - 1, **big) == -5
     assert blk(bs=0, bl=64, ws=FAKE + 16, wsn=need, **big) == -5      # 256-byte alignment
 
+    def refresh(Kblk=FAKE, Vblk=FAKE, bs=0, bl=16, **kw):
+        a = dict(ok_args); a.update(kw)
+        return L.dd_block_attention_refresh(FAKE, FAKE, FAKE, FAKE, bs, bl, Kblk, Vblk, a["B"], a["H"], a["Hkv"],
+                                            a["N"], a["d"], a["qk"], a["v"], None, None, None, 0, None)
+    assert refresh(Kblk=None, Vblk=None) == -1             # a refresh needs the block's rows
+    assert refresh(Vblk=None) == -1 and refresh(bs=60) == -2 and refresh(Kblk=FAKE + 8) == -6
+    assert refresh(bs=0, bl=64, **big) == -5               # same workspace rule as the plain call
+    assert L.dd_block_attention_refresh_workspace_bytes(64, 1, 32, 32, 4096, 128, dd.BF16, dd.BF16) == need
+
 
 def test_verify_argument_validation():
     L = dd.lib()

@@ -515,6 +515,41 @@ def test_block_attention_cache_semantics():
         oracle.block_attention_cached(Qblk, K, V, N - bl + 1, F32, F32)
 
 
+def test_block_refresh_semantics():
+    # Sec. 2.3, block completion: afterwards the cache holds the block's rows, the output is the one of full
+    # attention over the refreshed sequence, and a later plain cached call sees the same thing
+    rng = np.random.default_rng(10)
+    B, H, Hkv, N, d, bl, bs = 2, 4, 2, 40, 16, 8, 16
+    Q, K, V = _rand_qkv(rng, B, H, Hkv, N, d)
+    _, Kst, Vst = _rand_qkv(rng, B, H, Hkv, N, d)                      # a stale cache, unrelated to K, V
+    Qblk = np.ascontiguousarray(Q[:, :, bs:bs + bl])
+    Kblk = np.ascontiguousarray(K[:, :, bs:bs + bl]); Vblk = np.ascontiguousarray(V[:, :, bs:bs + bl])
+    Kst0, Vst0 = Kst.copy(), Vst.copy()
+    O, Kn, Vn = oracle.block_attention_refresh(Qblk, Kst, Vst, bs, F32, F32, Kblk, Vblk)
+    assert np.array_equal(Kst, Kst0) and np.array_equal(Vst, Vst0)    # inputs untouched
+    inside = np.zeros(N, bool); inside[bs:bs + bl] = True
+    assert np.array_equal(Kn[:, :, inside], Kblk) and np.array_equal(Vn[:, :, inside], Vblk)
+    assert np.array_equal(Kn[:, :, ~inside], Kst[:, :, ~inside]) and np.array_equal(Vn[:, :, ~inside], Vst[:, :, ~inside])
+    # the output: rows bs.. of full attention with Q's block rows over the refreshed K/V (library formulation)
+    Qfull = np.zeros((B, H, N, d), np.float32); Qfull[:, :, bs:bs + bl] = Qblk
+    assert np.array_equal(O, oracle.bidir_attention(Qfull, Kn, Vn, F32, F32)[:, :, bs:bs + bl])
+    # ... which the splicing form of the cached call computes without touching the cache
+    np.testing.assert_allclose(O, oracle.block_attention_cached(Qblk, Kst, Vst, bs, F32, F32, Kblk=Kblk, Vblk=Vblk),
+                               rtol=1e-13, atol=1e-15)
+    # refreshing with the rows the cache already holds changes nothing; refreshing twice equals once
+    O2, Kn2, Vn2 = oracle.block_attention_refresh(Qblk, Kn, Vn, bs, F32, F32, Kblk, Vblk)
+    assert np.array_equal(O2, O) and np.array_equal(Kn2, Kn) and np.array_equal(Vn2, Vn)
+    # when every block has been refreshed with the current K/V the cache IS K/V and the drafter is exact
+    Kc, Vc = Kst.copy(), Vst.copy()
+    for s0 in range(0, N, bl):
+        _, Kc, Vc = oracle.block_attention_refresh(np.ascontiguousarray(Q[:, :, s0:s0 + bl]), Kc, Vc, s0, F32, F32,
+                                                   np.ascontiguousarray(K[:, :, s0:s0 + bl]),
+                                                   np.ascontiguousarray(V[:, :, s0:s0 + bl]))
+    assert np.array_equal(Kc, K) and np.array_equal(Vc, V)
+    assert np.array_equal(oracle.block_attention_cached(Qblk, Kc, Vc, bs, F32, F32),
+                          oracle.bidir_attention(Q, K, V, F32, F32)[:, :, bs:bs + bl])
+
+
 def test_workload_shapes_and_determinism():
     cfg = wl.CONFIGS[1]
     a = wl.attention_inputs(cfg, 0); b = wl.attention_inputs(cfg, 0); c = wl.attention_inputs(cfg, 1)
