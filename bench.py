@@ -60,6 +60,11 @@ def parse():
     ap.add_argument("--verify-threshold", type=float, default=0.0)
     ap.add_argument("--unmask-threshold", type=float, default=0.9,
                     help="confidence threshold of the optional 'unmask' part (add it to --parts)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="additionally time the cycle of an L-layer model (attention only): every draft step runs the "
+                         "drafter's block attention on L caches, the last one with the block-completion refresh, then "
+                         "the unmasking step; the verifier runs L full attentions, then the verification rule. "
+                         "Reported as the extra object 'multi_layer' (32 = LLaDA-8B's depth)")
     ap.add_argument("--no-graph", action="store_true", help="skip the additional HIP-graph replay of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
@@ -295,6 +300,10 @@ def main():
                                   "algorithmic_bytes": unmask_bytes,
                                   "note": f"K={cfg.K} calls per step on the active block's drafter logits [{cfg.B * cfg.bl}, {cfg.V}]"}
 
+    if args.layers > 0:
+        out["multi_layer"] = multi_layer_cycle(args, cfg, dd, wl, torch, sets[0], blk_dev, qs, ks, kcs, mask, mode, tau,
+                                               up(ver["logits_d"]), O, Oblk, out_mask, out_tok, out_sc)
+
     if not args.no_cpu_baseline:
         import oracle
         att_host = att
@@ -331,6 +340,90 @@ def main():
                                       "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
                                       "sample": f"fp64 oracle verify scores on {n} logit rows ({t:.1f} s)"}
     print(json.dumps(out), flush=True)
+
+
+def multi_layer_cycle(args, cfg, dd, wl, torch, s0, blk_dev, qs, ks, kcs, mask, mode, tau, ld_full, O, Oblk,
+                      out_mask, out_tok, out_sc):
+    """One draft-then-verify cycle (Alg. 1) of an L-layer model, attention and vocabulary passes only (the
+    projections and MLPs between them are outside this library).  Every layer has its own Q/K/V and cache in HBM
+    (rolled copies of the workload's tensors: same distribution, distinct memory, so that no layer finds its
+    operands in a cache because the previous one used them).  Timed eagerly and as one HIP graph."""
+    from paper_2604_05250_amd.step import capture_step
+    L, K = args.layers, cfg.K
+    kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB, wl.KL_TOPK)
+    layers = [{k: torch.roll(s0[k], shifts=l, dims=2) if l else s0[k] for k in ("Q", "K", "V", "Kc", "Vc")}
+              for l in range(L)]
+    dev = O.device
+    nb = cfg.B * cfg.bl
+    ld3 = ld_full.view(cfg.B, cfg.G, cfg.V)
+    um = []
+    rng = __import__("numpy").random.default_rng(args.seed + 78)
+    for k in range(K):
+        g0 = (k * cfg.bl) % max(1, cfg.G - cfg.bl + 1)
+        um.append({"ld": ld3[:, g0:g0 + cfg.bl, :].contiguous().view(nb, cfg.V),
+                   "mask": torch.from_numpy((rng.random(nb) < 0.5).astype("uint8")).to(dev)})
+    um_mask = torch.empty(nb, dtype=torch.uint8, device=dev)
+    um_tok = torch.empty(nb, dtype=torch.int32, device=dev)
+    um_conf = torch.empty(nb, dtype=torch.float32, device=dev)
+    um_x = torch.zeros(nb, dtype=torch.int32, device=dev)
+    ld = ld_full if kl_mode else None
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def cycle(marks=None):
+        if marks: marks[0].record()
+        for k, b in enumerate(blk_dev):
+            for lay in layers:
+                if k == K - 1:      # the block is complete after its last draft step: its rows enter the cache
+                    dd.dd_block_attention_refresh(b["Q"], lay["Kc"], lay["Vc"], b["bs"], b["K"], b["V"], O=Oblk,
+                                                  q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+                else:
+                    dd.dd_block_attention_cached(b["Q"], lay["Kc"], lay["Vc"], b["bs"], O=Oblk, Kblk=b["K"], Vblk=b["V"],
+                                                 q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+            u = um[k]
+            dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
+                         out_mask=um_mask, out_tokens=um_tok, out_conf=um_conf, logit_dtype=cfg.logit_dtype)
+        if marks: marks[1].record()
+        for lay in layers:
+            dd.dd_bidir_attention(lay["Q"], lay["K"], lay["V"], O=O, q_scale=qs, k_scale=ks,
+                                  qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+        if marks: marks[2].record()
+        dd.dd_verify_remask(ld, s0["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
+                            out_mask=out_mask, out_tokens=out_tok, out_scores=out_sc, logit_dtype=cfg.logit_dtype)
+        if marks: marks[3].record()
+
+    n = max(2, min(args.steps, 5))
+    for _ in range(2):
+        cycle()
+    torch.cuda.synchronize()
+    rec = []
+    for _ in range(n):
+        m = [ev() for _ in range(4)]
+        cycle(m)
+        rec.append(m)
+    torch.cuda.synchronize()
+    t = [sum(m[i].elapsed_time(m[i + 1]) for m in rec) / n for i in range(3)]
+    res = {"layers": L, "cycles_timed": n,
+           "launch_calls_per_cycle": K * L + K + L + 1,
+           "ms_per_cycle": round(sum(t), 4),
+           "components_ms": {"draft_phase (K x (L block attentions + unmask))": round(t[0], 4),
+                             "verifier_attention_xL": round(t[1], 4), "verify_remask": round(t[2], 4)},
+           "verifier_attention_TFLOPs": round(4.0 * cfg.B * cfg.H * cfg.N * cfg.N * cfg.d * L / (t[1] * 1e-3) / 1e12, 1),
+           "note": "attention and vocabulary passes only; per-layer tensors are distinct HBM buffers"}
+    if not args.no_graph:
+        g = capture_step(lambda: cycle())
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(n):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res["graph_ms_per_cycle"] = round(e0.elapsed_time(e1) / n, 4)
+    return res
 
 
 if __name__ == "__main__":

@@ -152,6 +152,26 @@ size_t dd_block_attention_refresh_workspace_bytes(int block_len, int B, int H, i
                                                   dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
+ * Drafter attention over a local window of the cache (Sec. 2.3 cites dKV-Cache, whose greedy variant restricts
+ * the cached context to the positions around the tokens being decoded): as dd_block_attention_cached, but the
+ * softmax of Eq. 3 runs over the key rows win_start <= j < win_start + win_len only; every other row of the
+ * cache is neither read nor weighted.  The window must contain the block:
+ *     0 <= win_start <= block_start,  block_start + block_len <= win_start + win_len <= N.
+ * With win_start = 0 and win_len = N the result is that of dd_block_attention_cached (same kernels, same order
+ * of operations).  Kc, Vc are the whole cache [B,Hkv,N,d]; the call costs what a cache of win_len rows costs.
+ * Workspace from dd_block_attention_window_workspace_bytes; everything else as for dd_block_attention_cached.
+ */
+int dd_block_attention_window(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                              int block_start, int block_len, int win_start, int win_len,
+                              const void *Kblk, const void *Vblk,
+                              int B, int H, int Hkv, int N, int d,
+                              dd_dtype qk_dtype, dd_dtype v_dtype,
+                              const float *q_scale, const float *k_scale,
+                              void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_block_attention_window_workspace_bytes(int block_len, int win_len, int B, int H, int Hkv, int N, int d,
+                                                 dd_dtype qk_dtype, dd_dtype v_dtype);
+
+/*
  * Verification rule of Sec. 3.2 for P = B*G positions (G verified positions per sequence),
  * softmax at temperature 1 over the whole vocabulary, natural logarithm:
  *     c_V,i  = max_x p_V(x | i)                     (Eq. 7)      t_V,i = lowest x attaining it

@@ -163,6 +163,20 @@ def block_attention_refresh(Qblk, Kc, Vc, block_start: int, qk_dtype: int, v_dty
     return O, Kn, Vn
 
 
+def block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, win_len: int, qk_dtype: int, v_dtype: int,
+                           Kblk=None, Vblk=None, q_scale=None, k_scale=None, rows=None) -> np.ndarray:
+    """Drafter attention restricted to key rows [win_start, win_start + win_len) (local-window drafters, Sec. 2.3):
+    by definition the cached call on the sequence that consists of those rows only."""
+    Kc = _chk(Kc, qk_dtype, "Kc"); Vc = _chk(Vc, v_dtype, "Vc")
+    N = Kc.shape[2]
+    bl = Qblk.shape[2]
+    if not (0 <= win_start <= block_start and block_start + bl <= win_start + win_len <= N):
+        raise ValueError("oracle block_attention_window: the window must lie in the cache and contain the block")
+    Kw = np.ascontiguousarray(Kc[:, :, win_start:win_start + win_len, :])
+    Vw = np.ascontiguousarray(Vc[:, :, win_start:win_start + win_len, :])
+    return block_attention_cached(Qblk, Kw, Vw, block_start - win_start, qk_dtype, v_dtype, Kblk, Vblk, q_scale, k_scale, rows)
+
+
 def verify_scores(logits_d, logits_v, dtype: int, rows: Optional[Sequence[int]] = None):
     """(kl, conf, token) per row; logits [P,V] in storage form; logits_d may be None (kl = NaN)."""
     lv = _chk(logits_v, dtype, "logits_v")

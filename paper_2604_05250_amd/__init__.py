@@ -64,6 +64,10 @@ def lib():
     L.dd_block_attention_refresh.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
     L.dd_block_attention_refresh_workspace_bytes.restype = sz
     L.dd_block_attention_refresh_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.dd_block_attention_window.restype = i
+    L.dd_block_attention_window.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
+    L.dd_block_attention_window_workspace_bytes.restype = sz
+    L.dd_block_attention_window_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, i]
     L.dd_verify_scores.restype = i
     L.dd_verify_scores.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
     L.dd_verify_scores_workspace_bytes.restype = sz
@@ -76,7 +80,8 @@ EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attentio
            "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
            "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
            "dd_verify_scores", "dd_verify_scores_workspace_bytes",
-           "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes")
+           "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
+           "dd_block_attention_window", "dd_block_attention_window_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -197,6 +202,37 @@ def dd_block_attention_refresh(Qblk, Kc, Vc, block_start: int, Kblk, Vblk, O=Non
     [block_start, block_start + bl) of Kc / Vc are overwritten with Kblk / Vblk in the same call."""
     return dd_block_attention_cached(Qblk, Kc, Vc, block_start, O=O, Kblk=Kblk, Vblk=Vblk, q_scale=q_scale,
                                      k_scale=k_scale, qk_dtype=qk_dtype, v_dtype=v_dtype, _refresh=True)
+
+
+def dd_block_attention_window_workspace_bytes(block_len, win_len, B, H, Hkv, N, d, qk_dtype, v_dtype) -> int:
+    return lib().dd_block_attention_window_workspace_bytes(block_len, win_len, B, H, Hkv, N, d, qk_dtype, v_dtype)
+
+
+def dd_block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, win_len: int, O=None, Kblk=None,
+                              Vblk=None, q_scale=None, k_scale=None, qk_dtype: Optional[int] = None,
+                              v_dtype: Optional[int] = None):
+    """Drafter attention over the key rows [win_start, win_start + win_len) of the cache only.
+    Shapes as for dd_block_attention_cached (Kc, Vc are the whole cache)."""
+    torch = _torch()
+    B, H, bl, d = Qblk.shape
+    _, Hkv, N, _ = Kc.shape
+    if tuple(Kc.shape) != (B, Hkv, N, d) or tuple(Vc.shape) != (B, Hkv, N, d):
+        raise ValueError("Kc/Vc shape must be [B,Hkv,N,d]")
+    if Kblk is not None and (tuple(Kblk.shape) != (B, Hkv, bl, d) or tuple(Vblk.shape) != (B, Hkv, bl, d)):
+        raise ValueError("Kblk/Vblk shape must be [B,Hkv,block_len,d]")
+    qk = _dtype_tag(Qblk, "Qblk") if qk_dtype is None else qk_dtype
+    vd = _dtype_tag(Vc, "Vc") if v_dtype is None else v_dtype
+    if O is None:
+        O = torch.empty((B, H, bl, d), dtype=Vc.dtype, device=Vc.device)
+    ws, wsn = _workspace(dd_block_attention_window_workspace_bytes(bl, int(win_len), B, H, Hkv, N, d, qk, vd), Qblk.device)
+    rc = lib().dd_block_attention_window(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
+                                         int(block_start), bl, int(win_start), int(win_len),
+                                         _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"), B, H, Hkv, N, d, qk, vd,
+                                         _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
+                                         _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_block_attention_window")
+    return O
 
 
 def dd_verify_remask_workspace_bytes(B, G, V, logit_dtype) -> int:

@@ -18,6 +18,7 @@ struct AttnKernelArgs {
     float *part_ml;            // [rows][splits][2] (running max in log2 units, partial sum)
     const float *q_scale, *k_scale;
     int B, H, Hkv, Nq, N;
+    int kv_stride;             // rows between consecutive (batch, kv head) in K and V (N unless the call sees a window)
     int group;                 // H / Hkv
     int rows_per_wg;           // query rows per workgroup (a multiple of a wave's rows)
     int row_tiles;             // ceil(group * Nq / rows_per_wg)

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_f32_kernel(const AttnKernel
             if (j < k_end) {
                 const bool in_blk = a.Kblk != nullptr && j >= a.block_start && j < a.block_start + a.block_len;
                 const size_t off = in_blk ? (kv_head * a.block_len + (size_t)(j - a.block_start)) * D
-                                          : (kv_head * a.N + (size_t)j) * D;
+                                          : (kv_head * a.kv_stride + (size_t)j) * D;
                 const float *kp = static_cast<const float *>(in_blk ? a.Kblk : a.K) + off;
                 const float *vp = static_cast<const float *>(in_blk ? a.Vblk : a.V) + off;
                 kw = reinterpret_cast<const float4 *>(kp)[ch];

@@ -154,8 +154,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     const int vt_dchunk = tid % CH, vt_e4 = (tid / CH) & 1, vt_g = tid / (2 * CH);   // V task of this thread
     // keys of task (g, e4): tile-local index (g/4)*32 + ((g/2)&1)*16 + 8*e4 + 4*(g&1) + e,  e = 0..3
     const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
-    const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
-    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)(D * 2) + vt_dchunk * 16;
+    const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.kv_stride * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
+    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)(D * 2) + vt_dchunk * 16;
 
     // address of key row j's chunk for this thread; rows past the range are clamped to the last
     // valid row (their scores are masked to -inf, their values multiply a zero probability)
@@ -523,6 +523,7 @@ void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int
     k.Q = a.Q; k.K = a.K; k.V = a.V; k.Kblk = a.Kblk; k.Vblk = a.Vblk; k.O = a.O;
     k.q_scale = a.q_scale; k.k_scale = a.k_scale;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.Nq = a.Nq; k.N = a.N;
+    k.kv_stride = a.kv_stride > 0 ? a.kv_stride : a.N;
     k.group = a.H / a.Hkv;
     k.rows_per_wg = rows_per_wg;
     k.row_tiles = (k.group * a.Nq + rows_per_wg - 1) / rows_per_wg;
@@ -605,7 +606,7 @@ static hipError_t launch_combine_refresh(const AttnArgs &a, bool merge, hipStrea
         for (int w = 0; w < 2; ++w) {
             const long row_chunks = (long)a.d * eb[w] / 16;            // d is 64 or 128: whole chunks
             r.per_bh[w] = (int)(a.block_len * row_chunks);             // block_len <= N < 2^31 / 32
-            r.bh_stride[w] = (long)a.N * row_chunks;
+            r.bh_stride[w] = (long)(a.kv_stride > 0 ? a.kv_stride : a.N) * row_chunks;
             r.offset[w] = (long)a.block_start * row_chunks;
             most = r.per_bh[w] > most ? r.per_bh[w] : most;
         }

@@ -108,8 +108,8 @@ void attn_stream_kernel(const AttnKernelArgs a)
     const unsigned dma_koff = (dma_pos ^ (dma_row0 & 7)) * 16;
     const unsigned dma_voff = (dma_pos ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
     const size_t kv_head = (size_t)b * a.Hkv + kvh;
-    const uint8_t *const kc = static_cast<const uint8_t *>(a.K) + kv_head * a.N * (size_t)ROWB;
-    const uint8_t *const vc = static_cast<const uint8_t *>(a.V) + kv_head * a.N * (size_t)ROWB;
+    const uint8_t *const kc = static_cast<const uint8_t *>(a.K) + kv_head * a.kv_stride * (size_t)ROWB;
+    const uint8_t *const vc = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)ROWB;
     const uint8_t *const kb_ = a.block_len ? static_cast<const uint8_t *>(a.Kblk) + kv_head * a.block_len * (size_t)ROWB : nullptr;
     const uint8_t *const vb_ = a.block_len ? static_cast<const uint8_t *>(a.Vblk) + kv_head * a.block_len * (size_t)ROWB : nullptr;
     // rows of the last tile at or past the end of the key range repeat its last row (finite stand-ins, masked later)

@@ -221,8 +221,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto tile_of = [&](int t) __attribute__((always_inline)) {
         const int rt = t % a.row_tiles, bk = t / a.row_tiles, kvh = bk % a.Hkv, b = bk / a.Hkv;
         Tile r;
-        r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.N * (size_t)KROWB;
-        r.v = static_cast<const uint8_t *>(a.V) + (size_t)bk * a.N * (size_t)ROWB;
+        r.k = static_cast<const uint8_t *>(a.K) + (size_t)bk * a.kv_stride * (size_t)KROWB;
+        r.v = static_cast<const uint8_t *>(a.V) + (size_t)bk * a.kv_stride * (size_t)ROWB;
         r.kb = r.vb = nullptr;
         if (BLOCK && a.block_len) {
             r.kb = static_cast<const uint8_t *>(a.Kblk) + (size_t)bk * a.block_len * (size_t)KROWB;

@@ -132,12 +132,14 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
 
 }  // extern "C"
 
-// the drafter's call, with (refresh) or without the block's rows written back into the cache
+// the drafter's call, with (refresh) or without the block's rows written back into the cache, over the
+// whole cache (win_len == 0) or over the key rows [win_start, win_start + win_len) only
 static int block_attention(const void *Qblk, const void *Kc, const void *Vc, void *O,
                            int block_start, int block_len, const void *Kblk, const void *Vblk,
                            int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
                            const float *q_scale, const float *k_scale,
-                           void *workspace, size_t workspace_bytes, void *stream, bool refresh)
+                           void *workspace, size_t workspace_bytes, void *stream, bool refresh,
+                           int win_start = 0, int win_len = 0)
 {
     if (!Qblk || !Kc || !Vc || !O) return DD_ERR_NULL;
     if ((Kblk == nullptr) != (Vblk == nullptr)) return DD_ERR_NULL;
@@ -146,6 +148,18 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
     int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale);
     if (rc != DD_OK) return rc;
     if (block_start < 0 || block_len < 1 || (long)block_start + block_len > N) return DD_ERR_SHAPE;
+    const int full_N = N;
+    if (win_len != 0) {
+        // a window is a shorter sequence that starts win_start rows into every (batch, kv head) of the cache:
+        // same kernels, K/V based at the window's first row, the cache's own row count as the stride
+        if (win_start < 0 || win_len < 1 || (long)win_start + win_len > N) return DD_ERR_SHAPE;
+        if (block_start < win_start || (long)block_start + block_len > (long)win_start + win_len) return DD_ERR_SHAPE;
+        const size_t ebk = qk_dtype == DD_F32 ? 4 : qk_dtype == DD_BF16 ? 2 : 1, ebv = v_dtype == DD_F32 ? 4 : 2;
+        Kc = static_cast<const uint8_t *>(Kc) + (size_t)win_start * d * ebk;
+        Vc = static_cast<const uint8_t *>(Vc) + (size_t)win_start * d * ebv;
+        block_start -= win_start;
+        N = win_len;
+    }
     if (misaligned16(Qblk) || misaligned16(Kc) || misaligned16(Vc) || misaligned16(O) ||
         misaligned16(Kblk) || misaligned16(Vblk))
         return DD_ERR_ALIGN;
@@ -156,6 +170,7 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
     a.block_start = block_start; a.block_len = block_len;
     a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
     a.workspace = workspace;
+    a.kv_stride = full_N;
     if (refresh) {
         a.K_refresh = const_cast<void *>(Kc);
         a.V_refresh = const_cast<void *>(Vc);
@@ -201,6 +216,26 @@ int dd_block_attention_refresh(const void *Qblk, void *Kc, void *Vc, void *O,
 {
     return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
                            q_scale, k_scale, workspace, workspace_bytes, stream, true);
+}
+
+size_t dd_block_attention_window_workspace_bytes(int block_len, int win_len, int B, int H, int Hkv, int N, int d,
+                                                 dd_dtype qk_dtype, dd_dtype v_dtype)
+{
+    if (win_len < 1 || win_len > N) return 0;
+    if (check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, (const float *)16, (const float *)16) != DD_OK) return 0;
+    return dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, win_len, d, qk_dtype, v_dtype);
+}
+
+int dd_block_attention_window(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                              int block_start, int block_len, int win_start, int win_len,
+                              const void *Kblk, const void *Vblk,
+                              int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                              const float *q_scale, const float *k_scale,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (win_len < 1) return DD_ERR_SHAPE;
+    return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
+                           q_scale, k_scale, workspace, workspace_bytes, stream, false, win_start, win_len);
 }
 
 size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)

@@ -62,6 +62,8 @@ struct AttnArgs {
     const float *q_scale;  // [B*H] or nullptr
     const float *k_scale;  // [B*Hkv] or nullptr
     int B, H, Hkv, Nq, N, d;
+    int kv_stride = 0;       // rows between consecutive (batch, kv head) of K and V; 0 = N (dense).  A call on a
+                             // window of the cache passes K/V at the window's first row, N = the window length
     int block_start, block_len;
     int qk_dtype, v_dtype;   // dd_dtype values
     int splits;              // key-range splits (1 = write O directly)

@@ -70,6 +70,16 @@ def test_attention_argument_validation():
     assert refresh(bs=0, bl=64, **big) == -5               # same workspace rule as the plain call
     assert L.dd_block_attention_refresh_workspace_bytes(64, 1, 32, 32, 4096, 128, dd.BF16, dd.BF16) == need
 
+    def window(bs=16, bl=16, w0=0, wl=64, **kw):
+        a = dict(ok_args); a.update(kw)
+        return L.dd_block_attention_window(FAKE, FAKE, FAKE, FAKE, bs, bl, w0, wl, None, None, a["B"], a["H"], a["Hkv"],
+                                           a["N"], a["d"], a["qk"], a["v"], None, None, None, 0, None)
+    assert window(wl=0) == -2 and window(w0=-1) == -2 and window(w0=8, wl=60) == -2         # window leaves the cache
+    assert window(w0=17, wl=40) == -2 and window(w0=0, wl=31) == -2                         # block not inside the window
+    assert window(bs=0, bl=64, w0=0, wl=4096, **big) == -5                                  # wide window: split keys
+    assert L.dd_block_attention_window_workspace_bytes(64, 4096, 1, 32, 32, 8192, 128, dd.BF16, dd.BF16) == need
+    assert L.dd_block_attention_window_workspace_bytes(64, 0, 1, 32, 32, 8192, 128, dd.BF16, dd.BF16) == 0
+
 
 def test_verify_argument_validation():
     L = dd.lib()

@@ -550,6 +550,42 @@ def test_block_refresh_semantics():
                           oracle.bidir_attention(Q, K, V, F32, F32)[:, :, bs:bs + bl])
 
 
+def test_block_window_semantics():
+    # local-window drafter attention: the softmax runs over the window's key rows only
+    rng = np.random.default_rng(11)
+    B, H, N, d, bl, bs, w0, wl_ = 2, 3, 37, 8, 5, 14, 9, 17
+    Q, K, V = _rand_qkv(rng, B, H, H, N, d)
+    Qb = np.ascontiguousarray(Q[:, :, bs:bs + bl])
+    O = oracle.block_attention_window(Qb, K, V, bs, w0, wl_, F32, F32)
+    # library formulation: scores of rows outside the window set to -inf before the softmax
+    S = np.einsum("bhid,bhjd->bhij", Qb.astype(np.float64), K.astype(np.float64)) / math.sqrt(d)
+    S[..., :w0] = -np.inf
+    S[..., w0 + wl_:] = -np.inf
+    ref = np.einsum("bhij,bhjd->bhid", sp.softmax(S, axis=-1), V.astype(np.float64))
+    assert np.allclose(O, ref, rtol=1e-12, atol=1e-14)
+    # rows outside the window have no influence, rows at both of its ends do
+    K2, V2 = K.copy(), V.copy()
+    K2[:, :, :w0] += 5.0; V2[:, :, w0 + wl_:] -= 7.0
+    assert np.array_equal(oracle.block_attention_window(Qb, K2, V2, bs, w0, wl_, F32, F32), O)
+    for j in (w0, w0 + wl_ - 1):
+        V3 = V.copy(); V3[:, :, j] += 3.0
+        assert not np.allclose(oracle.block_attention_window(Qb, K, V3, bs, w0, wl_, F32, F32), O)
+    # the whole sequence as the window is the plain cached call; fresh block rows splice in as usual
+    assert np.array_equal(oracle.block_attention_window(Qb, K, V, bs, 0, N, F32, F32),
+                          oracle.block_attention_cached(Qb, K, V, bs, F32, F32))
+    Kb = rng.standard_normal((B, H, bl, d)).astype(np.float32); Vb = rng.standard_normal((B, H, bl, d)).astype(np.float32)
+    Ks, Vs = K.copy(), V.copy()
+    Ks[:, :, bs:bs + bl] = Kb; Vs[:, :, bs:bs + bl] = Vb
+    assert np.array_equal(oracle.block_attention_window(Qb, K, V, bs, w0, wl_, F32, F32, Kblk=Kb, Vblk=Vb),
+                          oracle.block_attention_window(Qb, Ks, Vs, bs, w0, wl_, F32, F32))
+    # the window is exactly the block: the block attends to itself only
+    assert np.allclose(oracle.block_attention_window(Qb, K, V, bs, bs, bl, F32, F32),
+                       _numpy_attention(Qb, K[:, :, bs:bs + bl], V[:, :, bs:bs + bl]), rtol=1e-12, atol=1e-14)
+    for bad in ((bs + 1, wl_), (w0, bs + bl - w0 - 1), (-1, 10), (30, 10)):
+        with pytest.raises(ValueError):
+            oracle.block_attention_window(Qb, K, V, bs, bad[0], bad[1], F32, F32)
+
+
 def test_workload_shapes_and_determinism():
     cfg = wl.CONFIGS[1]
     a = wl.attention_inputs(cfg, 0); b = wl.attention_inputs(cfg, 0); c = wl.attention_inputs(cfg, 1)
