@@ -172,6 +172,23 @@ size_t dd_block_attention_window_workspace_bytes(int block_len, int win_len, int
                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
+ * Token-granular cache update.  The cached drafters of Sec. 2.3 differ in when a position's key/value enter
+ * the cache (block-wise schemes: when the block is complete; dKV-Cache: one step after the token was decoded);
+ * the operation on the cache is the same: rows the drafter computed replace the cache rows of chosen positions:
+ *     for b < B, g < Hkv, r < n, with p = positions[b*n + r]:   if 0 <= p < N:
+ *         Kc[b,g,p,:] <- Krows[b,g,r,:],   Vc[b,g,p,:] <- Vrows[b,g,r,:]            (stored bytes are copied)
+ *
+ *   Kc [B,Hkv,N,d] qk_dtype, Vc [B,Hkv,N,d] v_dtype     the cache (modified in place)
+ *   Krows [B,Hkv,n,d] qk_dtype, Vrows [B,Hkv,n,d] v_dtype
+ *   positions [B*n] i32, DEVICE memory: one list per batch entry, shared by its kv heads; an entry outside
+ *       [0, N) (e.g. -1) skips its row; the positions of one batch entry must be distinct (else which row wins
+ *       is unspecified)
+ * dtypes / d as for dd_bidir_attention (H plays no role); n == 0 is a no-op.  Krows/Vrows must not overlap the cache.
+ */
+int dd_cache_insert_rows(void *Kc, void *Vc, const void *Krows, const void *Vrows, const int32_t *positions, int n,
+                         int B, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype, void *stream);
+
+/*
  * Verification rule of Sec. 3.2 for P = B*G positions (G verified positions per sequence),
  * softmax at temperature 1 over the whole vocabulary, natural logarithm:
  *     c_V,i  = max_x p_V(x | i)                     (Eq. 7)      t_V,i = lowest x attaining it

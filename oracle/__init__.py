@@ -177,6 +177,23 @@ def block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, win_l
     return block_attention_cached(Qblk, Kw, Vw, block_start - win_start, qk_dtype, v_dtype, Kblk, Vblk, q_scale, k_scale, rows)
 
 
+def cache_insert_rows(Kc, Vc, Krows, Vrows, positions):
+    """Token-granular cache update (Sec. 2.3, delayed insertion): row r of Krows/Vrows [B,Hkv,n,d] replaces cache
+    row positions[b][r] of every kv head of batch b; entries outside [0, N) are skipped.  Plain loops; returns new
+    arrays."""
+    Kn, Vn = np.array(Kc, copy=True), np.array(Vc, copy=True)
+    B, Hkv, N, _ = Kn.shape
+    pos = np.asarray(positions).reshape(B, -1)
+    for b in range(B):
+        for r in range(pos.shape[1]):
+            p = int(pos[b, r])
+            if 0 <= p < N:
+                for g in range(Hkv):
+                    Kn[b, g, p, :] = Krows[b, g, r, :]
+                    Vn[b, g, p, :] = Vrows[b, g, r, :]
+    return Kn, Vn
+
+
 def verify_scores(logits_d, logits_v, dtype: int, rows: Optional[Sequence[int]] = None):
     """(kl, conf, token) per row; logits [P,V] in storage form; logits_d may be None (kl = NaN)."""
     lv = _chk(logits_v, dtype, "logits_v")

@@ -68,6 +68,8 @@ def lib():
     L.dd_block_attention_window.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
     L.dd_block_attention_window_workspace_bytes.restype = sz
     L.dd_block_attention_window_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, i]
+    L.dd_cache_insert_rows.restype = i
+    L.dd_cache_insert_rows.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     L.dd_verify_scores.restype = i
     L.dd_verify_scores.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, vp, sz, vp]
     L.dd_verify_scores_workspace_bytes.restype = sz
@@ -81,7 +83,7 @@ EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attentio
            "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
            "dd_verify_scores", "dd_verify_scores_workspace_bytes",
            "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
-           "dd_block_attention_window", "dd_block_attention_window_workspace_bytes")
+           "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -233,6 +235,24 @@ def dd_block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, wi
     if rc != 0:
         raise DDError(rc, "dd_block_attention_window")
     return O
+
+
+def dd_cache_insert_rows(Kc, Vc, Krows, Vrows, positions, qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None):
+    """Kc/Vc [B,Hkv,N,d] <- rows of Krows/Vrows [B,Hkv,n,d] at positions [B,n] (i32, on the device; entries outside
+    [0, N) skip their row).  In place; returns None."""
+    torch = _torch()
+    B, Hkv, N, d = Kc.shape
+    n = Krows.shape[2]
+    if tuple(Vc.shape) != (B, Hkv, N, d) or tuple(Krows.shape) != (B, Hkv, n, d) or tuple(Vrows.shape) != (B, Hkv, n, d):
+        raise ValueError("shapes must be Kc,Vc [B,Hkv,N,d] and Krows,Vrows [B,Hkv,n,d]")
+    if positions.dtype != torch.int32 or positions.numel() != B * n:
+        raise ValueError("positions must be int32 with B*n entries")
+    qk = _dtype_tag(Kc, "Kc") if qk_dtype is None else qk_dtype
+    vd = _dtype_tag(Vc, "Vc") if v_dtype is None else v_dtype
+    rc = lib().dd_cache_insert_rows(_dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(Krows, "Krows"), _dev(Vrows, "Vrows"),
+                                    _dev(positions, "positions"), n, B, Hkv, N, d, qk, vd, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_cache_insert_rows")
 
 
 def dd_verify_remask_workspace_bytes(B, G, V, logit_dtype) -> int:

@@ -8,7 +8,7 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libdd.so")
-SOURCES = ["dd_api.hip", "verify.hip", "attention_mfma.hip", "attention_wide.hip", "attention_stream.hip", "attention_f32.hip"]
+SOURCES = ["dd_api.hip", "verify.hip", "attention_mfma.hip", "attention_wide.hip", "attention_stream.hip", "attention_f32.hip", "cache.hip"]
 HEADERS = ["dd_internal.h", "attention_common.h", os.path.join("..", "..", "include", "dd.h")]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          # packed-fp32 instructions are kept out of the generated code on the test machines

@@ -238,6 +238,23 @@ int dd_block_attention_window(const void *Qblk, const void *Kc, const void *Vc, 
                            q_scale, k_scale, workspace, workspace_bytes, stream, false, win_start, win_len);
 }
 
+int dd_cache_insert_rows(void *Kc, void *Vc, const void *Krows, const void *Vrows, const int32_t *positions, int n,
+                         int B, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype, void *stream)
+{
+    if (n < 0) return DD_ERR_SHAPE;
+    const int rc = check_attention_common(B, Hkv, Hkv, N, d, qk_dtype, v_dtype, (const float *)16, (const float *)16);
+    if (rc != DD_OK) return rc;
+    if ((double)B * Hkv * n * d >= 1099511627776.0) return DD_ERR_SHAPE;
+    if (n == 0) return DD_OK;
+    if (!Kc || !Vc || !Krows || !Vrows || !positions) return DD_ERR_NULL;
+    if (misaligned16(Kc) || misaligned16(Vc) || misaligned16(Krows) || misaligned16(Vrows)) return DD_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(positions) & 3u) != 0) return DD_ERR_ALIGN;
+    const int ebk = qk_dtype == DD_F32 ? 4 : qk_dtype == DD_BF16 ? 2 : 1, ebv = v_dtype == DD_F32 ? 4 : 2;
+    const hipError_t e = dd::launch_cache_insert_rows(Krows, Vrows, Kc, Vc, positions, n, B, Hkv, N, d, ebk, ebv,
+                                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
 size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)
 {
     if (B < 0 || G < 0 || V < 1 || (logit_dtype != DD_F32 && logit_dtype != DD_BF16)) return 0;

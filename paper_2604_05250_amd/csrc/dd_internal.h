@@ -88,6 +88,13 @@ bool attn_wide_block_fits(const AttnArgs &a);
 int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N);
 hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream);
 bool attn_stream_fits(const AttnArgs &a);
+
+// ---- cache maintenance (cache.hip) ----------------------------------------------
+// Row r of Krows/Vrows [B, Hkv, n, d] replaces cache row pos[b * n + r] of every kv head of batch b
+// (entries outside [0, N) are skipped by the kernel).
+hipError_t launch_cache_insert_rows(const void *Krows, const void *Vrows, void *Kc, void *Vc, const int32_t *pos,
+                                    int n, int B, int Hkv, int N, int d, int k_elem_bytes, int v_elem_bytes,
+                                    hipStream_t stream);
 // merge of the partial states (a.splits > 1), carrying the cache refresh on extra workgroups when one is asked for
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream);
 // what every attention launcher ends with: the merge if the key range was split (`splits_used` > 1),

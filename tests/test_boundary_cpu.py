@@ -81,6 +81,17 @@ def test_attention_argument_validation():
     assert L.dd_block_attention_window_workspace_bytes(64, 0, 1, 32, 32, 8192, 128, dd.BF16, dd.BF16) == 0
 
 
+def test_cache_insert_argument_validation():
+    L = dd.lib()
+
+    def call(Kc=FAKE, Vc=FAKE, Kr=FAKE, Vr=FAKE, pos=FAKE, n=4, B=2, Hkv=2, N=64, d=128, qk=dd.BF16, v=dd.BF16):
+        return L.dd_cache_insert_rows(Kc, Vc, Kr, Vr, pos, n, B, Hkv, N, d, qk, v, None)
+    assert call(n=-1) == -2 and call(B=0) == -2 and call(d=96) == -2 and call(qk=dd.BF16, v=dd.F32) == -3
+    assert call(Kc=None) == -1 and call(Vr=None) == -1 and call(pos=None) == -1
+    assert call(Kr=FAKE + 8) == -6 and call(pos=FAKE + 2) == -6
+    assert call(n=0, Kc=None, pos=None) == 0               # nothing to insert
+
+
 def test_verify_argument_validation():
     L = dd.lib()
 

@@ -586,6 +586,39 @@ def test_block_window_semantics():
             oracle.block_attention_window(Qb, K, V, bs, bad[0], bad[1], F32, F32)
 
 
+def test_cache_insert_rows_semantics():
+    rng = np.random.default_rng(12)
+    B, Hkv, N, d, n = 3, 2, 21, 8, 5
+    Kc = rng.standard_normal((B, Hkv, N, d)).astype(np.float32); Vc = rng.standard_normal((B, Hkv, N, d)).astype(np.float32)
+    Kr = rng.standard_normal((B, Hkv, n, d)).astype(np.float32); Vr = rng.standard_normal((B, Hkv, n, d)).astype(np.float32)
+    pos = np.array([[4, 0, 20, 7, 13], [-1, 3, 21, 5, 100], [9, 8, 7, 6, 5]], np.int32)     # skips: -1, 21, 100
+    K0, V0 = Kc.copy(), Vc.copy()
+    Kn, Vn = oracle.cache_insert_rows(Kc, Vc, Kr, Vr, pos)
+    assert np.array_equal(Kc, K0) and np.array_equal(Vc, V0)
+    # library formulation: fancy-index assignment per batch entry on the valid positions
+    Ke, Ve = Kc.copy(), Vc.copy()
+    for b in range(B):
+        ok = (pos[b] >= 0) & (pos[b] < N)
+        Ke[b][:, pos[b][ok]] = Kr[b][:, ok]
+        Ve[b][:, pos[b][ok]] = Vr[b][:, ok]
+    assert np.array_equal(Kn, Ke) and np.array_equal(Vn, Ve)
+    touched = np.zeros((B, N), bool)
+    for b in range(B):
+        touched[b, pos[b][(pos[b] >= 0) & (pos[b] < N)]] = True
+    assert touched.sum() == 12
+    for b in range(B):
+        assert np.array_equal(Kn[b][:, ~touched[b]], Kc[b][:, ~touched[b]])
+    # consecutive positions of one block = the block-completion refresh
+    bs, bl = 6, n
+    Q = rng.standard_normal((B, 4, bl, d)).astype(np.float32)
+    _, Kref, Vref = oracle.block_attention_refresh(Q, Kc, Vc, bs, F32, F32, Kr, Vr)
+    Kn2, Vn2 = oracle.cache_insert_rows(Kc, Vc, Kr, Vr, np.tile(np.arange(bs, bs + bl, dtype=np.int32), (B, 1)))
+    assert np.array_equal(Kn2, Kref) and np.array_equal(Vn2, Vref)
+    # nothing to insert
+    Kn3, _ = oracle.cache_insert_rows(Kc, Vc, Kr[:, :, :0], Vr[:, :, :0], np.zeros((B, 0), np.int32))
+    assert np.array_equal(Kn3, Kc)
+
+
 def test_workload_shapes_and_determinism():
     cfg = wl.CONFIGS[1]
     a = wl.attention_inputs(cfg, 0); b = wl.attention_inputs(cfg, 0); c = wl.attention_inputs(cfg, 1)
