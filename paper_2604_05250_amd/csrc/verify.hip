@@ -105,7 +105,8 @@ struct LaneState {
 
 // Fold one 16-byte vector of verifier logits (and the matching drafter vector) into the state.
 // Must be called by all lanes of a wave together; `valid` masks lanes past the row chunk's end.
-template <bool BF16, bool KL>
+// TRACKD: also keep the index of the drafter's maximum (only the all-scores entry point asks for it)
+template <bool BF16, bool KL, bool TRACKD>
 __device__ __forceinline__ void consume(const uint4 &rv, const uint4 &rd, bool valid, int elem_base, LaneState &st)
 {
     constexpr int E = VecTraits<BF16>::kElems;
@@ -138,17 +139,19 @@ __device__ __forceinline__ void consume(const uint4 &rv, const uint4 &rd, bool v
         if (!valid) dmax = kNegInf;
         if (__any(dmax > st.ref_d + kLazyMargin)) {
             const float wmax = wave_max(dmax);
-            int cand = INT_MAX;
-            if (valid && dmax == wmax) {
+            if (TRACKD) {
+                int cand = INT_MAX;
+                if (valid && dmax == wmax) {
 #pragma unroll
-                for (int e = E - 1; e >= 0; --e)
-                    if (xd[e] == wmax) cand = elem_base + e;
+                    for (int e = E - 1; e >= 0; --e)
+                        if (xd[e] == wmax) cand = elem_base + e;
+                }
+                st.idx_d = wave_min(cand);
             }
             const float c = rescale_factor(st.ref_d, wmax);
             st.s_d *= c;
             st.a *= c;
             st.ref_d = wmax;
-            st.idx_d = wave_min(cand);
         }
     }
     if (valid) {
@@ -197,7 +200,7 @@ __device__ __forceinline__ WaveState merge(const WaveState &x, const WaveState &
 
 // Reduce vectors [vbeg, vend) of one row with a workgroup of THREADS lanes.  Returns true on thread 0,
 // whose `out` then holds the merged state of the range (lanes -> waves -> workgroup, fixed order).
-template <bool BF16, bool KL, int THREADS>
+template <bool BF16, bool KL, int THREADS, bool TRACKD>
 __device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const uint4 *__restrict__ pd,
                                              int vbeg, int vend, WaveState &out)
 {
@@ -217,7 +220,7 @@ __device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            consume<BF16, KL>(rv[u], rd[u], true, (base + u * THREADS + tid) * E, st);
+            consume<BF16, KL, TRACKD>(rv[u], rd[u], true, (base + u * THREADS + tid) * E, st);
     }
     // ragged remainder of the range
     if (base < vend) {
@@ -236,7 +239,7 @@ __device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const
         }
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            consume<BF16, KL>(rv[u], rd[u], ok[u], (base + u * THREADS + tid) * E, st);
+            consume<BF16, KL, TRACKD>(rv[u], rd[u], ok[u], (base + u * THREADS + tid) * E, st);
     }
 
     // lanes -> wave (references are already wave-uniform), waves -> workgroup
@@ -260,7 +263,7 @@ __device__ __forceinline__ bool reduce_range(const uint4 *__restrict__ pv, const
 }
 
 // grid: P * S workgroups; workgroup (row, split) reduces vectors [split*chunk, (split+1)*chunk) of its row
-template <bool BF16, bool KL>
+template <bool BF16, bool KL, bool TRACKD = false>
 __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *__restrict__ logits_d,
                                                                   const uint4 *__restrict__ logits_v,
                                                                   int nvec, int S, int chunk,
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void verify_partial_kernel(const uint4 *_
     const int vbeg = split * chunk;
     const int vend = min(nvec, vbeg + chunk);
     WaveState r;
-    if (reduce_range<BF16, KL, kThreads>(logits_v + rbase, KL ? logits_d + rbase : nullptr, vbeg, vend, r)) {
+    if (reduce_range<BF16, KL, kThreads, TRACKD>(logits_v + rbase, KL ? logits_d + rbase : nullptr, vbeg, vend, r)) {
         VerifyPartial p;
         p.ref_d = r.ref_d; p.s_d = r.s_d; p.a = r.a;
         p.best_v = r.best_v; p.s_v = r.s_v; p.idx = r.idx;
@@ -372,7 +375,7 @@ __global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartia
 
 // One workgroup per row: stream the whole row and finish it in the same kernel (no partial states,
 // no second launch).  Used whenever there are enough rows to fill the chip with such workgroups.
-template <bool BF16, bool KL, int THREADS>
+template <bool BF16, bool KL, int THREADS, bool TRACKD = false>
 __global__ __launch_bounds__(THREADS) void verify_row_kernel(const uint4 *__restrict__ logits_d,
                                                              const uint4 *__restrict__ logits_v, int nvec,
                                                              const uint8_t *__restrict__ mask, int mode,
@@ -384,7 +387,7 @@ __global__ __launch_bounds__(THREADS) void verify_row_kernel(const uint4 *__rest
     const int row = blockIdx.x;
     const size_t rbase = (size_t)row * (size_t)nvec;
     WaveState r;
-    if (reduce_range<BF16, KL, THREADS>(logits_v + rbase, KL ? logits_d + rbase : nullptr, 0, nvec, r))
+    if (reduce_range<BF16, KL, THREADS, TRACKD>(logits_v + rbase, KL ? logits_d + rbase : nullptr, 0, nvec, r))
         finish_row(row, (double)r.ref_d, (double)r.s_d, (double)r.a, (double)r.best_v, (double)r.s_v, r.idx,
                    mask, mode, threshold, seed, KL ? 1 : 0, out_mask, out_tokens, out_scores, r.idx_d, ex);
 }
@@ -533,15 +536,15 @@ size_t verify_workspace_bytes(int P, int V, int elem_bytes)
     return (size_t)P * (size_t)verify_splits(P, V, elem_bytes) * sizeof(VerifyPartial);
 }
 
-template <bool BF16, bool KL>
+template <bool BF16, bool KL, bool TRACKD = false>
 static hipError_t launch_row_kernel(int threads, dim3 grid, hipStream_t stream, const uint4 *ld, const uint4 *lv,
                                     int nvec, const uint8_t *mask, int mode, float threshold, uint64_t seed,
                                     uint8_t *out_mask, int32_t *out_tokens, float *out_scores, VerifyExtra ex)
 {
     if (threads == 256)
-        return launch(verify_row_kernel<BF16, KL, 256>, grid, dim3(256), stream, ld, lv, nvec, mask, mode,
+        return launch(verify_row_kernel<BF16, KL, 256, TRACKD>, grid, dim3(256), stream, ld, lv, nvec, mask, mode,
                       threshold, seed, out_mask, out_tokens, out_scores, ex);
-    return launch(verify_row_kernel<BF16, KL, 512>, grid, dim3(512), stream, ld, lv, nvec, mask, mode,
+    return launch(verify_row_kernel<BF16, KL, 512, TRACKD>, grid, dim3(512), stream, ld, lv, nvec, mask, mode,
                   threshold, seed, out_mask, out_tokens, out_scores, ex);
 }
 
@@ -561,7 +564,12 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
     const uint4 *lv = static_cast<const uint4 *>(logits_v);
     hipError_t e;
     const int fused = verify_fused_threads(P);
-    if (fused != 0) {
+    const bool track_d = mode == kModeScores && ex.tok_d != nullptr;     // the drafter's argmax is wanted as well
+    if (fused != 0 && track_d) {
+        const dim3 grid((unsigned)P);
+        e = logit_is_bf16 ? launch_row_kernel<true, true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex)
+                          : launch_row_kernel<false, true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex);
+    } else if (fused != 0) {
         const dim3 grid((unsigned)P);
         if (logit_is_bf16)
             e = kl ? launch_row_kernel<true, true>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex)
@@ -574,7 +582,10 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
         const int chunk = (nvec + S - 1) / S;
         VerifyPartial *part = static_cast<VerifyPartial *>(workspace);
         const dim3 grid((unsigned)((long)P * S)), block(kThreads);
-        if (logit_is_bf16) {
+        if (track_d) {
+            e = logit_is_bf16 ? launch(verify_partial_kernel<true, true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part)
+                              : launch(verify_partial_kernel<false, true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
+        } else if (logit_is_bf16) {
             if (kl) e = launch(verify_partial_kernel<true, true>, grid, block, stream, ld, lv, nvec, S, chunk, part);
             else    e = launch(verify_partial_kernel<true, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
         } else {
