@@ -466,14 +466,9 @@ __device__ __forceinline__ void refresh_cache_rows(const RefreshArgs &r)
 
 // Merge the per-split partial states of each query row: O = sum_s 2^{m_s-M} O_s / sum_s 2^{m_s-M} l_s.
 template <bool OUT_BF16>
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
-                                                           const float *__restrict__ part_ml, void *__restrict__ O,
-                                                           long rows, int splits, int d, const RefreshArgs refresh)
+__device__ __forceinline__ void combine_rows(const float *__restrict__ part_o, const float *__restrict__ part_ml,
+                                             void *__restrict__ O, long rows, int splits, int d)
 {
-    if ((int)blockIdx.x >= refresh.first_wg) {             // workgroup-uniform: these only copy
-        refresh_cache_rows(refresh);
-        return;
-    }
     const int per_row = d / 4;
     const long gid = (long)blockIdx.x * blockDim.x + threadIdx.x;
     const long row = gid / per_row;
@@ -514,6 +509,28 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         *reinterpret_cast<float4 *>(static_cast<float *>(O) + row * d + c4 * 4) =
             make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
     }
+}
+
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
+                                                           const float *__restrict__ part_ml, void *__restrict__ O,
+                                                           long rows, int splits, int d)
+{
+    combine_rows<OUT_BF16>(part_o, part_ml, O, rows, splits, d);
+}
+
+// the same launch with the block-completion copy on the workgroups past the merging ones
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void attn_combine_refresh_kernel(const float *__restrict__ part_o,
+                                                                   const float *__restrict__ part_ml,
+                                                                   void *__restrict__ O, long rows, int splits, int d,
+                                                                   const RefreshArgs refresh)
+{
+    if ((int)blockIdx.x >= refresh.first_wg) {             // workgroup-uniform: these only copy
+        refresh_cache_rows(refresh);
+        return;
+    }
+    combine_rows<OUT_BF16>(part_o, part_ml, O, rows, splits, d);
 }
 
 }  // namespace
@@ -618,9 +635,14 @@ static hipError_t launch_combine_refresh(const AttnArgs &a, bool merge, hipStrea
     }
     if (merge_wgs + copy_wgs == 0) return hipSuccess;
     const dim3 grid((unsigned)(merge_wgs + copy_wgs)), block(256);
+    if (copy_wgs == 0) {
+        if (a.v_dtype == 1)
+            return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
+        return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
+    }
     if (a.v_dtype == 1)
-        return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
-    return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
+        return launch(attn_combine_refresh_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
+    return launch(attn_combine_refresh_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
 }
 
 hipError_t launch_attention_combine(const AttnArgs &a, hipStream_t stream)
