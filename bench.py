@@ -202,6 +202,18 @@ def main():
     if "verify" in parts:
         assert torch.isfinite(out_sc).all().item(), "non-finite verification scores"
     t_block, t_attn, t_ver = (max(t, 1e-9) for t in (t_block, t_attn, t_ver))
+    per_step = {"block_attention_xK": [m[0].elapsed_time(m[1]) for m in rec],
+                "bidir_attention": [m[4].elapsed_time(m[2]) for m in rec],
+                "verify_remask": [m[2].elapsed_time(m[3]) for m in rec]}
+
+    # the same parts with every step on ONE input set: whatever fits stays in the 256 MB last-level cache.
+    # Reported beside the figures above, which rotate input sets and are the ones every rate is computed from.
+    warm_rec = []
+    for i in range(args.warmup):
+        step(0)
+    for i in range(args.steps):
+        step(0, warm_rec)
+    torch.cuda.synchronize()
 
     # the same steps replayed as HIP graphs (one per input set): what the cycle costs without the host in the loop
     graph_ms = None
@@ -272,6 +284,13 @@ def main():
         "verify_GBps": round(ver_gbps, 1),
         "components_ms": {"block_attention_xK": round(t_block, 4), "bidir_attention": round(t_attn, 4),
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
+        "components_median_ms": {k: round(float(np.median(v)), 4) for k, v in per_step.items()},
+        "components_min_ms": {k: round(float(np.min(v)), 4) for k, v in per_step.items()},
+        "warm_cache_components_ms": {
+            "block_attention_xK": round(sum(m[0].elapsed_time(m[1]) for m in warm_rec) / len(warm_rec), 4),
+            "bidir_attention": round(sum(m[4].elapsed_time(m[2]) for m in warm_rec) / len(warm_rec), 4),
+            "verify_remask": round(sum(m[2].elapsed_time(m[3]) for m in warm_rec) / len(warm_rec), 4),
+            "note": "every step on the same input set (operands that fit stay in the last-level cache); not used for any rate"},
         "block_attention_GBps": round(blk_gbps, 1),
         "graph_replay": None if graph_ms is None else {
             "ms_per_step": round(graph_ms, 4),
@@ -326,6 +345,21 @@ def main():
                                "kind": "oracle",
                                "sample": f"fp64 oracle attention on {n} random (b,h,i) query rows of this workload "
                                          f"({t:.1f} s); rate = rows*4*N*d FLOP / time"}
+        # the same oracle on one thread (a shorter sample), through the OpenMP runtime the oracle is linked to
+        gomp = None
+        try:
+            import ctypes
+            gomp = ctypes.CDLL("libgomp.so.1")
+            gomp.omp_set_num_threads(1)
+            n1 = max(16, n // (4 * oracle.num_threads()))
+            t1 = run_attn(n1)
+            out["cpu_baseline"]["value_1_thread"] = float(f"{n1 * 4.0 * cfg.N * cfg.d / t1 / 1e12:.3e}")
+            out["cpu_baseline"]["sample_1_thread"] = f"{n1} rows ({t1:.1f} s)"
+        except OSError:
+            gomp = None
+        finally:
+            if gomp is not None:
+                gomp.omp_set_num_threads(oracle.num_threads())
 
         def run_ver(n):
             r = rng.integers(0, cfg.P, n)
@@ -339,6 +373,13 @@ def main():
         out["cpu_baseline_verify"] = {"value": round(n * (2 if kl_mode else 1) * cfg.V * eb_l / t / 1e9, 4),
                                       "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
                                       "sample": f"fp64 oracle verify scores on {n} logit rows ({t:.1f} s)"}
+        if gomp is not None:
+            gomp.omp_set_num_threads(1)
+            n1 = max(8, n // (4 * oracle.num_threads()))
+            t1 = run_ver(n1)
+            gomp.omp_set_num_threads(oracle.num_threads())
+            out["cpu_baseline_verify"]["value_1_thread"] = round(n1 * (2 if kl_mode else 1) * cfg.V * eb_l / t1 / 1e9, 4)
+            out["cpu_baseline_verify"]["sample_1_thread"] = f"{n1} logit rows ({t1:.1f} s)"
     print(json.dumps(out), flush=True)
 
 
