@@ -299,6 +299,7 @@ def main():
         "roofline": {"kernel": attn_kernel, "bound": attn_bound,
                      "achieved": round(attn_tflops, 3), "peak": round(attn_peak, 1), "unit": "TFLOP/s",
                      "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
+                     "frac_of_bf16_peak": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),
                      "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
         "roofline_verify": {"kernel": ("verify_row_kernel" if cfg.P >= 192 else "verify_partial_kernel + verify_finalize_kernel")
