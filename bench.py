@@ -51,7 +51,13 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--parts", default="block,attention,verify",
                     help="comma list of the step's parts to run (profiling a single kernel); default: the whole step; "
-                         "'unmask' adds the drafter's unmasking step after the K block calls")
+                         "'unmask' adds the drafter's unmasking step after the K block calls, 'scores' one "
+                         "dd_verify_scores call (KL, both confidences, both argmax tokens) after the verification")
+    ap.add_argument("--refresh-last", action="store_true",
+                    help="the last of the K drafter calls completes its block: dd_block_attention_refresh")
+    ap.add_argument("--window", type=int, default=0,
+                    help="the drafter attends over a window of this many key rows around the block "
+                         "(dd_block_attention_window) instead of the whole cache")
     ap.add_argument("--calib-copy-mb", type=int, default=0,
                     help="after the timed steps, run one device-to-device copy of this many MiB (a kernel of known "
                          "traffic, used to scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -122,7 +128,7 @@ def main():
         sets.append({
             "Q": up(att["Q"]), "K": up(att["K"]), "V": up(att["V"]),
             "Kc": up(cache["Kc"]), "Vc": up(cache["Vc"]),
-            "ld": up(ver["logits_d"]) if kl_mode else None, "lv": up(ver["logits_v"]),
+            "ld": up(ver["logits_d"]) if (kl_mode or "scores" in args.parts.split(",")) else None, "lv": up(ver["logits_v"]),
         })
     qs, ks = up(att["q_scale"]), up(att["k_scale"])
     kcs = up(cache["k_scale"])
@@ -158,13 +164,28 @@ def main():
         um_conf = torch.empty(cfg.B * cfg.bl, dtype=torch.float32, device=dev)
         um_x = torch.zeros(cfg.B * cfg.bl, dtype=torch.int32, device=dev)
 
+    win = min(args.window, cfg.N) if args.window > 0 else 0
+    if win and win < cfg.bl:
+        print("bench.py: --window must cover the block", file=sys.stderr)
+        sys.exit(2)
+    if win:                                              # K/V bytes of a call follow the window
+        block_bytes = cfg.B * cfg.Hkv * win * cfg.d * (eb_qk + eb_v) + blk_rows * (eb_qk + eb_v)
+
     def step(i, rec=None):
         s = sets[i % n_sets]
-        marks = [ev() for _ in range(5)] if rec is not None else None
+        marks = [ev() for _ in range(6)] if rec is not None else None
         if marks: marks[0].record()
-        for b in (blk_dev if "block" in parts else ()):
-            dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], O=Oblk, Kblk=b["K"], Vblk=b["V"],
-                                         q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
+        for k, b in enumerate(blk_dev if "block" in parts else ()):
+            kw = dict(O=Oblk, Kblk=b["K"], Vblk=b["V"], q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype,
+                      v_dtype=cfg.v_dtype)
+            if win:
+                w0 = min(max(0, b["bs"] + cfg.bl // 2 - win // 2), cfg.N - win)
+                dd.dd_block_attention_window(b["Q"], s["Kc"], s["Vc"], b["bs"], w0, win, **kw)
+            elif args.refresh_last and k == cfg.K - 1:
+                kw.pop("Kblk"); kw.pop("Vblk")
+                dd.dd_block_attention_refresh(b["Q"], s["Kc"], s["Vc"], b["bs"], b["K"], b["V"], **kw)
+            else:
+                dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], **kw)
         if marks: marks[1].record()
         for u in unmask_dev:
             dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
@@ -175,10 +196,13 @@ def main():
                                   qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
         if marks: marks[2].record()
         if "verify" in parts:
-            dd.dd_verify_remask(s["ld"], s["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
+            dd.dd_verify_remask(s["ld"] if kl_mode else None, s["lv"], mask, mode, tau, args.seed, cfg.B, cfg.G,
                                 out_mask=out_mask, out_tokens=out_tok, out_scores=out_sc, logit_dtype=cfg.logit_dtype)
+        if marks: marks[3].record()
+        if "scores" in parts:
+            dd.dd_verify_scores(s["ld"], s["lv"], logit_dtype=cfg.logit_dtype)
         if marks:
-            marks[3].record()
+            marks[5].record()
             rec.append(marks)
 
     for i in range(args.warmup):
@@ -311,6 +335,18 @@ def main():
                             "algorithmic_bytes": verify_bytes},
     }
 
+    if "scores" in parts:
+        t_sc = max(sum(m[3].elapsed_time(m[5]) for m in rec) / len(rec), 1e-9)
+        sc_bytes = 2 * cfg.P * cfg.V * eb_l
+        out["components_ms"]["verify_scores"] = round(t_sc, 4)
+        out["roofline_scores"] = {"kernel": "verify_row_kernel<.., KL, .., TRACKD> / verify_partial_kernel + verify_finalize_kernel (dd_verify_scores)",
+                                  "bound": "hbm", "achieved": round(sc_bytes / (t_sc * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBPS,
+                                  "unit": "GB/s", "frac": round(sc_bytes / (t_sc * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4),
+                                  "traffic": None, "algorithmic_bytes": sc_bytes,
+                                  "note": "both logit matrices read once; outputs allocated by the binding inside the timed call"}
+    if win or args.refresh_last:
+        out["config"]["drafter_call"] = (f"dd_block_attention_window, {win} key rows" if win else
+                                         "dd_block_attention_cached x (K-1) + dd_block_attention_refresh")
     if "unmask" in parts:
         um_gbps = unmask_bytes / (max(t_unmask, 1e-9) / cfg.K * 1e-3) / 1e9
         out["components_ms"]["unmask_xK"] = round(t_unmask, 4)

@@ -335,42 +335,47 @@ __device__ __forceinline__ void finish_row(int row, double md, double sd, double
     out_mask[row] = (uint8_t)((m != 0) || remask);
 }
 
-// one thread per row: merge the S partials in fp64, finish the scores, apply the rule
-__global__ __launch_bounds__(128) void verify_finalize_kernel(const VerifyPartial *__restrict__ part, int S, int P,
+// Sixteen lanes per row (S <= 16): lane s takes the partial state of split s, the group merges them in fp64
+// with xor-butterflies (every lane ends with the same totals: a + b == b + a exactly), lane 0 finishes the row.
+constexpr int kFinalizeLanes = 16;
+__global__ __launch_bounds__(256) void verify_finalize_kernel(const VerifyPartial *__restrict__ part, int S, int P,
                                                               const uint8_t *__restrict__ mask, int mode,
                                                               float threshold, uint64_t seed, int kl_mode,
                                                               uint8_t *__restrict__ out_mask,
                                                               int32_t *__restrict__ out_tokens,
                                                               float *__restrict__ out_scores, VerifyExtra ex)
 {
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= P) return;
-    const VerifyPartial *p = part + (size_t)row * S;
-    float mv = kNegInf, md = kNegInf;
-    int idx = INT_MAX, idx_d = INT_MAX;
-    for (int s = 0; s < S; ++s) {
-        const float b = p[s].best_v;
-        if (b > mv || (b == mv && p[s].idx < idx)) {
-            mv = b;
-            idx = p[s].idx;
-        }
-        const float rd = p[s].ref_d;
-        if (kl_mode && (rd > md || (rd == md && p[s].idx_d < idx_d))) {
-            md = rd;
-            idx_d = p[s].idx_d;
-        }
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int row = gid / kFinalizeLanes, sp = gid % kFinalizeLanes;
+    const bool have = row < P && sp < S;                   // no early exit: the shuffles below need every lane
+    VerifyPartial p;
+    p.ref_d = kNegInf; p.s_d = 0.f; p.a = 0.f; p.best_v = kNegInf; p.s_v = 0.f; p.idx = INT_MAX; p.idx_d = INT_MAX;
+    if (have) p = part[(size_t)row * S + sp];
+    float mv = p.best_v, md = kl_mode ? p.ref_d : kNegInf;
+    int idx = p.idx, idx_d = p.idx_d;
+#pragma unroll
+    for (int o = kFinalizeLanes / 2; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(mv, o), od = __shfl_xor(md, o);
+        const int oi = __shfl_xor(idx, o), oid = __shfl_xor(idx_d, o);
+        if (ov > mv || (ov == mv && oi < idx)) { mv = ov; idx = oi; }
+        if (od > md || (od == md && oid < idx_d)) { md = od; idx_d = oid; }
     }
     double sv = 0.0, sd = 0.0, a = 0.0;
-    for (int s = 0; s < S; ++s) {
-        if (p[s].best_v != kNegInf) sv += (double)p[s].s_v * exp((double)p[s].best_v - (double)mv);
-        if (kl_mode && p[s].ref_d != kNegInf) {
-            const double c = exp((double)p[s].ref_d - (double)md);
-            sd += (double)p[s].s_d * c;
-            a += (double)p[s].a * c;
-        }
+    if (p.best_v != kNegInf) sv = (double)p.s_v * exp((double)p.best_v - (double)mv);
+    if (kl_mode && p.ref_d != kNegInf) {
+        const double c = exp((double)p.ref_d - (double)md);
+        sd = (double)p.s_d * c;
+        a = (double)p.a * c;
     }
-    finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores,
-               idx_d, ex);
+#pragma unroll
+    for (int o = kFinalizeLanes / 2; o > 0; o >>= 1) {
+        sv += __shfl_xor(sv, o);
+        sd += __shfl_xor(sd, o);
+        a += __shfl_xor(a, o);
+    }
+    if (sp == 0 && row < P)
+        finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores,
+                   idx_d, ex);
 }
 
 // One workgroup per row: stream the whole row and finish it in the same kernel (no partial states,
@@ -593,7 +598,7 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
             else    e = launch(verify_partial_kernel<false, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
         }
         if (e != hipSuccess) return e;
-        e = launch(verify_finalize_kernel, dim3((P + 127) / 128), dim3(128), stream,
+        e = launch(verify_finalize_kernel, dim3((unsigned)(((long)P * kFinalizeLanes + 255) / 256)), dim3(256), stream,
                    (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores,
                    ex);
     }
