@@ -338,16 +338,16 @@ __device__ __forceinline__ void finish_row(int row, double md, double sd, double
 // Sixteen lanes per row (S <= 16): lane s takes the partial state of split s, the group merges them in fp64
 // with xor-butterflies (every lane ends with the same totals: a + b == b + a exactly), lane 0 finishes the row.
 constexpr int kFinalizeLanes = 16;
-__global__ __launch_bounds__(256) void verify_finalize_kernel(const VerifyPartial *__restrict__ part, int S, int P,
-                                                              const uint8_t *__restrict__ mask, int mode,
-                                                              float threshold, uint64_t seed, int kl_mode,
-                                                              uint8_t *__restrict__ out_mask,
-                                                              int32_t *__restrict__ out_tokens,
-                                                              float *__restrict__ out_scores, VerifyExtra ex)
+// Called by whole groups of sixteen consecutive lanes (lane sp of the group takes split sp of `row`); `row_ok`
+// false for a group without a row: it still takes part in the shuffles.
+__device__ __forceinline__ void merge_splits_and_finish(const VerifyPartial *__restrict__ part, int S, long row,
+                                                        bool row_ok, int sp, const uint8_t *__restrict__ mask,
+                                                        int mode, float threshold, uint64_t seed, int kl_mode,
+                                                        uint8_t *__restrict__ out_mask,
+                                                        int32_t *__restrict__ out_tokens,
+                                                        float *__restrict__ out_scores, const VerifyExtra &ex)
 {
-    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
-    const int row = gid / kFinalizeLanes, sp = gid % kFinalizeLanes;
-    const bool have = row < P && sp < S;                   // no early exit: the shuffles below need every lane
+    const bool have = row_ok && sp < S;                    // no early exit: the shuffles below need every lane
     VerifyPartial p;
     p.ref_d = kNegInf; p.s_d = 0.f; p.a = 0.f; p.best_v = kNegInf; p.s_v = 0.f; p.idx = INT_MAX; p.idx_d = INT_MAX;
     if (have) p = part[(size_t)row * S + sp];
@@ -373,9 +373,22 @@ __global__ __launch_bounds__(256) void verify_finalize_kernel(const VerifyPartia
         sd += __shfl_xor(sd, o);
         a += __shfl_xor(a, o);
     }
-    if (sp == 0 && row < P)
-        finish_row(row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens, out_scores,
-                   idx_d, ex);
+    if (sp == 0 && row_ok)
+        finish_row((int)row, md, sd, a, mv, sv, idx, mask, mode, threshold, seed, kl_mode, out_mask, out_tokens,
+                   out_scores, idx_d, ex);
+}
+
+__global__ __launch_bounds__(256) void verify_finalize_kernel(const VerifyPartial *__restrict__ part, int S, int P,
+                                                              const uint8_t *__restrict__ mask, int mode,
+                                                              float threshold, uint64_t seed, int kl_mode,
+                                                              uint8_t *__restrict__ out_mask,
+                                                              int32_t *__restrict__ out_tokens,
+                                                              float *__restrict__ out_scores, VerifyExtra ex)
+{
+    const int gid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int row = gid / kFinalizeLanes;
+    merge_splits_and_finish(part, S, row, row < P, gid % kFinalizeLanes, mask, mode, threshold, seed, kl_mode, out_mask,
+                            out_tokens, out_scores, ex);
 }
 
 // One workgroup per row: stream the whole row and finish it in the same kernel (no partial states,
@@ -398,26 +411,25 @@ __global__ __launch_bounds__(THREADS) void verify_row_kernel(const uint4 *__rest
 }
 
 // Eq. 6: one workgroup per sequence sums the divergences of its eligible rows, then draws
-__global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restrict__ scores,
-                                                            const uint8_t *__restrict__ mask, int G, uint64_t seed,
-                                                            uint8_t *__restrict__ out_mask)
+template <int THREADS>
+__device__ __forceinline__ void klprob_sequence(const float *__restrict__ scores, const uint8_t *__restrict__ mask,
+                                                size_t base, int G, uint64_t seed, uint8_t *__restrict__ out_mask,
+                                                double *red)
 {
-    __shared__ double red[256];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const size_t base = (size_t)b * G;
+    const int tid = threadIdx.x;
     double local = 0.0;
-    for (int g = tid; g < G; g += 256) {
+    for (int g = tid; g < G; g += THREADS) {
         const float s = scores[base + g];
         if (mask[base + g] == 0 && s > 0.0f) local += (double)s;
     }
     red[tid] = local;
     __syncthreads();
-    for (int o = 128; o > 0; o >>= 1) {
+    for (int o = THREADS / 2; o > 0; o >>= 1) {
         if (tid < o) red[tid] += red[tid + o];
         __syncthreads();
     }
     const double total = red[0];
-    for (int g = tid; g < G; g += 256) {
+    for (int g = tid; g < G; g += THREADS) {
         const size_t i = base + g;
         const float s = scores[i];
         const double k = s > 0.0f ? (double)s : 0.0;
@@ -427,6 +439,14 @@ __global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restr
     }
 }
 
+__global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restrict__ scores,
+                                                            const uint8_t *__restrict__ mask, int G, uint64_t seed,
+                                                            uint8_t *__restrict__ out_mask)
+{
+    __shared__ double red[256];
+    klprob_sequence<256>(scores, mask, (size_t)blockIdx.x * G, G, seed, out_mask, red);
+}
+
 // Budgeted remasking: rank the eligible rows of a sequence by badness (KL: larger score, confidence: smaller
 // score; equal scores: lower row first) and remask those of rank < k.  The rank of a row is the number of
 // eligible rows of its sequence that are worse.  One workgroup takes 64 rows of one sequence, four lanes per
@@ -434,9 +454,10 @@ __global__ __launch_bounds__(256) void verify_klprob_kernel(const float *__restr
 // read back 16 bytes at a time (a scalar loop here is bound by the LDS latency of every single read).
 constexpr int kTopkRows = 64, kTopkChunk = 2048;
 // Rank of row g among the rows of its sequence whose mask byte equals `want` (the candidates), ordered by
-// sign * score descending, equal values by row; -1 for a row that is no candidate.  Called by all 256 lanes
-// of a workgroup (it contains barriers); lanes 4r..4r+3 hold row r of the workgroup's 64 and all four
+// sign * score descending, equal values by row; -1 for a row that is no candidate.  Called by all THREADS lanes
+// of a workgroup (it contains barriers); lanes 4r..4r+3 hold row r of the workgroup's THREADS / 4 and all four
 // return its rank.
+template <int THREADS>
 __device__ __forceinline__ int sequence_rank(const float *__restrict__ scores, const uint8_t *__restrict__ mask,
                                              size_t base, int G, int g, uint8_t want, float sign, float *bad_sh)
 {
@@ -447,7 +468,7 @@ __device__ __forceinline__ int sequence_rank(const float *__restrict__ scores, c
     for (int c0 = 0; c0 < G; c0 += kTopkChunk) {             // uniform trip count: every lane reaches the barriers
         const int n = min(kTopkChunk, G - c0), n16 = (n + 15) & ~15;
         __syncthreads();
-        for (int j = tid; j < n16; j += 256)                 // -inf marks a row that is no candidate
+        for (int j = tid; j < n16; j += THREADS)             // -inf marks a row that is no candidate
             bad_sh[j] = (j < n && mask[base + c0 + j] == want) ? sign * scores[base + c0 + j] : kNegInf;
         __syncthreads();
         if (candidate) {
@@ -467,22 +488,46 @@ __device__ __forceinline__ int sequence_rank(const float *__restrict__ scores, c
     return candidate ? rank : -1;
 }
 
+// rows [slab * THREADS / 4, + THREADS / 4) of the sequence at `base`; called by all lanes of a workgroup
+template <int THREADS>
+__device__ __forceinline__ void topk_slab(const float *__restrict__ scores, const uint8_t *__restrict__ mask,
+                                          size_t base, int G, int slab, int kl_mode, float budget,
+                                          uint8_t *__restrict__ out_mask, float *bad_sh)
+{
+    const int tid = threadIdx.x;
+    const int g = slab * (THREADS / 4) + tid / 4;
+    const int rank = sequence_rank<THREADS>(scores, mask, base, G, g, 0, kl_mode ? 1.0f : -1.0f, bad_sh);
+    if (g < G && tid % 4 == 0) out_mask[base + g] = (uint8_t)(mask[base + g] != 0 || (rank >= 0 && (float)rank < budget));
+}
+
 __global__ __launch_bounds__(256) void verify_topk_kernel(const float *__restrict__ scores,
                                                           const uint8_t *__restrict__ mask, int G, int kl_mode,
                                                           float budget, uint8_t *__restrict__ out_mask)
 {
     __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];
     const int slabs = (G + kTopkRows - 1) / kTopkRows;        // workgroups per sequence
-    const int b = blockIdx.x / slabs, tid = threadIdx.x;
-    const size_t base = (size_t)b * G;
-    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4;
-    const int rank = sequence_rank(scores, mask, base, G, g, 0, kl_mode ? 1.0f : -1.0f, bad_sh);
-    if (g < G && tid % 4 == 0) out_mask[base + g] = (uint8_t)(mask[base + g] != 0 || (rank >= 0 && (float)rank < budget));
+    topk_slab<256>(scores, mask, (size_t)(blockIdx.x / slabs) * G, G, blockIdx.x % slabs, kl_mode, budget, out_mask, bad_sh);
 }
 
 // Drafter unmasking (Alg. 1, drafting phase): of the positions that still hold [MASK], those selected by
 // confidence are decoded to the drafter's most likely token.  mode 0: confidence above the threshold, and
 // always the most confident one of the sequence; mode 1: the k most confident ones.
+template <int THREADS>
+__device__ __forceinline__ void unmask_slab(const float *__restrict__ conf, const uint8_t *__restrict__ mask,
+                                            const int32_t *__restrict__ tokens, size_t base, int G, int slab, int mode,
+                                            float threshold, uint8_t *__restrict__ out_mask, int32_t *__restrict__ x,
+                                            float *bad_sh)
+{
+    const int tid = threadIdx.x;
+    const int g = slab * (THREADS / 4) + tid / 4;
+    const int rank = sequence_rank<THREADS>(conf, mask, base, G, g, 1, 1.0f, bad_sh);
+    if (g < G && tid % 4 == 0) {
+        const bool take = rank >= 0 && (mode == 0 ? (rank == 0 || conf[base + g] > threshold) : (float)rank < threshold);
+        out_mask[base + g] = (uint8_t)(mask[base + g] != 0 && !take);
+        if (take && x) x[base + g] = tokens[base + g];
+    }
+}
+
 __global__ __launch_bounds__(256) void unmask_select_kernel(const float *__restrict__ conf,
                                                             const uint8_t *__restrict__ mask,
                                                             const int32_t *__restrict__ tokens, int G, int mode,
@@ -491,14 +536,45 @@ __global__ __launch_bounds__(256) void unmask_select_kernel(const float *__restr
 {
     __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];
     const int slabs = (G + kTopkRows - 1) / kTopkRows;
-    const int b = blockIdx.x / slabs, tid = threadIdx.x;
-    const size_t base = (size_t)b * G;
-    const int g = (blockIdx.x % slabs) * kTopkRows + tid / 4;
-    const int rank = sequence_rank(conf, mask, base, G, g, 1, 1.0f, bad_sh);
-    if (g < G && tid % 4 == 0) {
-        const bool take = rank >= 0 && (mode == 0 ? (rank == 0 || conf[base + g] > threshold) : (float)rank < threshold);
-        out_mask[base + g] = (uint8_t)(mask[base + g] != 0 && !take);
-        if (take && x) x[base + g] = tokens[base + g];
+    unmask_slab<256>(conf, mask, tokens, (size_t)(blockIdx.x / slabs) * G, G, blockIdx.x % slabs, mode, threshold, out_mask,
+                     x, bad_sh);
+}
+
+// Split path with a per-sequence rule (Eq. 6, the budgeted rules, the unmasking step): one workgroup per
+// sequence first finishes the rows of its sequence from their partial states, then applies the rule to them
+// - the second and third launch of such a call in one.  The scores and tokens the rule reads were written by
+// this workgroup; the barrier between the two phases makes them visible to all of its lanes.
+constexpr int kSeqThreads = 1024;
+__global__ __launch_bounds__(kSeqThreads) void verify_finalize_seq_kernel(const VerifyPartial *__restrict__ part, int S, int G,
+                                                                  const uint8_t *__restrict__ mask, int mode,
+                                                                  float threshold, uint64_t seed, int kl_mode,
+                                                                  uint8_t *__restrict__ out_mask,
+                                                                  int32_t *__restrict__ out_tokens,
+                                                                  float *__restrict__ out_scores,
+                                                                  int32_t *__restrict__ x_tokens)
+{
+    __shared__ __attribute__((aligned(16))) float bad_sh[kTopkChunk];
+    __shared__ double red[kSeqThreads];
+    const int tid = threadIdx.x;
+    const size_t base = (size_t)blockIdx.x * G;
+    constexpr int kRowsPerPass = kSeqThreads / kFinalizeLanes;
+    for (int g0 = 0; g0 < G; g0 += kRowsPerPass) {           // uniform trip count
+        const int g = g0 + tid / kFinalizeLanes;
+        merge_splits_and_finish(part, S, (long)base + g, g < G, tid % kFinalizeLanes, mask, mode, threshold, seed, kl_mode,
+                                out_mask, out_tokens, out_scores, VerifyExtra{});
+    }
+    __threadfence_block();
+    __syncthreads();
+    const int slabs = (G + kSeqThreads / 4 - 1) / (kSeqThreads / 4);
+    if (mode == 3) {
+        klprob_sequence<kSeqThreads>(out_scores, mask, base, G, seed, out_mask, red);
+    } else if (mode == 5 || mode == 6) {
+        for (int slab = 0; slab < slabs; ++slab)
+            topk_slab<kSeqThreads>(out_scores, mask, base, G, slab, kl_mode, floorf(threshold), out_mask, bad_sh);
+    } else {
+        for (int slab = 0; slab < slabs; ++slab)
+            unmask_slab<kSeqThreads>(out_scores, mask, out_tokens, base, G, slab, mode - kModeUnmaskThresh,
+                                     mode == kModeUnmaskTopk ? floorf(threshold) : threshold, out_mask, x_tokens, bad_sh);
     }
 }
 
@@ -521,18 +597,30 @@ int verify_fused_threads(int P)
     return P >= 2048 ? 256 : 512;        // measured: 512 lanes per row stream best for 256..1024 rows
 }
 
-int verify_splits(int P, int V, int elem_bytes)
+// Vectors per split: a whole number of full iterations (kThreads * kUnroll vectors), so that only the last
+// split of a row has a ragged remainder - every load round of a workgroup is a dependent memory round trip,
+// and with few rows those round trips are the call.
+static int verify_split_chunk(int P, int V, int elem_bytes)
 {
-    if (P <= 0 || verify_fused_threads(P) != 0) return 1;
     const long nvec = (long)V * elem_bytes / 16;
     static const int forced = env_int("DD_TUNE_VERIFY_SPLITS", 0);
     static const int target = env_int("DD_TUNE_VERIFY_TARGET_WGS", 2048);
     long s = forced > 0 ? forced : (target + P - 1) / P;
-    const long max_s = nvec / (2L * kThreads * kUnroll);   // at least two full iterations per workgroup
-    if (s > max_s) s = max_s;
     if (s > 16) s = 16;
     if (s < 1) s = 1;
-    return (int)s;
+    const long iter = (long)kThreads * kUnroll;
+    long chunk = (nvec + s - 1) / s;
+    chunk = (chunk + iter - 1) / iter * iter;
+    return (int)chunk;
+}
+
+int verify_splits(int P, int V, int elem_bytes)
+{
+    if (P <= 0 || verify_fused_threads(P) != 0) return 1;
+    const long nvec = (long)V * elem_bytes / 16;
+    const long chunk = verify_split_chunk(P, V, elem_bytes);
+    const long s = (nvec + chunk - 1) / chunk;
+    return (int)(s < 1 ? 1 : s);
 }
 
 size_t verify_workspace_bytes(int P, int V, int elem_bytes)
@@ -584,7 +672,7 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
                    : launch_row_kernel<false, false>(fused, grid, stream, ld, lv, nvec, mask, mode, threshold, seed, out_mask, out_tokens, out_scores, ex);
     } else {
         const int S = verify_splits(P, V, eb);
-        const int chunk = (nvec + S - 1) / S;
+        const int chunk = verify_split_chunk(P, V, eb);
         VerifyPartial *part = static_cast<VerifyPartial *>(workspace);
         const dim3 grid((unsigned)((long)P * S)), block(kThreads);
         if (track_d) {
@@ -598,6 +686,9 @@ hipError_t launch_verify(const void *logits_d, const void *logits_v, const uint8
             else    e = launch(verify_partial_kernel<false, false>, grid, block, stream, ld, lv, nvec, S, chunk, part);
         }
         if (e != hipSuccess) return e;
+        if (mode == 3 || mode == 5 || mode == 6 || mode == kModeUnmaskThresh || mode == kModeUnmaskTopk)
+            return launch(verify_finalize_seq_kernel, dim3((unsigned)B), dim3(kSeqThreads), stream, (const VerifyPartial *)part, S,
+                          G, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores, x_tokens);
         e = launch(verify_finalize_kernel, dim3((unsigned)(((long)P * kFinalizeLanes + 255) / 256)), dim3(256), stream,
                    (const VerifyPartial *)part, S, P, mask, mode, threshold, seed, kl ? 1 : 0, out_mask, out_tokens, out_scores,
                    ex);
