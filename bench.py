@@ -72,6 +72,9 @@ def parse():
                          "the unmasking step; the verifier runs L full attentions, then the verification rule. "
                          "Reported as the extra object 'multi_layer' (32 = LLaDA-8B's depth)")
     ap.add_argument("--no-graph", action="store_true", help="skip the additional HIP-graph replay of the step")
+    ap.add_argument("--no-warm", action="store_true",
+                    help="skip the additional warm-cache repetition of the steps (profiling: every launch in the "
+                         "trace then belongs to the rotated, cold-cache steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
@@ -233,11 +236,12 @@ def main():
     # the same parts with every step on ONE input set: whatever fits stays in the 256 MB last-level cache.
     # Reported beside the figures above, which rotate input sets and are the ones every rate is computed from.
     warm_rec = []
-    for i in range(args.warmup):
-        step(0)
-    for i in range(args.steps):
-        step(0, warm_rec)
-    torch.cuda.synchronize()
+    if not args.no_warm:
+        for i in range(args.warmup):
+            step(0)
+        for i in range(args.steps):
+            step(0, warm_rec)
+        torch.cuda.synchronize()
 
     # the same steps replayed as HIP graphs (one per input set): what the cycle costs without the host in the loop
     graph_ms = None
@@ -310,7 +314,7 @@ def main():
                           "verify_remask": round(t_ver, 4), "host_wall_per_step": round(wall * 1e3 / args.steps, 4)},
         "components_median_ms": {k: round(float(np.median(v)), 4) for k, v in per_step.items()},
         "components_min_ms": {k: round(float(np.min(v)), 4) for k, v in per_step.items()},
-        "warm_cache_components_ms": {
+        "warm_cache_components_ms": None if not warm_rec else {
             "block_attention_xK": round(sum(m[0].elapsed_time(m[1]) for m in warm_rec) / len(warm_rec), 4),
             "bidir_attention": round(sum(m[4].elapsed_time(m[2]) for m in warm_rec) / len(warm_rec), 4),
             "verify_remask": round(sum(m[2].elapsed_time(m[3]) for m in warm_rec) / len(warm_rec), 4),
