@@ -126,13 +126,15 @@ _ws_cache = {}
 
 
 def _workspace(nbytes: int, device):
-    """A per-device scratch tensor (device memory only; the library never allocates)."""
+    """A scratch tensor per (device, stream) - device memory only; the library never allocates.  Calls on one
+    stream run in order and may share it; calls on different streams may overlap and must not."""
     if nbytes == 0:
         return None, 0
-    cur = _ws_cache.get(device)
+    key = (device, _stream())
+    cur = _ws_cache.get(key)
     if cur is None or cur.numel() < nbytes:
         cur = _torch().empty(max(nbytes, 1 << 20), dtype=_torch().uint8, device=device)
-        _ws_cache[device] = cur
+        _ws_cache[key] = cur
     return cur, cur.numel()
 
 

@@ -12,8 +12,9 @@ from typing import Callable
 
 
 def capture_step(fn: Callable[[], None], warmup: int = 2):
-    """Run `fn` (calls of this package on fixed tensors) `warmup` times on a side stream - so that the
-    binding's scratch tensor exists before capture - then record it once.  Returns the torch.cuda.CUDAGraph;
+    """Run `fn` (calls of this package on fixed tensors) `warmup` times on a side stream, then record it once
+    (the binding keeps one scratch tensor per stream; the one of the capture stream is allocated during capture
+    and belongs to the graph's memory pool).  Returns the torch.cuda.CUDAGraph;
     `graph.replay()` enqueues the whole sequence on the current stream."""
     import torch
     side = torch.cuda.Stream()                    # default priority
