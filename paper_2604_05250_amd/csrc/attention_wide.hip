@@ -537,17 +537,20 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto step = [&](int u, floatx16 (&s_cur)[QB], floatx16 (&s_nxt)[QB], unsigned (&pk_prev)[QB][2][4],
                     unsigned (&pk_cur)[QB][2][4], const uint4 *kb, int ksub, const uint4 *vb, int vsub,
                     auto primed, auto chain, auto dma, uint4 *dk, const uint8_t *kg,
-                    uint4 *dv, const uint8_t *vg, auto can_finish, bool fin, const Tile &cur)
+                    uint4 *dv, const uint8_t *vg, auto can_finish, bool fin, const Tile &cur, auto maskable)
                     __attribute__((always_inline)) {
         constexpr bool PRIMED = decltype(primed)::value, CHAIN = decltype(chain)::value;
         constexpr bool DMA = decltype(dma)::value, CANFIN = decltype(can_finish)::value;
+        // `maskable` false: the caller knows that unit u lies in a tile that starts at its nominal row (any tile
+        // of the verifier's pass before the last one), so there is nothing to mask and nothing to test
+        constexpr bool MASKABLE = BLOCK || decltype(maskable)::value;
         if (!PRIMED) {
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
         // rows of unit u's tile that lie before its nominal start repeat keys of the previous tile
-        const int lim = tile_at(cur, u >> 1).shift - 32 * (u & 1);
-        if (__builtin_expect(lim > 0, 0)) {                  // uniform branch: those score -inf
+        const int lim = MASKABLE ? tile_at(cur, u >> 1).shift - 32 * (u & 1) : 0;
+        if (MASKABLE && __builtin_expect(lim > 0, 0)) {      // uniform branch: those score -inf
             int k0 = 4 * hh;
             asm volatile("" : "+v"(k0));
 #pragma unroll
@@ -698,7 +701,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // `kind`: 0 = a stage in the middle of a pass (the hot loop: no tile-boundary logic at all),
     //         1 = the last but one stage (PAR = 0; its K load is tile 0 of the next row tile),
     //         2 = the last stage (PAR = 1).
-    auto stage = [&](int sp, auto par, auto kind) __attribute__((always_inline)) {
+    auto stage = [&](int sp, auto par, auto kind, auto maskable) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par)::value, KIND = decltype(kind)::value;
         static_assert(KIND == 0 || (KIND == 1 && PAR == 0) || (KIND == 2 && PAR == 1), "stage kinds");
         constexpr bool last = KIND == 2;
@@ -719,7 +722,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
              kbuf(I_<PAR>{}), tile_at(KIND == 0 || BLOCK ? cur : nxt, ktile).k,
-             vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur);
+             vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur, maskable);
         if (!BLOCK && KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
             mc_done[0] = mc[0];
@@ -730,7 +733,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
             c[1] = c_next[1];
         }
         step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
-             kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur);
+             kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur, maskable);
         // The barrier that ends a stage waits for the stage's tile loads.  Memory operations complete in
         // order, so the requests issued after those loads - the next tile's Q rows, the finished tile's
         // output rows - can stay in flight: wait until only that many are outstanding.
@@ -771,7 +774,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur);
+    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur, T_{});
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
 
     // ---- passes: stages 0 .. nt_even-1 = steps 1 .. 2 nt_even; the product with P(u) happens in step u+1,
@@ -787,18 +790,24 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #ifdef DDW_TIMING2
         const unsigned long long t0 = __builtin_readcyclecounter();
 #endif
+        // stages sp <= nt_even - 4 only touch units of tiles <= nt_even - 3 <= nt_local - 2: never the last
+        // tile of the key range, the only one of the verifier's pass that can overlap its predecessor
+        for (; sp + 4 < nt_even; sp += 2) {
+            stage(sp, I_<0>{}, I_<0>{}, F_{});
+            stage(sp + 1, I_<1>{}, I_<0>{}, F_{});
+        }
         for (; sp + 2 < nt_even; sp += 2) {
-            stage(sp, I_<0>{}, I_<0>{});
-            stage(sp + 1, I_<1>{}, I_<0>{});
+            stage(sp, I_<0>{}, I_<0>{}, T_{});
+            stage(sp + 1, I_<1>{}, I_<0>{}, T_{});
         }
 #ifdef DDW_TIMING2
         const unsigned long long t1 = __builtin_readcyclecounter();
 #endif
-        stage(sp, I_<0>{}, I_<1>{});
+        stage(sp, I_<0>{}, I_<1>{}, T_{});
 #ifdef DDW_TIMING2
         const unsigned long long t2 = __builtin_readcyclecounter();
 #endif
-        stage(sp + 1, I_<1>{}, I_<2>{});
+        stage(sp + 1, I_<1>{}, I_<2>{}, T_{});
 #ifdef DDW_TIMING2
         const unsigned long long t3 = __builtin_readcyclecounter();
         tacc[0] += t1 - t0; tacc[1] += t2 - t1; tacc[2] += t3 - t2;
