@@ -172,6 +172,27 @@ size_t dd_block_attention_window_workspace_bytes(int block_len, int win_len, int
                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
+ * Drafter attention for a batch whose sequences stand at different blocks (sequences of a serving batch finish
+ * their blocks at different times; Alg. 1 runs per sequence): as dd_block_attention_cached with Kblk/Vblk, but the
+ * active block of batch entry b begins at block_starts[b]:
+ *     key/value row j of batch b = Kblk/Vblk[b,g,j-block_starts[b],:]  if 0 <= j - block_starts[b] < block_len
+ *                                  Kc/Vc[b,g,j,:]                       otherwise.
+ *   block_starts [B] i32, DEVICE memory.  The positions are not validated (they live on the device): rows of a
+ *   block that would fall outside [0, N) simply replace nothing; no access leaves the tensors for any value.
+ *   Kblk and Vblk are required (without them the block position plays no role: use dd_block_attention_cached).
+ * Everything else as for dd_block_attention_cached; workspace from dd_block_attention_batched_workspace_bytes.
+ */
+int dd_block_attention_batched(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                               const int32_t *block_starts, int block_len,
+                               const void *Kblk, const void *Vblk,
+                               int B, int H, int Hkv, int N, int d,
+                               dd_dtype qk_dtype, dd_dtype v_dtype,
+                               const float *q_scale, const float *k_scale,
+                               void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_block_attention_batched_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
+
+/*
  * Token-granular cache update.  The cached drafters of Sec. 2.3 differ in when a position's key/value enter
  * the cache (block-wise schemes: when the block is complete; dKV-Cache: one step after the token was decoded);
  * the operation on the cache is the same: rows the drafter computed replace the cache rows of chosen positions:

@@ -177,6 +177,28 @@ def block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, win_l
     return block_attention_cached(Qblk, Kw, Vw, block_start - win_start, qk_dtype, v_dtype, Kblk, Vblk, q_scale, k_scale, rows)
 
 
+def block_attention_batched(Qblk, Kc, Vc, block_starts, qk_dtype: int, v_dtype: int, Kblk, Vblk,
+                            q_scale=None, k_scale=None) -> np.ndarray:
+    """Drafter attention with one block position per batch entry: by definition the cached call on each batch
+    entry alone, at its own position.  Rows of a block that fall outside [0, N) replace nothing."""
+    B, H, bl, d = Qblk.shape
+    N = Kc.shape[2]
+    Hkv = Kc.shape[1]
+    out = np.empty((B, H, bl, d), dtype=np.float64)
+    qs = None if q_scale is None else np.asarray(q_scale, dtype=np.float32).reshape(B, H)
+    ks = None if k_scale is None else np.asarray(k_scale, dtype=np.float32).reshape(B, Hkv)
+    for b in range(B):
+        s0 = int(block_starts[b])
+        Kn, Vn = np.array(Kc[b:b + 1], copy=True), np.array(Vc[b:b + 1], copy=True)
+        for r in range(bl):                                   # splice the block's rows that lie inside the sequence
+            if 0 <= s0 + r < N:
+                Kn[0, :, s0 + r, :] = Kblk[b, :, r, :]
+                Vn[0, :, s0 + r, :] = Vblk[b, :, r, :]
+        out[b] = block_attention_cached(Qblk[b:b + 1], Kn, Vn, 0, qk_dtype, v_dtype, None, None,
+                                        None if qs is None else qs[b:b + 1], None if ks is None else ks[b:b + 1])[0]
+    return out
+
+
 def cache_insert_rows(Kc, Vc, Krows, Vrows, positions):
     """Token-granular cache update (Sec. 2.3, delayed insertion): row r of Krows/Vrows [B,Hkv,n,d] replaces cache
     row positions[b][r] of every kv head of batch b; entries outside [0, N) are skipped.  Plain loops; returns new

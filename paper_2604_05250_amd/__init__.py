@@ -68,6 +68,10 @@ def lib():
     L.dd_block_attention_window.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
     L.dd_block_attention_window_workspace_bytes.restype = sz
     L.dd_block_attention_window_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i, i]
+    L.dd_block_attention_batched.restype = i
+    L.dd_block_attention_batched.argtypes = [vp, vp, vp, vp, vp, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
+    L.dd_block_attention_batched_workspace_bytes.restype = sz
+    L.dd_block_attention_batched_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.dd_cache_insert_rows.restype = i
     L.dd_cache_insert_rows.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, i, i, vp]
     L.dd_verify_scores.restype = i
@@ -83,7 +87,8 @@ EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attentio
            "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
            "dd_verify_scores", "dd_verify_scores_workspace_bytes",
            "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
-           "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows")
+           "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows",
+           "dd_block_attention_batched", "dd_block_attention_batched_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -236,6 +241,32 @@ def dd_block_attention_window(Qblk, Kc, Vc, block_start: int, win_start: int, wi
                                          _dev(ws, "workspace"), wsn, _stream())
     if rc != 0:
         raise DDError(rc, "dd_block_attention_window")
+    return O
+
+
+def dd_block_attention_batched(Qblk, Kc, Vc, block_starts, Kblk, Vblk, O=None, q_scale=None, k_scale=None,
+                               qk_dtype: Optional[int] = None, v_dtype: Optional[int] = None):
+    """Drafter attention with one block position per batch entry: block_starts [B] i32 on the device."""
+    torch = _torch()
+    B, H, bl, d = Qblk.shape
+    _, Hkv, N, _ = Kc.shape
+    if tuple(Kc.shape) != (B, Hkv, N, d) or tuple(Vc.shape) != (B, Hkv, N, d):
+        raise ValueError("Kc/Vc shape must be [B,Hkv,N,d]")
+    if tuple(Kblk.shape) != (B, Hkv, bl, d) or tuple(Vblk.shape) != (B, Hkv, bl, d):
+        raise ValueError("Kblk/Vblk shape must be [B,Hkv,block_len,d]")
+    if block_starts.dtype != torch.int32 or block_starts.numel() != B:
+        raise ValueError("block_starts must be int32 with B entries")
+    qk = _dtype_tag(Qblk, "Qblk") if qk_dtype is None else qk_dtype
+    vd = _dtype_tag(Vc, "Vc") if v_dtype is None else v_dtype
+    if O is None:
+        O = torch.empty((B, H, bl, d), dtype=Vc.dtype, device=Vc.device)
+    ws, wsn = _workspace(lib().dd_block_attention_batched_workspace_bytes(bl, B, H, Hkv, N, d, qk, vd), Qblk.device)
+    rc = lib().dd_block_attention_batched(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
+                                          _dev(block_starts, "block_starts"), bl, _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"),
+                                          B, H, Hkv, N, d, qk, vd, _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
+                                          _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_block_attention_batched")
     return O
 
 

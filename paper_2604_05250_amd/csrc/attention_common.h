@@ -25,6 +25,7 @@ struct AttnKernelArgs {
     int splits;                // key-range splits
     int keys_per_split;        // multiple of the key tile
     int block_start, block_len;
+    const int32_t *block_starts;   // [B] or nullptr: the block's first row per batch entry (overrides block_start)
     float scale_log2;          // log2(e) / sqrt(d)
 };
 

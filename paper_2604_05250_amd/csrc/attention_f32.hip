@@ -58,6 +58,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_f32_kernel(const AttnKernel
     const int k_begin = sp * a.keys_per_split;
     const int k_end = min(a.N, k_begin + a.keys_per_split);
     const size_t kv_head = (size_t)b * a.Hkv + kvh;
+    const int bstart = a.block_starts ? a.block_starts[b] : a.block_start;   // any value is safe: rows are chosen by range test
     float m_run = -INFINITY, l_run = 0.f;
 
     for (int k0 = k_begin; k0 < k_end; k0 += TKF) {
@@ -67,8 +68,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_f32_kernel(const AttnKernel
             const int j = k0 + row;
             float4 kw = make_float4(0.f, 0.f, 0.f, 0.f), vw = kw;
             if (j < k_end) {
-                const bool in_blk = a.Kblk != nullptr && j >= a.block_start && j < a.block_start + a.block_len;
-                const size_t off = in_blk ? (kv_head * a.block_len + (size_t)(j - a.block_start)) * D
+                const bool in_blk = a.Kblk != nullptr && (unsigned)j - (unsigned)bstart < (unsigned)a.block_len;
+                const size_t off = in_blk ? (kv_head * a.block_len + (size_t)(j - bstart)) * D
                                           : (kv_head * a.kv_stride + (size_t)j) * D;
                 const float *kp = static_cast<const float *>(in_blk ? a.Kblk : a.K) + off;
                 const float *vp = static_cast<const float *>(in_blk ? a.Vblk : a.V) + off;

@@ -146,6 +146,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     const int k_end = min(a.N, k_begin + a.keys_per_split);
     const int ntiles = (k_end - k_begin + TK - 1) / TK;
     const size_t kv_head = (size_t)b * a.Hkv + kvh;
+    const int bstart = a.block_starts ? a.block_starts[b] : a.block_start;   // any value is safe: rows are chosen by range test
 
     // ---- staging: global -> registers -> LDS
     uint4 kreg[KCH];
@@ -161,16 +162,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // valid row (their scores are masked to -inf, their values multiply a zero probability)
     auto k_src = [&](int j) -> const uint8_t * {
         j = min(j, k_end - 1);
-        if (BLOCK && j >= a.block_start && j < a.block_start + a.block_len)
+        if (BLOCK && (unsigned)j - (unsigned)bstart < (unsigned)a.block_len)
             return static_cast<const uint8_t *>(a.Kblk) +
-                   (kv_head * a.block_len + (size_t)(j - a.block_start)) * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
+                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
         return k_base + (size_t)j * (D * KELEM);
     };
     auto v_src = [&](int j) -> const uint8_t * {
         j = min(j, k_end - 1);
-        if (BLOCK && j >= a.block_start && j < a.block_start + a.block_len)
+        if (BLOCK && (unsigned)j - (unsigned)bstart < (unsigned)a.block_len)
             return static_cast<const uint8_t *>(a.Vblk) +
-                   (kv_head * a.block_len + (size_t)(j - a.block_start)) * (size_t)(D * 2) + vt_dchunk * 16;
+                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)(D * 2) + vt_dchunk * 16;
         return v_base + (size_t)j * (D * 2);
     };
     // K is staged in windows of 64 keys that are offset by half a tile against the V tiles:
@@ -551,6 +552,7 @@ void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int
     // drop trailing splits that would be empty after rounding the split length up to whole tiles
     k.splits = (a.N + per - 1) / per;
     k.block_start = a.block_start; k.block_len = a.block_len;
+    k.block_starts = a.block_starts;
     k.scale_log2 = 1.44269504088896340736f / sqrtf((float)a.d);
     const size_t rows = (size_t)a.B * a.H * a.Nq;
     k.part_o = static_cast<float *>(a.workspace);

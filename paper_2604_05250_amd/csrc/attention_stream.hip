@@ -99,6 +99,7 @@ void attn_stream_kernel(const AttnKernelArgs a)
     const size_t row_base = ((size_t)b * a.H + (size_t)kvh * a.group) * a.Nq;
     const int kbeg = sp * a.keys_per_split;
     const int kend = min(a.N, kbeg + a.keys_per_split);
+    const int bstart = a.block_starts ? a.block_starts[b] : a.block_start;   // any value is safe: rows are chosen by range test
     const int ntiles = (kend - kbeg + TKS - 1) / TKS;
 
     // ---- staging by LDS DMA: load i of this wave moves rows (4i + wave) * DMA_ROWS .. of a tile; lane l
@@ -119,8 +120,8 @@ void attn_stream_kernel(const AttnKernelArgs a)
         for (int i = 0; i < NDMA; ++i) {
             const int r0 = (i * 4 + wave) * DMA_ROWS;
             const int j = min(kbeg + tile * TKS + i * 4 * DMA_ROWS + dma_row0, kend - 1);
-            const bool in_blk = (unsigned)(j - a.block_start) < (unsigned)a.block_len;
-            const size_t roff = (size_t)(in_blk ? j - a.block_start : j) * ROWB;
+            const bool in_blk = (unsigned)j - (unsigned)bstart < (unsigned)a.block_len;
+            const size_t roff = (size_t)(in_blk ? j - bstart : j) * ROWB;
             const uint8_t *ks = (in_blk ? kb_ : kc) + roff + dma_koff;
             const uint8_t *vs = (in_blk ? vb_ : vc) + roff + dma_voff;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)ks,

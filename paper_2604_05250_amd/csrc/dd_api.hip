@@ -139,7 +139,7 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
                            int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
                            const float *q_scale, const float *k_scale,
                            void *workspace, size_t workspace_bytes, void *stream, bool refresh,
-                           int win_start = 0, int win_len = 0)
+                           int win_start = 0, int win_len = 0, const int32_t *block_starts = nullptr)
 {
     if (!Qblk || !Kc || !Vc || !O) return DD_ERR_NULL;
     if ((Kblk == nullptr) != (Vblk == nullptr)) return DD_ERR_NULL;
@@ -171,13 +171,15 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
     a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
     a.workspace = workspace;
     a.kv_stride = full_N;
+    a.block_starts = block_starts;
     if (refresh) {
         a.K_refresh = const_cast<void *>(Kc);
         a.V_refresh = const_cast<void *>(Vc);
     }
     // DD_TUNE_BLOCK_WIDE=0 keeps calls with many rows per kv head off the wide kernel (read per call: tests switch it)
     const char *wenv = getenv("DD_TUNE_BLOCK_WIDE");
-    const bool wide = !(wenv && wenv[0] == '0') && dd::attn_wide_block_fits(a);
+    // (the wide kernel plans its tile list on the host from one block position: not for per-sequence positions)
+    const bool wide = !(wenv && wenv[0] == '0') && block_starts == nullptr && dd::attn_wide_block_fits(a);
     const int splits = wide ? dd::attn_wide_block_splits(block_len, B, H, Hkv, N)
                             : dd::attn_block_splits(block_len, B, H, Hkv, N, d);
     rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));
@@ -216,6 +218,24 @@ int dd_block_attention_refresh(const void *Qblk, void *Kc, void *Vc, void *O,
 {
     return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
                            q_scale, k_scale, workspace, workspace_bytes, stream, true);
+}
+
+size_t dd_block_attention_batched_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,
+                                                  dd_dtype qk_dtype, dd_dtype v_dtype)
+{
+    return dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, qk_dtype, v_dtype);
+}
+
+int dd_block_attention_batched(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                               const int32_t *block_starts, int block_len, const void *Kblk, const void *Vblk,
+                               int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
+                               const float *q_scale, const float *k_scale,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!block_starts || !Kblk || !Vblk) return DD_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(block_starts) & 3u) != 0) return DD_ERR_ALIGN;
+    return block_attention(Qblk, Kc, Vc, O, 0, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
+                           q_scale, k_scale, workspace, workspace_bytes, stream, false, 0, 0, block_starts);
 }
 
 size_t dd_block_attention_window_workspace_bytes(int block_len, int win_len, int B, int H, int Hkv, int N, int d,

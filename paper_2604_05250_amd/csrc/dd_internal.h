@@ -65,6 +65,8 @@ struct AttnArgs {
     int kv_stride = 0;       // rows between consecutive (batch, kv head) of K and V; 0 = N (dense).  A call on a
                              // window of the cache passes K/V at the window's first row, N = the window length
     int block_start, block_len;
+    const int32_t *block_starts = nullptr;   // device [B] or nullptr: the block's first row per batch entry
+                                             // (overrides block_start; not served by the wide kernel)
     int qk_dtype, v_dtype;   // dd_dtype values
     int splits;              // key-range splits (1 = write O directly)
     void *workspace;         // partial states when splits > 1

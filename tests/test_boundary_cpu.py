@@ -70,6 +70,15 @@ def test_attention_argument_validation():
     assert refresh(bs=0, bl=64, **big) == -5               # same workspace rule as the plain call
     assert L.dd_block_attention_refresh_workspace_bytes(64, 1, 32, 32, 4096, 128, dd.BF16, dd.BF16) == need
 
+    def batched(starts=FAKE, Kblk=FAKE, Vblk=FAKE, bl=16, **kw):
+        a = dict(ok_args); a.update(kw)
+        return L.dd_block_attention_batched(FAKE, FAKE, FAKE, FAKE, starts, bl, Kblk, Vblk, a["B"], a["H"], a["Hkv"],
+                                            a["N"], a["d"], a["qk"], a["v"], None, None, None, 0, None)
+    assert batched(starts=None) == -1 and batched(Kblk=None, Vblk=None) == -1 and batched(starts=FAKE + 2) == -6
+    assert batched(bl=0) == -2 and batched(bl=65) == -2
+    assert batched(bl=64, **big) == -5
+    assert L.dd_block_attention_batched_workspace_bytes(64, 1, 32, 32, 4096, 128, dd.BF16, dd.BF16) == need
+
     def window(bs=16, bl=16, w0=0, wl=64, **kw):
         a = dict(ok_args); a.update(kw)
         return L.dd_block_attention_window(FAKE, FAKE, FAKE, FAKE, bs, bl, w0, wl, None, None, a["B"], a["H"], a["Hkv"],

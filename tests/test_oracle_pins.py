@@ -586,6 +586,39 @@ def test_block_window_semantics():
             oracle.block_attention_window(Qb, K, V, bs, bad[0], bad[1], F32, F32)
 
 
+def test_block_attention_batched_semantics():
+    # one block position per batch entry: every entry is the cached call at its own position
+    rng = np.random.default_rng(13)
+    B, H, Hkv, N, d, bl = 3, 4, 2, 29, 8, 6
+    Q, K, V = _rand_qkv(rng, B, H, Hkv, N, d)
+    Qb = rng.standard_normal((B, H, bl, d)).astype(np.float32)
+    Kb = rng.standard_normal((B, Hkv, bl, d)).astype(np.float32); Vb = rng.standard_normal((B, Hkv, bl, d)).astype(np.float32)
+    starts = np.array([0, 11, N - bl], np.int32)
+    O = oracle.block_attention_batched(Qb, K, V, starts, F32, F32, Kb, Vb)
+    for b in range(B):
+        ref = oracle.block_attention_cached(Qb[b:b + 1], K[b:b + 1], V[b:b + 1], int(starts[b]), F32, F32,
+                                            Kblk=Kb[b:b + 1], Vblk=Vb[b:b + 1])
+        assert np.array_equal(O[b], ref[0])
+    # equal positions: the plain call on the whole batch
+    same = np.full(B, 7, np.int32)
+    assert np.array_equal(oracle.block_attention_batched(Qb, K, V, same, F32, F32, Kb, Vb),
+                          oracle.block_attention_cached(Qb, K, V, 7, F32, F32, Kblk=Kb, Vblk=Vb))
+    # library formulation for one entry: splice, then einsum + softmax (MHA view of the GQA heads)
+    b = 1
+    Ks, Vs = K[b].copy(), V[b].copy()
+    Ks[:, 11:11 + bl] = Kb[b]; Vs[:, 11:11 + bl] = Vb[b]
+    rep = H // Hkv
+    ref = _numpy_attention(Qb[b:b + 1], np.repeat(Ks, rep, axis=0)[None], np.repeat(Vs, rep, axis=0)[None])
+    assert np.allclose(O[b], ref[0], rtol=1e-12, atol=1e-14)
+    # a block that hangs over either end of the sequence replaces only the rows inside; far outside: nothing
+    edge = np.array([-2, N - 3, 1000], np.int32)
+    Oe = oracle.block_attention_batched(Qb, K, V, edge, F32, F32, Kb, Vb)
+    K0, V0 = K[0:1].copy(), V[0:1].copy()
+    K0[0, :, 0:bl - 2] = Kb[0, :, 2:]; V0[0, :, 0:bl - 2] = Vb[0, :, 2:]
+    assert np.array_equal(Oe[0], oracle.block_attention_cached(Qb[0:1], K0, V0, 0, F32, F32)[0])
+    assert np.array_equal(Oe[2], oracle.block_attention_cached(Qb[2:3], K[2:3], V[2:3], 0, F32, F32)[0])
+
+
 def test_cache_insert_rows_semantics():
     rng = np.random.default_rng(12)
     B, Hkv, N, d, n = 3, 2, 21, 8, 5
