@@ -130,8 +130,8 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
- * The same call when the block is complete (Sec. 2.3: the cache is refreshed at block granularity; cached
- * activations are reused "with periodic refreshes" after a block's denoising steps): the attention exactly as
+ * The same call when the block is complete (Sec. 2.3: cached activations are reused across the denoising
+ * steps of a block and refreshed at block granularity): the attention exactly as
  * dd_block_attention_cached computes it with Kblk/Vblk given, and in the same call
  *     Kc[b,g,block_start+r,:] <- Kblk[b,g,r,:],   Vc[b,g,block_start+r,:] <- Vblk[b,g,r,:]      0 <= r < block_len
  * (a copy of the stored bytes: with DD_FP8_E4M3 the block's K already uses the cache's k_scale).  Afterwards a
@@ -234,7 +234,10 @@ int dd_cache_insert_rows(void *Kc, void *Vc, const void *Krows, const void *Vrow
  *   logits_d [P,V] logit_dtype  drafter logits; read only in the KL modes (may be NULL otherwise)
  *   logits_v [P,V] logit_dtype  verifier logits
  *   mask     [P] u8             1 = position still holds [MASK], 0 = decoded
- *   out_mask   [P] u8   = mask[i] | remask_i
+ *   out_mask   [P] u8   = mask[i] | remask_i.  out_mask == mask (update in place) is allowed in DD_TRUST, the
+ *                         two threshold modes and DD_CONF_PROB, whose decision for row i reads mask[i] only; in
+ *                         DD_KL_PROB and the budgeted modes, which read the whole sequence's mask, and for ranges
+ *                         that overlap without being identical, the call returns DD_ERR_SHAPE
  *   out_tokens [P] i32  = t_V,i            (every row, eligible or not, every mode)
  *   out_scores [P] f32  = score_i          (every row)
  * logit_dtype in {DD_F32, DD_BF16}; V >= 1 with V * sizeof(element) a multiple of 16;
@@ -257,7 +260,7 @@ typedef enum {
 
 /*
  * One drafter unmasking step, x <- Unmask(p_D, x) (Alg. 1, drafting phase): the model's probabilities at the
- * masked positions decide which of them are revealed (Sec. 2.1: "a subset of high-confidence tokens");
+ * masked positions decide which of them are revealed (Sec. 2.1: the most confident ones);
  * the two selection rules are the ones Sec. 2.3 names: all tokens above a confidence threshold
  * (confidence-aware parallel decoding) or a fixed number per step.  For P = B*G positions, softmax at
  * temperature 1 over the whole vocabulary:
@@ -277,7 +280,8 @@ typedef enum {
  *   out_mask   [P] u8   = mask[i] and not select_i
  *   out_tokens [P] i32  = t_D,i     (every row)
  *   out_conf   [P] f32  = c_D,i     (every row)
- * Same shape rules, workspace and single-pass property as dd_verify_remask; out_mask must not alias mask.
+ * Same shape rules, workspace and single-pass property as dd_verify_remask; out_mask must not overlap mask
+ * (DD_ERR_SHAPE).
  */
 int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, float threshold,
               int32_t *x_tokens, uint8_t *out_mask, int32_t *out_tokens, float *out_conf,

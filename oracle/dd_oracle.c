@@ -8,8 +8,8 @@
  *
  *   attention            softmax(Q K^T / sqrt(d_k)) V, the form of Eq. 3 (Sec. 2.2),
  *                        taken over ALL positions because the verifier's attention
- *                        is bidirectional (Sec. 2.2, "every token can attend to all
- *                        positions"); Alg. 1's verification line needs it at every
+ *                        is bidirectional (Sec. 2.2: no position is hidden from any
+ *                        other); Alg. 1's verification line needs it at every
  *                        position.
  *   block attention      the same formula for the active block's queries only, with
  *                        keys/values of the other positions read from a (possibly

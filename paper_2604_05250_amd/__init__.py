@@ -135,12 +135,65 @@ def _workspace(nbytes: int, device):
     stream run in order and may share it; calls on different streams may overlap and must not."""
     if nbytes == 0:
         return None, 0
+    global _ws_peak
+    torch = _torch()
+    _ws_peak = max(_ws_peak, nbytes)
+    if _ws_fixed is not None:
+        if _ws_fixed.numel() < nbytes or _ws_fixed.device != device:
+            raise RuntimeError(f"the fixed workspace holds {_ws_fixed.numel()} bytes on {_ws_fixed.device}; "
+                               f"this call needs {nbytes} on {device}")
+        return _ws_fixed, _ws_fixed.numel()
+    if torch.cuda.is_current_stream_capturing():
+        # memory allocated under capture would come from that graph's private pool and a cached tensor of it
+        # could be handed to a later, unrelated call: the scratch memory of captured calls is allocated beforehand
+        raise RuntimeError("a call that needs scratch memory is being captured without a fixed workspace: "
+                           "capture through paper_2604_05250_amd.step.capture_step, or inside fixed_workspace()")
     key = (device, _stream())
     cur = _ws_cache.get(key)
     if cur is None or cur.numel() < nbytes:
-        cur = _torch().empty(max(nbytes, 1 << 20), dtype=_torch().uint8, device=device)
+        cur = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=device)
         _ws_cache[key] = cur
     return cur, cur.numel()
+
+
+_ws_fixed = None      # set by fixed_workspace(): every call inside uses this tensor
+_ws_peak = 0          # largest scratch size any call has asked for since reset_workspace_peak()
+
+
+def reset_workspace_peak() -> None:
+    global _ws_peak
+    _ws_peak = 0
+
+
+def workspace_peak() -> int:
+    return _ws_peak
+
+
+class fixed_workspace:
+    """Context manager: calls of the binding inside it use `tensor` (uint8, on the GPU) as their scratch memory
+    instead of the per-stream cached one; they must all be ordered on one stream.  For graph capture: the
+    tensor is allocated before the capture and kept alive by whoever keeps the graph."""
+
+    def __init__(self, tensor):
+        self.tensor = tensor
+
+    def __enter__(self):
+        global _ws_fixed
+        self.prev, _ws_fixed = _ws_fixed, self.tensor
+        return self.tensor
+
+    def __exit__(self, *exc):
+        global _ws_fixed
+        _ws_fixed = self.prev
+        return False
+
+
+def _check_vec(t, n, dtype, what):
+    """A per-position vector handed to the library: n elements of the given torch dtype (or None)."""
+    if t is None:
+        return
+    if t.dtype != dtype or t.numel() != n:
+        raise ValueError(f"{what}: must have {n} elements of {dtype}, has {t.numel()} of {t.dtype}")
 
 
 # ---------------------------------------------------------------- entry points
@@ -304,6 +357,10 @@ def dd_verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed
         raise ValueError("logits_d shape must match logits_v")
     dt = _dtype_tag(logits_v, "logits_v") if logit_dtype is None else logit_dtype
     dev = logits_v.device
+    _check_vec(mask, P, torch.uint8, "mask")
+    _check_vec(out_mask, P, torch.uint8, "out_mask")
+    _check_vec(out_tokens, P, torch.int32, "out_tokens")
+    _check_vec(out_scores, P, torch.float32, "out_scores")
     if out_mask is None:
         out_mask = torch.empty(P, dtype=torch.uint8, device=dev)
     if out_tokens is None:
@@ -334,6 +391,11 @@ def dd_unmask(logits_d, mask, mode: int, threshold: float, B: int, G: int, x_tok
         raise ValueError("logits_d must have B*G rows")
     dt = _dtype_tag(logits_d, "logits_d") if logit_dtype is None else logit_dtype
     dev = logits_d.device
+    _check_vec(mask, P, torch.uint8, "mask")
+    _check_vec(x_tokens, P, torch.int32, "x_tokens")
+    _check_vec(out_mask, P, torch.uint8, "out_mask")
+    _check_vec(out_tokens, P, torch.int32, "out_tokens")
+    _check_vec(out_conf, P, torch.float32, "out_conf")
     if out_mask is None:
         out_mask = torch.empty(P, dtype=torch.uint8, device=dev)
     if out_tokens is None:

@@ -40,23 +40,5 @@ def build_library(force: bool = True, verbose: bool = False, extra_flags=()) -> 
     return LIB
 
 
-PROBE_SRC = os.path.join(CSRC, "probes", "mfma_rate.hip")
-PROBE_BIN = os.path.join(CSRC, "probes", "mfma_rate")
-
-
-def build_probe(verbose: bool = False) -> str:
-    """Compile the stand-alone MFMA-rate calibration program (not part of the library)."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           PROBE_SRC, "-o", PROBE_BIN]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return PROBE_BIN
-
-
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True, extra_flags=sys.argv[1:]))
-    print(build_probe(verbose=True))

@@ -572,23 +572,19 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     if (!blk && (!fp8 || a.d == 128)) {
         // The wide-wave kernel (256 query rows per workgroup, one wave per SIMD; bf16, or fp8 Q/K with
         // d = 128) wins once there are enough row tiles to occupy the chip; below that smaller workgroups
-        // spread better.  DD_TUNE_ATTN_WIDE=0/1 forces the choice (read per call so that tests can switch it).
+        // spread better.
         const long tiles = (long)a.B * a.Hkv * (((long)(a.H / a.Hkv) * a.Nq + 255) / 256);
-        bool wide = tiles >= 192 && a.N >= 512;
-        if (const char *e = getenv("DD_TUNE_ATTN_WIDE")) wide = e[0] == '1';
+        const bool wide = tune("DD_TUNE_ATTN_WIDE", tiles >= 192 && a.N >= 512) != 0;
         if (wide && a.N >= 64) return launch_attention_wide(a, stream);   // its K/V tiles are 64 whole rows
         // A small bf16 call leaves most compute units idle with 128-row workgroups: the streaming kernel's
         // 64-row workgroups (two row blocks x two key phases) spread it over more of them.
-        // DD_TUNE_BIDIR_STREAM=0/1 forces the choice.
-        bool small = blocks < 256;
-        if (const char *e = getenv("DD_TUNE_BIDIR_STREAM")) small = e[0] == '1';
+        const bool small = tune("DD_TUNE_BIDIR_STREAM", blocks < 256) != 0;
         if (small && !fp8) return launch_attention_stream(a, stream);
     }
     if (blk && !fp8 && a.Nq != a.N && attn_stream_fits(a)) {
         // The drafter's call is bound by streaming K/V once: a kernel built around the memory pipeline
-        // serves it (DD_TUNE_BLOCK_STREAM=0 keeps it on this file's kernel).
-        const char *env = getenv("DD_TUNE_BLOCK_STREAM");
-        if (!(env && env[0] == '0')) return launch_attention_stream(a, stream);
+        // serves it.
+        if (tune("DD_TUNE_BLOCK_STREAM", 1) != 0) return launch_attention_stream(a, stream);
     }
     if (!blk) {
         if (a.d == 128) e = fp8 ? launch(attn_mfma_kernel<128, true, false>, grid, block, stream, k)

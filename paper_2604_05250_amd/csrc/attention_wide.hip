@@ -48,7 +48,6 @@
 #include "attention_common.h"
 #include "dd_internal.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace dd {
@@ -66,10 +65,7 @@ constexpr int TKW = 64;                 // keys per tile
 constexpr int QB = 2;                   // 32-row query blocks per wave
 constexpr int kRowsWave = 32 * QB;
 constexpr int kRowsWGWide = 4 * kRowsWave;
-#ifndef DDW_PACK_LAG
-#define DDW_PACK_LAG 2
-#endif
-constexpr int kPackLag = DDW_PACK_LAG;   // pieces between an exponential and its conversion to bf16
+constexpr int kPackLag = 2;              // pieces between an exponential and its conversion to bf16
 constexpr float kSlack = 8.0f;          // the maximum in use is raised when exceeded by 2^8
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -184,9 +180,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-#ifdef DDW_TIMING2
-    const unsigned long long t_kernel = __builtin_readcyclecounter();
-#endif
     const int l32 = lane & 31, hh = lane >> 5;
 
     // ---- this workgroup's row tiles.  Tile t = ((b * Hkv + kvh) * row_tiles + rt); workgroup w takes tiles
@@ -520,9 +513,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
     };
 
-#ifdef DDW_TIMING2
-    unsigned long long tfine[4] = {0, 0, 0, 0};      // waiting for Q, installing Q, writing out, the last barrier
-#endif
     intx4 kfr[RD];
     bf16x8 vfr[RD];
     // Pipeline step.  In: s_cur = S(u), pk_prev = P(u-1).  Out: pk_cur = P(u), s_nxt = S(u+1).
@@ -664,14 +654,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         for (int pr = 0; pr < 16; ++pr)
             if (exp_piece(2 * pr + 1) >= NP - kPackLag) pack_pair(pr);
         if (CANFIN && fin) {                                 // uniform: the row tile is complete
-#ifdef DDW_TIMING2
-            const unsigned long long ta = __builtin_readcyclecounter();
-#endif
             write_out(cur);
             clear_acc_mfma();
-#ifdef DDW_TIMING2
-            tfine[2] += __builtin_readcyclecounter() - ta;
-#endif
         } else if (__builtin_expect(changed, 0)) {           // rare: everything accumulated so far changes units
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
@@ -707,17 +691,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         constexpr bool last = KIND == 2;
         if (!BLOCK && last && has_next) {
             // the Q rows were requested a stage ago and deliberately not waited for at its barrier
-#ifdef DDW_TIMING2
-            const unsigned long long ta = __builtin_readcyclecounter();
-#endif
             __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-#ifdef DDW_TIMING2
-            const unsigned long long tb = __builtin_readcyclecounter();
-#endif
             install_q(nxt);
-#ifdef DDW_TIMING2
-            tfine[0] += tb - ta; tfine[1] += __builtin_readcyclecounter() - tb;
-#endif
         }
         const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
@@ -740,13 +715,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         constexpr int NST = kRowsWave / (64 / (ROWB / 16));  // output stores per wave
         if (!BLOCK && KIND == 1 && has_next) wait_loads_and_sync(I_<NQDMA>{});
         else if (last && cur.v0 + kRowsWGWide <= rows_total) {
-#ifdef DDW_TIMING2
-            const unsigned long long ta = __builtin_readcyclecounter();
-#endif
             wait_loads_and_sync(I_<NST>{});
-#ifdef DDW_TIMING2
-            tfine[3] += __builtin_readcyclecounter() - ta;
-#endif
         }
         else wait_loads_and_sync(I_<0>{});
     };
@@ -779,17 +748,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // ---- passes: stages 0 .. nt_even-1 = steps 1 .. 2 nt_even; the product with P(u) happens in step u+1,
     // so this covers every unit, and the surplus steps work for the next row tile (or on masked stand-ins)
-#ifdef DDW_TIMING2
-    unsigned long long tacc[3] = {0, 0, 0};
-    const unsigned long long t_loop = __builtin_readcyclecounter();
-#endif
     for (;;) {
         has_next = !BLOCK && t_cur + t_stride < tiles_total;
         if (!BLOCK && has_next) nxt = tile_of(t_cur + t_stride);
         int sp = 0;
-#ifdef DDW_TIMING2
-        const unsigned long long t0 = __builtin_readcyclecounter();
-#endif
         // stages sp <= nt_even - 4 only touch units of tiles <= nt_even - 3 <= nt_local - 2: never the last
         // tile of the key range, the only one of the verifier's pass that can overlap its predecessor
         for (; sp + 4 < nt_even; sp += 2) {
@@ -800,31 +762,12 @@ void attn_wide_kernel(const AttnKernelArgs a)
             stage(sp, I_<0>{}, I_<0>{}, T_{});
             stage(sp + 1, I_<1>{}, I_<0>{}, T_{});
         }
-#ifdef DDW_TIMING2
-        const unsigned long long t1 = __builtin_readcyclecounter();
-#endif
         stage(sp, I_<0>{}, I_<1>{}, T_{});
-#ifdef DDW_TIMING2
-        const unsigned long long t2 = __builtin_readcyclecounter();
-#endif
         stage(sp + 1, I_<1>{}, I_<2>{}, T_{});
-#ifdef DDW_TIMING2
-        const unsigned long long t3 = __builtin_readcyclecounter();
-        tacc[0] += t1 - t0; tacc[1] += t2 - t1; tacc[2] += t3 - t2;
-#endif
         if (BLOCK || !has_next) break;
         cur = nxt;
         t_cur += t_stride;
     }
-#ifdef DDW_TIMING2
-    if (tid == 0) {
-        unsigned long long *dbg = reinterpret_cast<unsigned long long *>(const_cast<float *>(a.q_scale)) + blockIdx.x * 8;
-        dbg[0] = tacc[0]; dbg[1] = tacc[1]; dbg[2] = tacc[2];
-        dbg[3] = __builtin_readcyclecounter() - t_loop; dbg[4] = t_loop - t_kernel;
-        unsigned long long *fine = reinterpret_cast<unsigned long long *>(const_cast<float *>(a.q_scale)) + 256 * 8 + blockIdx.x * 4;
-        for (int i = 0; i < 4; ++i) fine[i] = tfine[i];
-    }
-#endif
 }
 
 }  // namespace
@@ -843,10 +786,8 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
     }
     const long tiles = (long)a.B * a.Hkv * k.row_tiles;
     long wgs = tiles < cus ? tiles : cus;                  // one persistent workgroup per compute unit
-    if (const char *e = getenv("DD_TUNE_ATTN_WIDE_GRID")) {
-        const long v = atol(e);
-        if (v >= 1 && v < wgs) wgs = v;
-    }
+    const long cap = tune("DD_TUNE_ATTN_WIDE_GRID", 0);
+    if (cap >= 1 && cap < wgs) wgs = cap;
     const dim3 grid((unsigned)wgs), block(kAttnThreads);
     if (a.qk_dtype == 2) {
         if (a.d != 128) return hipErrorInvalidValue;      // 64-byte fp8 rows are not worth a variant

@@ -35,20 +35,20 @@ int check_workspace(const void *ws, size_t have, size_t need)
 
 namespace dd {
 
-static int env_or(const char *name, int dflt)
+int tune(const char *name, int dflt)
 {
+    static const bool hooks = [] { const char *e = getenv("DD_TUNE"); return e && e[0] == '1'; }();
+    if (!hooks) return dflt;
     const char *e = getenv(name);
     return e && *e ? atoi(e) : dflt;
 }
 
 // Query rows per workgroup of the drafter's MFMA kernel.  Smaller row tiles (64, 32: more workgroups that
-// stream the same K/V side by side) were measured and lose on every benchmark shape, so 128 it is;
-// DD_TUNE_BLOCK_ROWS keeps the experiment repeatable.
+// stream the same K/V side by side) were measured and lose on every benchmark shape.
 int attn_block_rows_per_wg(int block_len, int B, int H, int Hkv)
 {
     (void)block_len; (void)B; (void)H; (void)Hkv;
-    static const int forced = env_or("DD_TUNE_BLOCK_ROWS", 0);
-    return (forced == 32 || forced == 64) ? forced : 128;
+    return 128;
 }
 
 int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
@@ -59,7 +59,7 @@ int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
     const long base = (long)B * Hkv * ((group * block_len + r - 1) / r);
     // Every extra split adds partial-state traffic and merge work, so the key range is only split until
     // there is about one workgroup per compute unit.
-    static const int target = env_or("DD_TUNE_BLOCK_TARGET_WGS", 256);
+    const int target = 256;
     long s = (target + base - 1) / base;
     const long max_s = N / 128 > 1 ? N / 128 : 1;   // at least 128 keys per split
     if (s > max_s) s = max_s;
@@ -176,10 +176,8 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
         a.K_refresh = const_cast<void *>(Kc);
         a.V_refresh = const_cast<void *>(Vc);
     }
-    // DD_TUNE_BLOCK_WIDE=0 keeps calls with many rows per kv head off the wide kernel (read per call: tests switch it)
-    const char *wenv = getenv("DD_TUNE_BLOCK_WIDE");
     // (the wide kernel plans its tile list on the host from one block position: not for per-sequence positions)
-    const bool wide = !(wenv && wenv[0] == '0') && block_starts == nullptr && dd::attn_wide_block_fits(a);
+    const bool wide = dd::tune("DD_TUNE_BLOCK_WIDE", 1) != 0 && block_starts == nullptr && dd::attn_wide_block_fits(a);
     const int splits = wide ? dd::attn_wide_block_splits(block_len, B, H, Hkv, N)
                             : dd::attn_block_splits(block_len, B, H, Hkv, N, d);
     rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));
@@ -299,6 +297,16 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
     const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB || mode == DD_KL_TOPK);
     if (!logits_v || !mask || !out_mask || !out_tokens || !out_scores) return DD_ERR_NULL;
     if (kl && !logits_d) return DD_ERR_NULL;
+    {
+        // The per-row rules read mask[i] and write out_mask[i] in one lane, so updating the mask in place is
+        // safe; the per-sequence rules (Eq. 6, the budgeted ones) read every mask byte of a sequence while other
+        // workgroups write out_mask.  Ranges that overlap without being identical are never meaningful.
+        const uintptr_t m0 = reinterpret_cast<uintptr_t>(mask), o0 = reinterpret_cast<uintptr_t>(out_mask);
+        const uintptr_t n = (uintptr_t)B * (uintptr_t)G;
+        const bool overlap = m0 < o0 + n && o0 < m0 + n;
+        const bool per_sequence = mode == DD_KL_PROB || mode == DD_KL_TOPK || mode == DD_CONF_TOPK;
+        if (overlap && (per_sequence || m0 != o0)) return DD_ERR_SHAPE;
+    }
     if (misaligned16(logits_v) || (kl && misaligned16(logits_d))) return DD_ERR_ALIGN;
     const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(B * G, V, eb));
     if (rc != DD_OK) return rc;
@@ -327,7 +335,12 @@ int dd_unmask(const void *logits_d, const uint8_t *mask, dd_unmask_mode mode, fl
     if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
     if (B == 0 || G == 0) return DD_OK;
     if (!logits_d || !mask || !out_mask || !out_tokens || !out_conf) return DD_ERR_NULL;
-    if (out_mask == mask) return DD_ERR_SHAPE;             // the selection reads every mask byte of a sequence
+    {
+        // the selection reads every mask byte of a sequence while other lanes write out_mask
+        const uintptr_t m0 = reinterpret_cast<uintptr_t>(mask), o0 = reinterpret_cast<uintptr_t>(out_mask);
+        const uintptr_t n = (uintptr_t)B * (uintptr_t)G;
+        if (m0 < o0 + n && o0 < m0 + n) return DD_ERR_SHAPE;
+    }
     if (misaligned16(logits_d)) return DD_ERR_ALIGN;
     const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(B * G, V, eb));
     if (rc != DD_OK) return rc;

@@ -26,6 +26,17 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipSt
     return launch_impl(kernel, grid, block, stream, vals, std::index_sequence_for<Params...>{});
 }
 
+// Test hooks.  The kernel a call runs on is chosen from its shape alone; so that the tests can reach every
+// kernel with every shape, a process started with DD_TUNE=1 in its environment (looked at once) lets the
+// variables below override single choices, read at every call.  Without DD_TUNE no call reads the environment.
+//   DD_TUNE_ATTN_WIDE=0/1      verifier attention off / on the wide-wave kernel
+//   DD_TUNE_ATTN_WIDE_GRID=n   at most n persistent workgroups on that kernel
+//   DD_TUNE_BIDIR_STREAM=0/1   small bf16 verifier calls off / on the streaming kernel
+//   DD_TUNE_BLOCK_STREAM=0     drafter calls with few query rows off the streaming kernel
+//   DD_TUNE_BLOCK_WIDE=0       drafter calls with many query rows off the wide-wave kernel
+// Returns the variable's integer value, or `dflt` when hooks are off or the variable is unset.
+int tune(const char *name, int dflt);
+
 // ---- verification (verify.hip) -------------------------------------------------
 // Number of workgroups one logit row is split over, and workspace size.
 int verify_splits(int P, int V, int elem_bytes);

@@ -21,10 +21,7 @@ namespace dd {
 namespace {
 
 constexpr int kThreads = 256;
-#ifndef DD_VERIFY_UNROLL
-#define DD_VERIFY_UNROLL 4
-#endif
-constexpr int kUnroll = DD_VERIFY_UNROLL;   // independent 16-byte loads per matrix in flight per lane
+constexpr int kUnroll = 4;   // independent 16-byte loads per matrix in flight per lane
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kNegInf = -INFINITY;
 // The drafter reference is raised when a logit exceeds it by more than this.  Zero keeps it
@@ -578,22 +575,13 @@ __global__ __launch_bounds__(kSeqThreads) void verify_finalize_seq_kernel(const 
     }
 }
 
-int env_int(const char *name, int dflt)
-{
-    const char *v = getenv(name);
-    return v && *v ? atoi(v) : dflt;
-}
-
 }  // namespace
 
 // Rows are handled by one workgroup each (fused finish) once there are enough of them to occupy the
 // chip; the workgroup grows as the row count shrinks so that the bytes in flight stay about constant.
 int verify_fused_threads(int P)
 {
-    static const int min_rows = env_int("DD_TUNE_VERIFY_FUSED_MIN_ROWS", 192);
-    if (P < min_rows) return 0;          // too few rows: split them over several workgroups instead
-    static const int forced = env_int("DD_TUNE_VERIFY_THREADS", 0);
-    if (forced == 256 || forced == 512) return forced;
+    if (P < 192) return 0;               // too few rows: split them over several workgroups instead
     return P >= 2048 ? 256 : 512;        // measured: 512 lanes per row stream best for 256..1024 rows
 }
 
@@ -603,9 +591,7 @@ int verify_fused_threads(int P)
 static int verify_split_chunk(int P, int V, int elem_bytes)
 {
     const long nvec = (long)V * elem_bytes / 16;
-    static const int forced = env_int("DD_TUNE_VERIFY_SPLITS", 0);
-    static const int target = env_int("DD_TUNE_VERIFY_TARGET_WGS", 2048);
-    long s = forced > 0 ? forced : (target + P - 1) / P;
+    long s = (2048 + P - 1) / P;         // about 2048 workgroups in all
     if (s > 16) s = 16;
     if (s < 1) s = 1;
     const long iter = (long)kThreads * kUnroll;

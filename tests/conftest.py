@@ -3,6 +3,10 @@ import sys
 
 import pytest
 
+# the library's kernel-choice overrides (DD_TUNE_*) are test hooks: they only work in a process that
+# had DD_TUNE=1 in its environment when the library first looked (its first call)
+os.environ["DD_TUNE"] = "1"
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)

@@ -104,7 +104,7 @@ def test_cache_insert_argument_validation():
 def test_verify_argument_validation():
     L = dd.lib()
 
-    def call(ld=FAKE, lv=FAKE, mask=FAKE, mode=dd.KL_THRESH, om=FAKE, ot=FAKE, osc=FAKE, B=2, G=8, V=1024,
+    def call(ld=FAKE, lv=FAKE, mask=FAKE, mode=dd.KL_THRESH, om=FAKE + 4096, ot=FAKE, osc=FAKE, B=2, G=8, V=1024,
              dt=dd.BF16, ws=None, wsn=0, tau=0.3):
         return L.dd_verify_remask(ld, lv, mask, mode, C.c_float(tau), 0, om, ot, osc, B, G, V, dt, ws, wsn, None)
     assert call(mode=7) == -4 and call(mode=-1) == -4
@@ -121,6 +121,15 @@ def test_verify_argument_validation():
     need = L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)
     assert need >= 16 * 32
     assert call(ws=FAKE, wsn=need - 1) == -5
+    # updating the mask in place: fine for the per-row rules (validation goes on to the missing workspace),
+    # refused for the rules that read a whole sequence's mask; ranges that merely overlap are always refused
+    for mode in (dd.TRUST, dd.KL_THRESH, dd.CONF_THRESH, dd.CONF_PROB):
+        assert call(mode=mode, om=FAKE) == -5
+        assert call(mode=mode, om=FAKE + 15) == -2 and call(mode=mode, mask=FAKE + 8, om=FAKE) == -2
+        assert call(mode=mode, om=FAKE + 16) == -5         # P = 16 bytes: adjacent, not overlapping
+    for mode in (dd.KL_PROB, dd.KL_TOPK, dd.CONF_TOPK):
+        assert call(mode=mode, om=FAKE, tau=2.0) == -2 and call(mode=mode, om=FAKE + 3, tau=2.0) == -2
+        assert call(mode=mode, om=FAKE + 16, tau=2.0) == -5
 
 
 def test_unmask_argument_validation():
@@ -133,7 +142,8 @@ def test_unmask_argument_validation():
     assert call(mode=dd.UNMASK_TOPK, tau=-1.0) == -2 and call(mode=dd.UNMASK_TOPK, tau=float("nan")) == -2
     assert call(dt=dd.FP8_E4M3) == -3 and call(B=-1) == -2 and call(V=0) == -2 and call(V=1001) == -6
     assert call(ld=None) == -1 and call(mask=None) == -1 and call(om=None) == -1 and call(oc=None) == -1
-    assert call(om=FAKE) == -2                             # out_mask must not alias mask
+    assert call(om=FAKE) == -2 and call(om=FAKE + 15) == -2 and call(mask=FAKE + 15, om=FAKE) == -2   # no overlap with mask
+    assert call(om=FAKE + 16) == -5
     assert call() == -5                                    # everything valid except the missing workspace
     assert call(B=0) == 0 and call(G=0) == 0
     assert L.dd_unmask_workspace_bytes(2, 8, 1024, dd.BF16) == L.dd_verify_remask_workspace_bytes(2, 8, 1024, dd.BF16)

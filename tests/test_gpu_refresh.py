@@ -79,29 +79,14 @@ def test_refresh_every_kernel(monkeypatch, B, H, Hkv, N, d, bl, bs, qk, env):
     check_refresh(cfg, cache, blk, bs, f"refresh {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk} {env}")
 
 
-@pytest.mark.parametrize("cfg_id", [1, 2, 5])
+@pytest.mark.parametrize("cfg_id", [1, 2, 3, 4, 5])
 def test_refresh_configs(cfg_id):
+    # every benchmark configuration at full size (cfg3: no key split, the copy is a launch of its own; cfg4: eight
+    # splits; cfg5: the wide kernel's drafter form): every output row against the oracle, the cache byte for byte
     cfg = wl.CONFIGS[cfg_id]
     cache = wl.cache_inputs(cfg, 0)
     blk = wl.block_inputs(cfg, 0, cfg.K - 1, k_scale=cache["k_scale"])
-    if cfg_id == 5:                      # the oracle on a sample of rows; the cache check is complete anyway
-        import torch
-        Kc, Vc = to_dev(cache["Kc"]), to_dev(cache["Vc"])
-        O = dd.dd_block_attention_refresh(to_dev(blk["Qblk"]), Kc, Vc, blk["block_start"], to_dev(blk["Kblk"]),
-                                          to_dev(blk["Vblk"]), q_scale=to_dev(blk["q_scale"]),
-                                          k_scale=to_dev(cache["k_scale"]), qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
-        torch.cuda.synchronize()
-        rng = np.random.default_rng(3)
-        rows = sorted(set(zip(rng.integers(0, cfg.B, 128).tolist(), rng.integers(0, cfg.H, 128).tolist(),
-                              rng.integers(0, cfg.bl, 128).tolist())))
-        ref, Kn, Vn = oracle.block_attention_refresh(blk["Qblk"], cache["Kc"], cache["Vc"], blk["block_start"],
-                                                     cfg.qk_dtype, cfg.v_dtype, blk["Kblk"], blk["Vblk"],
-                                                     blk["q_scale"], cache["k_scale"], rows=rows)
-        got = out_to_f64(O, cfg.v_dtype)
-        assert_attention_close(np.stack([got[b, h, i] for b, h, i in rows]), ref, cfg.qk_dtype, "cfg5 refresh (sampled)")
-        assert np.array_equal(raw(Kc), raw_np(Kn)) and np.array_equal(raw(Vc), raw_np(Vn))
-    else:
-        check_refresh(cfg, cache, blk, blk["block_start"], f"{cfg.name} refresh")
+    check_refresh(cfg, cache, blk, blk["block_start"], f"{cfg.name} refresh")
 
 
 def test_refreshing_every_block_makes_the_drafter_exact():

@@ -36,6 +36,10 @@ def check_against_oracle(inp, mode, tau, seed, B, G, dtype, what):
     diff = (om != ora["out_mask"]) & ~exempt
     assert not diff.any(), f"{what}: remask decisions differ at rows {np.nonzero(diff)[0][:8]}"
     assert np.array_equal(om[inp["mask"] != 0], np.ones(int((inp["mask"] != 0).sum()), np.uint8))
+    # no exemption at all for the rule itself: the oracle's decision function applied to the library's own fp32
+    # scores reproduces the library's decisions (thresholds, Eq. 6 with its per-sequence sum, the draws)
+    own, _ = oracle.remask_decide(osc, inp["mask"], mode, tau, seed, B, G)
+    assert np.array_equal(om, own), f"{what}: the rule applied to the library's own scores gives other decisions"
     return om, ot, osc, ora
 
 
@@ -164,58 +168,47 @@ def test_probabilistic_rate_matches_probability():
 
 
 # ------------------------------------------------------------------ benchmark configurations, full size
-def _full_size(cfg_id, n_sample, seed=0):
+def _full_size(cfg_id, seed=0):
+    """Every row of the configuration's verification call against the oracle: tokens exact, scores within the
+    score tolerance, decisions exact outside the threshold exemption, and the rule exact on the library's scores."""
     cfg = wl.CONFIGS[cfg_id]
     inp = wl.verify_inputs(cfg, seed=seed)
-    rng = np.random.default_rng(100 + cfg_id)
-    rows = np.unique(np.concatenate([[0, cfg.P - 1, cfg.G - 1, cfg.G % cfg.P], rng.integers(0, cfg.P, n_sample)]))
     import torch
     ld = to_dev(inp["logits_d"]); lv = to_dev(inp["logits_v"]); mk = to_dev(inp["mask"])
+    need_kl = any(mode in (wl.KL_THRESH, wl.KL_PROB) for mode, _ in cfg.modes)
+    kl, conf, tok = oracle.verify_scores(inp["logits_d"] if need_kl else None, inp["logits_v"], cfg.logit_dtype)
     for mode, tau in cfg.modes:
         kl_mode = mode in (wl.KL_THRESH, wl.KL_PROB)
         om, ot, osc = dd.dd_verify_remask(ld if kl_mode else None, lv, mk, mode, tau, seed, cfg.B, cfg.G,
                                           logit_dtype=cfg.logit_dtype)
         torch.cuda.synchronize()
         om, ot, osc = om.cpu().numpy(), ot.cpu().numpy(), osc.cpu().numpy()
-        kl, conf, tok = oracle.verify_scores(inp["logits_d"] if kl_mode else None, inp["logits_v"], cfg.logit_dtype,
-                                             rows=rows)
         score = kl if kl_mode else conf
-        assert np.array_equal(ot[rows], tok), f"cfg{cfg_id} mode {mode}: tokens"
-        assert_scores_close(osc[rows], score, f"cfg{cfg_id} mode {mode}")
-        # decisions on the sampled rows against the oracle's rule ...
-        ora_mask, _ = oracle.remask_decide(score.astype(np.float32), inp["mask"][rows], mode, tau, seed, 1, len(rows))
+        assert np.array_equal(ot, tok), f"cfg{cfg_id} mode {mode}: tokens"
+        assert_scores_close(osc, score, f"cfg{cfg_id} mode {mode}")
+        ora_mask, _ = oracle.remask_decide(score.astype(np.float32), inp["mask"], mode, tau, seed, cfg.B, cfg.G)
         exempt = np.abs(score - tau) <= 1e-5 * max(1.0, abs(tau))
-        assert np.array_equal(om[rows][~exempt], ora_mask[~exempt])
-        # ... and on every row as a property of the library's own scores
-        elig = inp["mask"] == 0
+        assert np.array_equal(om[~exempt], ora_mask[~exempt]), f"cfg{cfg_id} mode {mode}: decisions"
+        own, _ = oracle.remask_decide(osc, inp["mask"], mode, tau, seed, cfg.B, cfg.G)
+        assert np.array_equal(om, own), f"cfg{cfg_id} mode {mode}: the rule on the library's own scores"
         if mode == wl.TRUST:
-            want = inp["mask"]
-        elif mode == wl.KL_THRESH:
-            want = ((inp["mask"] != 0) | (elig & (osc > np.float32(tau)))).astype(np.uint8)
-        else:
-            want = ((inp["mask"] != 0) | (elig & (osc < np.float32(tau)))).astype(np.uint8)
-        assert np.array_equal(om, want)
-        assert ((ot >= 0) & (ot < cfg.V)).all() and np.isfinite(osc).all()
-        if kl_mode:
-            assert (osc > -1e-5).all()
-        else:
-            assert ((osc > 0) & (osc <= 1.0 + 1e-6)).all()
+            assert np.array_equal(om, inp["mask"])
 
 
 def test_cfg2_full_size():
-    _full_size(2, 256)       # every row
+    _full_size(2)
 
 
 def test_cfg3_full_size():
-    _full_size(3, 96)
+    _full_size(3)
 
 
 def test_cfg4_full_size():
-    _full_size(4, 128)
+    _full_size(4)
 
 
 def test_cfg5_full_size():
-    _full_size(5, 64)
+    _full_size(5)
 
 
 # ------------------------------------------------------------------ budgeted remasking (k worst positions per sequence)

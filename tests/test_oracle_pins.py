@@ -95,6 +95,25 @@ def test_row_uniform_properties():
     assert oracle.row_uniform(7 + 2 ** 32, 5) != us[5]
 
 
+def test_row_uniform_word_placement():
+    # counter = (row low, row high, 0, 0), key = (seed low, seed high), top 24 bits of output word 0: against the
+    # generator itself (pinned by the published known answers above) with the words placed by hand.  Distinct
+    # non-zero low and high words everywhere, so that a row word in the wrong counter slot, exchanged seed halves,
+    # counter and key swapped, another output word or the low 24 bits would each give another number.
+    for seed, row in ((0x11111111_22222222, 0x33333333_44444444), (0xDEADBEEF_00000001, 0x00000002_CAFEF00D),
+                      (1, 2), (2, 1), (0xFFFFFFFF_00000000, 0x00000000_FFFFFFFF), (5, 0x1_0000_0000)):
+        s_lo, s_hi, r_lo, r_hi = seed & 0xFFFFFFFF, seed >> 32, row & 0xFFFFFFFF, row >> 32
+        words = oracle.philox4x32_10([r_lo, r_hi, 0, 0], [s_lo, s_hi])
+        u = oracle.row_uniform(seed, row)
+        assert u == (words[0] >> 8) / 2.0 ** 24
+        wrong = [oracle.philox4x32_10([r_hi, r_lo, 0, 0], [s_lo, s_hi])[0] >> 8,
+                 oracle.philox4x32_10([r_lo, r_hi, 0, 0], [s_hi, s_lo])[0] >> 8,
+                 oracle.philox4x32_10([0, 0, r_lo, r_hi], [s_lo, s_hi])[0] >> 8,
+                 oracle.philox4x32_10([s_lo, s_hi, 0, 0], [r_lo, r_hi])[0] >> 8,
+                 words[1] >> 8, words[0] & 0xFFFFFF]
+        assert all(u != w / 2.0 ** 24 for w in wrong)
+
+
 # ------------------------------------------------------------------ softmax / confidence / argmax
 def _scores(ld, lv, dtype=F32, rows=None):
     return oracle.verify_scores(None if ld is None else np.asarray(ld, np.float32),
