@@ -253,6 +253,27 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
                      void *workspace, size_t workspace_bytes, void *stream);
 size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype);
 
+/*
+ * dd_verify_remask for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace pair),
+ * same kernels, same results bit for bit.  The partial states of a split row live in a file-scope device array
+ * inside the library instead: 128 KiB per GPU, held from the time the library's code is loaded on that GPU until
+ * the process ends.  The call allocates and frees nothing.
+ *   - Limit: dd_verify_remask_workspace_bytes(B, G, V, logit_dtype) <= 131072, else DD_ERR_WORKSPACE and nothing
+ *     is launched.  (Today's kernels need at most 191 rows x 16 splits x 32 bytes = 97792 bytes, and none from
+ *     192 rows on, so every valid shape fits.)
+ *   - The array is looked up once per GPU, at the first call that needs it while that GPU is current (a symbol
+ *     look-up, DD_ERR_LAUNCH if it fails): make that first call outside graph capture.  `stream` must belong to
+ *     the current device.
+ *   - All calls on one GPU share the one array, which keeps the last call's contents (no call depends on them):
+ *     two calls of this entry point that overlap in time on one GPU (different streams) race and give wrong
+ *     results; calls on one stream, or ordered by events, are fine.  Calls with 192 rows or more use no scratch.
+ */
+int dd_verify_remask_static(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                            dd_mode mode, float threshold, uint64_t seed,
+                            uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                            int B, int G, int V, dd_dtype logit_dtype, void *stream);
+
 typedef enum {
     DD_UNMASK_THRESH = 0,  /* every masked position whose drafter confidence exceeds the threshold */
     DD_UNMASK_TOPK = 1     /* a fixed number per step: the k = floor(threshold) most confident masked positions */

@@ -56,6 +56,8 @@ def lib():
     L.dd_verify_remask.argtypes = [vp, vp, vp, i, C.c_float, C.c_uint64, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_verify_remask_workspace_bytes.restype = sz
     L.dd_verify_remask_workspace_bytes.argtypes = [i, i, i, i]
+    L.dd_verify_remask_static.restype = i
+    L.dd_verify_remask_static.argtypes = [vp, vp, vp, i, C.c_float, C.c_uint64, vp, vp, vp, i, i, i, i, vp]
     L.dd_unmask.restype = i
     L.dd_unmask.argtypes = [vp, vp, i, C.c_float, vp, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_unmask_workspace_bytes.restype = sz
@@ -84,7 +86,7 @@ def lib():
 
 EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attention_workspace_bytes",
            "dd_block_attention_cached", "dd_block_attention_cached_workspace_bytes",
-           "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_unmask", "dd_unmask_workspace_bytes",
+           "dd_verify_remask", "dd_verify_remask_workspace_bytes", "dd_verify_remask_static", "dd_unmask", "dd_unmask_workspace_bytes",
            "dd_verify_scores", "dd_verify_scores_workspace_bytes",
            "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
            "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows",
@@ -374,6 +376,30 @@ def dd_verify_remask(logits_d, logits_v, mask, mode: int, threshold: float, seed
                                 _dev(out_scores, "out_scores"), B, G, V, dt, _dev(ws, "workspace"), wsn, _stream())
     if rc != 0:
         raise DDError(rc, "dd_verify_remask")
+    return out_mask, out_tokens, out_scores
+
+
+def dd_verify_remask_static(logits_d, logits_v, mask, mode: int, threshold: float, seed: int, B: int, G: int,
+                            out_mask, out_tokens, out_scores, logit_dtype: Optional[int] = None):
+    """dd_verify_remask without a workspace: the library's static device array holds the partial states.  The
+    three output tensors are the caller's (nothing is allocated here either).  Returns them."""
+    torch = _torch()
+    P, V = logits_v.shape
+    if P != B * G:
+        raise ValueError("logits_v must have B*G rows")
+    if logits_d is not None and tuple(logits_d.shape) != (P, V):
+        raise ValueError("logits_d shape must match logits_v")
+    dt = _dtype_tag(logits_v, "logits_v") if logit_dtype is None else logit_dtype
+    _check_vec(mask, P, torch.uint8, "mask")
+    _check_vec(out_mask, P, torch.uint8, "out_mask")
+    _check_vec(out_tokens, P, torch.int32, "out_tokens")
+    _check_vec(out_scores, P, torch.float32, "out_scores")
+    rc = lib().dd_verify_remask_static(_dev(logits_d, "logits_d"), _dev(logits_v, "logits_v"), _dev(mask, "mask"),
+                                       int(mode), float(threshold), int(seed) & (2 ** 64 - 1),
+                                       _dev(out_mask, "out_mask"), _dev(out_tokens, "out_tokens"),
+                                       _dev(out_scores, "out_scores"), B, G, V, dt, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_verify_remask_static")
     return out_mask, out_tokens, out_scores
 
 

@@ -4,8 +4,32 @@
 #include "dd_internal.h"
 
 #include <cstdlib>
+#include <mutex>
 
 namespace {
+
+// Scratch memory of dd_verify_remask_static: one copy per GPU, at its own address on each, held from the moment
+// the library's code is loaded on that GPU until the process ends.  The name below is a host-side handle only;
+// the device address is looked up once per device (scratch_of_current_device) and is what the kernels get.
+constexpr size_t kStaticScratchBytes = 128u * 1024u;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];            // device address of `scratch` on device i, or nullptr: not looked up yet
+std::mutex g_scratch_mutex;
+
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DD_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return DD_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DD_OK;
+}
 
 inline bool misaligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -314,6 +338,24 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
                                            out_mask, out_tokens, out_scores, B, G, V, logit_dtype == DD_BF16,
                                            workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+int dd_verify_remask_static(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                            dd_mode mode, float threshold, uint64_t seed,
+                            uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                            int B, int G, int V, dd_dtype logit_dtype, void *stream)
+{
+    const size_t need = dd_verify_remask_workspace_bytes(B, G, V, logit_dtype);
+    if (need > kStaticScratchBytes) return DD_ERR_WORKSPACE;      // more partial states than the static array holds
+    void *ws = nullptr;
+    if (need > 0) {
+        const int rc = scratch_of_current_device(&ws);
+        if (rc != DD_OK) return rc;
+    }
+    // every partial state the finishing kernel reads is written by the streaming kernel of the same call:
+    // nothing in the array has to be cleared between calls
+    return dd_verify_remask(logits_d, logits_v, mask, mode, threshold, seed, out_mask, out_tokens, out_scores,
+                            B, G, V, logit_dtype, ws, need, stream);
 }
 
 size_t dd_unmask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)
