@@ -29,12 +29,36 @@ PEAK_FP8_TFLOPS = 5000.0      # MI355X dense fp8 MFMA
 PEAK_FP32_VALU_TFLOPS = 157.3 # MI355X fp32 vector
 PEAK_HBM_GBPS = 8000.0        # MI355X HBM3E
 LLC_ROTATE_BYTES = 600e6      # rotate input sets until their total exceeds 2x the 256 MB last-level cache
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a 1 GiB copy (0.5 and 1.0); figures and commands: profiles/step_kernels_<workload>.md
-PROFILED_TRAFFIC_BYTES = {
-    "attention": {2: 17.0e6, 3: 272.1e6, 4: 135.5e6, 5: 503.7e6},
-    "verify": {2: 130.1e6, 3: 1038.4e6, 4: 259.8e6, 5: 2495.1e6},
-}
+KERNEL_SOURCES = ("attention_wide.hip", "attention_mfma.hip", "attention_stream.hip", "attention_common.h", "verify.hip")
+
+
+def kernel_source_digest():
+    """Short hash of the kernel sources: a profile records the one it was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_05250_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:12]
+
+
+def profiled_traffic(config_id, part):
+    """HBM bytes per launch of the dominant kernel of `part`, as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE (scaled by what the same counters read for a copy of known size) and recorded in
+    profiles/step_kernels_cfg<N>_*.md on a line `traffic_bytes: attention=... verify=... kernels=<digest>`.
+    None when there is no such record or when it was taken with other kernel sources than the ones in the tree."""
+    import glob
+    import re
+    for path in glob.glob(os.path.join(ROOT, "profiles", f"step_kernels_cfg{config_id}_*.md")):
+        for line in open(path):
+            m = re.match(r"\s*traffic_bytes:\s*(.*)", line)
+            if not m:
+                continue
+            kv = dict(t.split("=", 1) for t in m.group(1).split() if "=" in t)
+            if kv.get("kernels") != kernel_source_digest() or part not in kv:
+                return None
+            return float(kv[part])
+    return None
 
 
 def wl_mode_names():
@@ -80,6 +104,9 @@ def parse():
                     help="skip the additional warm-cache repetition of the steps (profiling: every launch in the "
                          "trace then belongs to the rotated, cold-cache steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="time only the configuration named by --config (the default run also times the other benchmark "
+                         "configurations, reported under 'per_config')")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="CPU oracle time budget per sampled part")
     return ap.parse_args()
 
@@ -90,17 +117,44 @@ def main():
         print("bench.py: this build runs on ONE GPU (no sharding or collectives are part of it); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    out = run_config(args, args.config)
+    if not args.no_per_config:
+        # the other benchmark configurations, same protocol (rotated inputs, events around each part), fewer steps,
+        # no graph replay and no CPU baseline: every rate of every configuration comes from this one run
+        import copy
+        light = copy.copy(args)
+        light.steps, light.warmup, light.prewarm_ms = max(5, args.steps // 4), 3, min(args.prewarm_ms, 150.0)
+        light.no_graph = light.no_warm = light.no_cpu_baseline = True
+        light.layers, light.calib_copy_mb, light.verify_mode = 0, 0, None
+        light.parts, light.window, light.refresh_last = "block,attention,verify", 0, False
+        out["per_config"] = {}
+        for cid in (2, 4, 5, 3):
+            if cid == args.config:
+                continue
+            r = run_config(light, cid)
+            out["per_config"][f"cfg{cid}"] = {
+                "workload": r["config"]["workload"], "steps": r["steps"], "ms_per_step": r["ms_per_step"],
+                "components_ms": r["components_ms"], "dtype": r["dtype"],
+                "roofline": r["roofline"], "roofline_verify": r["roofline_verify"],
+                "roofline_block": r["roofline_block"]}
+    print(json.dumps(out), flush=True)
+
+
+def run_config(args, config_id):
+    import gc
+
     import numpy as np
     import torch
 
     import paper_2604_05250_amd as dd
     from paper_2604_05250_amd import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
     dev = torch.device("cuda:0")
-    cfg = wl.CONFIGS[args.config]
+    cfg = wl.CONFIGS[config_id]
     mode, tau = cfg.modes[-1]
     if args.verify_mode is not None:                     # another rule of the same call on the same inputs
         mode = {v: k for k, v in wl.MODE_NAMES.items()}[args.verify_mode]
@@ -127,16 +181,20 @@ def main():
     verify_bytes = (2 if kl_mode else 1) * cfg.P * cfg.V * eb_l                               # logits read once
     blk_rows = cfg.B * cfg.H * cfg.bl * cfg.d
     block_bytes = kv_elems * (eb_qk + eb_v) + blk_rows * (eb_qk + eb_v)                       # cache + Qblk + O
-    set_bytes = attn_bytes + verify_bytes + kv_elems * (eb_qk + eb_v)
+    cache_bytes = kv_elems * (eb_qk + eb_v)
+    set_bytes = attn_bytes + verify_bytes
     n_sets = max(1, min(8, math.ceil(LLC_ROTATE_BYTES / set_bytes)))
+    # the K drafter calls of a step follow each other directly: each reads ANOTHER copy of the cache, enough
+    # copies that a call never finds its operands in the 256 MB last-level cache because an earlier call read them
+    n_caches = max(2, min(96, math.ceil(LLC_ROTATE_BYTES / cache_bytes)))
 
     sets = []
     for _ in range(n_sets):
         sets.append({
             "Q": up(att["Q"]), "K": up(att["K"]), "V": up(att["V"]),
-            "Kc": up(cache["Kc"]), "Vc": up(cache["Vc"]),
             "ld": up(ver["logits_d"]) if (kl_mode or "scores" in args.parts.split(",")) else None, "lv": up(ver["logits_v"]),
         })
+    caches = [{"Kc": up(cache["Kc"]), "Vc": up(cache["Vc"])} for _ in range(n_caches)]
     qs, ks = up(att["q_scale"]), up(att["k_scale"])
     kcs = up(cache["k_scale"])
     mask = up(ver["mask"])
@@ -178,21 +236,22 @@ def main():
     if win:                                              # K/V bytes of a call follow the window
         block_bytes = cfg.B * cfg.Hkv * win * cfg.d * (eb_qk + eb_v) + blk_rows * (eb_qk + eb_v)
 
-    def step(i, rec=None):
+    def step(i, rec=None, one_cache=False):
         s = sets[i % n_sets]
         marks = [ev() for _ in range(6)] if rec is not None else None
         if marks: marks[0].record()
         for k, b in enumerate(blk_dev if "block" in parts else ()):
+            kc = caches[0 if one_cache else (i * cfg.K + k) % n_caches]
             kw = dict(O=Oblk, Kblk=b["K"], Vblk=b["V"], q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype,
                       v_dtype=cfg.v_dtype)
             if win:
                 w0 = min(max(0, b["bs"] + cfg.bl // 2 - win // 2), cfg.N - win)
-                dd.dd_block_attention_window(b["Q"], s["Kc"], s["Vc"], b["bs"], w0, win, **kw)
+                dd.dd_block_attention_window(b["Q"], kc["Kc"], kc["Vc"], b["bs"], w0, win, **kw)
             elif args.refresh_last and k == cfg.K - 1:
                 kw.pop("Kblk"); kw.pop("Vblk")
-                dd.dd_block_attention_refresh(b["Q"], s["Kc"], s["Vc"], b["bs"], b["K"], b["V"], **kw)
+                dd.dd_block_attention_refresh(b["Q"], kc["Kc"], kc["Vc"], b["bs"], b["K"], b["V"], **kw)
             else:
-                dd.dd_block_attention_cached(b["Q"], s["Kc"], s["Vc"], b["bs"], **kw)
+                dd.dd_block_attention_cached(b["Q"], kc["Kc"], kc["Vc"], b["bs"], **kw)
         if marks: marks[1].record()
         for u in unmask_dev:
             dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
@@ -250,9 +309,9 @@ def main():
     warm_rec = []
     if not args.no_warm:
         for i in range(args.warmup):
-            step(0)
+            step(0, one_cache=True)
         for i in range(args.steps):
-            step(0, warm_rec)
+            step(0, warm_rec, one_cache=True)
         torch.cuda.synchronize()
 
     # the same steps replayed as HIP graphs (one per input set): what the cycle costs without the host in the loop
@@ -324,7 +383,8 @@ def main():
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
                                f"drafter block_len={cfg.bl} x K={cfg.K} steps, verify P={cfg.P} x V={cfg.V} "
                                f"mode={wl.MODE_NAMES[mode]} tau={tau}",
-                   "baseline_config_index": args.config - 1, "input_sets_rotated": n_sets, "seed": args.seed,
+                   "baseline_config_index": config_id - 1, "input_sets_rotated": n_sets, "cache_copies_rotated": n_caches,
+                   "seed": args.seed,
                    "prewarm_steps": prewarm_steps,
                    "parts": sorted(parts)},
         "verify_GBps": round(ver_gbps, 1),
@@ -338,6 +398,8 @@ def main():
             "verify_remask": round(sum(m[2].elapsed_time(m[3]) for m in warm_rec) / len(warm_rec), 4),
             "note": "every step on the same input set (operands that fit stay in the last-level cache); not used for any rate"},
         "block_attention_GBps": round(blk_gbps, 1),
+        "block_attention_warm_GBps": None if not warm_rec else round(
+            block_bytes / (sum(m[0].elapsed_time(m[1]) for m in warm_rec) / len(warm_rec) / cfg.K * 1e-3) / 1e9, 1),
         "graph_replay": None if graph_ms is None else {
             "ms_per_step": round(graph_ms, 4),
             "note": "the same steps captured once per input set and replayed as HIP graphs; ms_per_step above is the eager "
@@ -346,17 +408,24 @@ def main():
                      "achieved": round(attn_tflops, 3), "peak": round(attn_peak, 1), "unit": "TFLOP/s",
                      "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
                      "frac_of_bf16_peak": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": PROFILED_TRAFFIC_BYTES["attention"].get(args.config),
+                     "traffic": profiled_traffic(config_id, "attention"),
                      "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
         "roofline_verify": {"kernel": ("verify_row_kernel" if cfg.P >= 192 else "verify_partial_kernel + verify_finalize_kernel")
                                       + {wl.KL_PROB: " + verify_klprob_kernel", wl.KL_TOPK: " + verify_topk_kernel",
                                          wl.CONF_TOPK: " + verify_topk_kernel"}.get(mode, "") + " (dd_verify_remask)",
                             "bound": "hbm", "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": round(ver_gbps / PEAK_HBM_GBPS, 4),
-                            "traffic": PROFILED_TRAFFIC_BYTES["verify"].get(args.config),
+                            "traffic": profiled_traffic(config_id, "verify"),
                             "algorithmic_bytes": verify_bytes},
     }
 
+    out["roofline_block"] = {"kernel": "dd_block_attention_cached (attn_stream_kernel / attn_wide_kernel<.., BLOCK> / "
+                                       "attn_mfma_kernel + attn_combine_kernel, by shape)",
+                             "bound": "hbm", "achieved": round(blk_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                             "frac": round(blk_gbps / PEAK_HBM_GBPS, 4), "traffic": profiled_traffic(config_id, "block"),
+                             "algorithmic_bytes": block_bytes, "cache_copies_rotated": n_caches,
+                             "note": f"per call, K={cfg.K} calls per step, each on another copy of the cache (cold); "
+                                     "block_attention_warm_GBps: every call on one copy"}
     if "scores" in parts:
         t_sc = max(sum(m[3].elapsed_time(m[5]) for m in rec) / len(rec), 1e-9)
         sc_bytes = 2 * cfg.P * cfg.V * eb_l
@@ -379,7 +448,7 @@ def main():
                                   "note": f"K={cfg.K} calls per step on the active block's drafter logits [{cfg.B * cfg.bl}, {cfg.V}]"}
 
     if args.layers > 0:
-        out["multi_layer"] = multi_layer_cycle(args, cfg, dd, wl, torch, sets[0], blk_dev, qs, ks, kcs, mask, mode, tau,
+        out["multi_layer"] = multi_layer_cycle(args, cfg, dd, wl, torch, dict(sets[0], **caches[0]), blk_dev, qs, ks, kcs, mask, mode, tau,
                                                up(ver["logits_d"]), O, Oblk, out_mask, out_tok, out_sc)
 
     if not args.no_cpu_baseline:
@@ -439,7 +508,10 @@ def main():
             gomp.omp_set_num_threads(oracle.num_threads())
             out["cpu_baseline_verify"]["value_1_thread"] = round(n1 * (2 if kl_mode else 1) * cfg.V * eb_l / t1 / 1e9, 4)
             out["cpu_baseline_verify"]["sample_1_thread"] = f"{n1} logit rows ({t1:.1f} s)"
-    print(json.dumps(out), flush=True)
+    del sets, blk_dev, caches
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
 
 
 def multi_layer_cycle(args, cfg, dd, wl, torch, s0, blk_dev, qs, ks, kcs, mask, mode, tau, ld_full, O, Oblk,

@@ -67,6 +67,8 @@ constexpr int kRowsWave = 32 * QB;
 constexpr int kRowsWGWide = 4 * kRowsWave;
 constexpr int kPackLag = 2;              // pieces between an exponential and its conversion to bf16
 constexpr float kSlack = 8.0f;          // the maximum in use is raised when exceeded by 2^8
+constexpr int kFoldMinKeys = 2048;      // key rows from which scaling Q once per row tile pays (see FOLD below)
+constexpr float kFoldMargin = 7.0f;     // folded form: the reference is set this far above a unit's maximum (log2 units)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ unsigned pack_bf16_rne(float lo, float hi)
@@ -140,10 +142,26 @@ using F_ = std::false_type;
 // part a whole number of 64-row tiles by the same overlap rule, so each part is empty or at least 64 rows:
 // the launcher checks), a workgroup takes one row tile and one of `splits` ranges of the tile list, and
 // with splits > 1 writes its unnormalised state for the merge kernel instead of O.
-template <int D, bool FP8, bool BLOCK>
+// FOLD (bf16 Q/K without per-head scales, key ranges of kFoldMinKeys rows or more): the factor
+// c = log2(e)/sqrt(d_k) is multiplied into the Q fragments once per row tile (rounded to bf16 again; this second
+// rounding perturbs a score by about 2^-10 of the typical score magnitude, as much as the bf16 rounding of the
+// weights does), and every score block accumulates onto minus the softmax reference of its query rows instead of
+// zero, so the matrix cores deliver S' = c q.k - m and the weight of a key is exp2(S') with no other arithmetic
+// per score.  Scaling Q costs some 1600 cycles per row tile and wave and the form saves about 100 per 64 keys:
+// at 4096 keys the call is 2.5 % faster, at 1024 keys nothing is left.  The same mechanism WITHOUT the folded
+// scale (one multiplication per score in place of the fused multiply-add and the maxima) was measured 2-3 %
+// slower than the row-maximum form below on the 1024- and 2048-key workloads, so that form stays for them.  (The registers of a score block are free between its last exponential and the
+// first product of the block after next: they are refilled with -m by four 16-byte LDS reads per row block, from a
+// per-lane slot that holds four copies of it.)  The reference only has to be NEAR the running maximum (weights and
+// sums are floating point, any common factor 2^-m cancels in O = sum(P v) / sum(P)): it is set to the maximum of a
+// row tile's first unit plus a margin, and raised when some weight reaches 2, which shows as one bit of its bf16
+// pattern - the packed weights are or-ed together as they are produced (one instruction per four scores) and
+// tested once per unit.
+template <int D, bool FP8, bool BLOCK, bool FOLD = false>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_wide_kernel(const AttnKernelArgs a)
 {
+    static_assert(!(FOLD && FP8), "the scale cannot be folded into fp8 operands");
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per V / O row
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
@@ -160,11 +178,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int NQK = KS * QB;                     // pieces of a step: S(u+1) ...
     constexpr int NPV = 2 * DC * QB;                 // ... O += V P ...
     constexpr int NP = NQK + NPV + 2 * QB;           // ... and the row sums
-    constexpr int MAXC = NP >= 32 ? 8 : 4;           // pieces that carry the row maxima
-    constexpr int EXC = NP - MAXC;                   // pieces that carry the 32 exponentials
+    constexpr int MAXC = FOLD ? 0 : NP >= 32 ? 8 : 4;   // pieces that carry the row maxima
+    constexpr int CHK = NP - 6;                      // FOLD: the piece that tests the unit's weights, after the last pack ...
+    constexpr int EXC = FOLD ? CHK - kPackLag : NP - MAXC;   // pieces that carry the 32 exponentials
+    constexpr int PRE = CHK + 1;                     // ... and the first of the 2 QB pieces that refill the score registers
     constexpr int RD = 3;                            // fragment rings: fetched RD uses (2 RD MFMAs) ahead
     static_assert(NDMA_K + NDMA + 1 <= NP, "one tile load per piece");
-    static_assert(16 % (2 * MAXC) == 0, "whole pairs of scores per maximum piece");
+    static_assert(FOLD || 16 % (2 * MAXC) == 0, "whole pairs of scores per maximum piece");
     static_assert(KF >= RD && 2 * DC >= RD, "fragment rings are three deep");
     static_assert((4 * DMA_ROWS) % 8 == 0 && DMA_ROWS <= 8, "swizzle phase must not depend on the load index");
     static_assert((4 * KDMA_ROWS) % 8 == 0 && KDMA_ROWS <= 8, "swizzle phase must not depend on the load index");
@@ -177,6 +197,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int QOW = kRowsWave * OPITCH;          // bytes per wave
     static_assert(QOW % 16 == 0, "wave regions stay 16-byte aligned");
     __shared__ uint4 QO[4 * QOW / 16];
+    // FOLD: minus the softmax reference of each query row, four copies per lane: [wave][row block][lane]
+    __shared__ float4 MREF[FOLD ? 4 * QB * 64 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -366,9 +388,20 @@ void attn_wide_kernel(const AttnKernelArgs a)
             for (int i = 0; i < DC; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[q][i]) : "v"(z));
         }
     };
-    float mc[QB] = {-INFINITY, -INFINITY};           // maximum in use (log2 units), equal in both lane halves
+    float mc[QB] = {FOLD ? 0.f : -INFINITY, FOLD ? 0.f : -INFINITY};   // maximum (FOLD: reference) in use, log2 units, equal in both lane halves
     float thr[QB] = {-INFINITY, -INFINITY};          // raw scores above (mc + slack) / c raise the maximum in use
     float mc_done[QB] = {-INFINITY, -INFINITY};      // the finished tile's maximum in use (BLOCK: part of its state)
+    bool ref_unset = false;                          // FOLD: a row tile has begun with wholly masked units, no reference yet (uniform)
+    unsigned seen0 = 0u;                             // ... what the or of a unit's weights starts from: the tested bit while that is so
+    if constexpr (FOLD) {
+#pragma unroll
+        for (int q = 0; q < QB; ++q) MREF[(wave * QB + q) * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+    // a score block's registers <- -m of its rows (this lane's slot; written and read by this wave only)
+    auto refill = [&](floatx16 &sb, int q, int quarter) __attribute__((always_inline)) {
+        const float4 v = MREF[(wave * QB + q) * 64 + lane];
+        sb[4 * quarter] = v.x; sb[4 * quarter + 1] = v.y; sb[4 * quarter + 2] = v.z; sb[4 * quarter + 3] = v.w;
+    };
     intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
 
@@ -421,10 +454,23 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 const int lo = ((ln & 31) * KCH + ((2 * f + (ln >> 5)) ^ (ln & 7))) * 16;
                 const intx4 w = __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
                                     reinterpret_cast<const char *>(QO) + wave * QOW + q * 32 * KROWB + lo));
+                if constexpr (FOLD) {
+                    // c q, rounded to bf16 once more (two values per register)
+                    intx4 ws;
 #pragma unroll
-                for (int m = 0; m < MPF; ++m) {
-                    qf[q][f * MPF + m] = k_op(w, m);
-                    asm volatile("" : "+a"(qf[q][f * MPF + m]));
+                    for (int k = 0; k < 4; ++k) {
+                        const unsigned u = (unsigned)w[k];
+                        ws[k] = (int)pack_bf16_rne(__uint_as_float(u << 16) * a.scale_log2,
+                                                   __uint_as_float(u & 0xFFFF0000u) * a.scale_log2);
+                    }
+                    qf[q][f] = ws;
+                    asm volatile("" : "+a"(qf[q][f]));
+                } else {
+#pragma unroll
+                    for (int m = 0; m < MPF; ++m) {
+                        qf[q][f * MPF + m] = k_op(w, m);
+                        asm volatile("" : "+a"(qf[q][f * MPF + m]));
+                    }
                 }
             }
             const int v = min(t.v0 + wave * kRowsWave + q * 32 + (ln & 31), rows_total - 1);
@@ -527,8 +573,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto step = [&](int u, floatx16 (&s_cur)[QB], floatx16 (&s_nxt)[QB], unsigned (&pk_prev)[QB][2][4],
                     unsigned (&pk_cur)[QB][2][4], const uint4 *kb, int ksub, const uint4 *vb, int vsub,
                     auto primed, auto chain, auto dma, uint4 *dk, const uint8_t *kg,
-                    uint4 *dv, const uint8_t *vg, auto can_finish, bool fin, const Tile &cur, auto maskable)
+                    uint4 *dv, const uint8_t *vg, auto can_finish, bool fin, const Tile &cur, auto maskable, auto first)
                     __attribute__((always_inline)) {
+        // `first` (FOLD): S(u) is the first score block of a row tile - the softmax reference is set from it
+        constexpr bool FIRST = decltype(first)::value;
         constexpr bool PRIMED = decltype(primed)::value, CHAIN = decltype(chain)::value;
         constexpr bool DMA = decltype(dma)::value, CANFIN = decltype(can_finish)::value;
         // `maskable` false: the caller knows that unit u lies in a tile that starts at its nominal row (any tile
@@ -550,7 +598,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     if (k0 + 8 * (r >> 2) + (r & 3) < lim) s_cur[q][r] = -INFINITY;
             // A key range that starts with a wholly masked unit (BLOCK: a split may begin at a part's
             // overlapping last tile) has no maximum yet: give it a finite one, so that its weights are 0, not NaN.
-            if (BLOCK && lim >= 32) {
+            if (BLOCK && !FOLD && lim >= 32) {
 #pragma unroll
                 for (int q = 0; q < QB; ++q)
                     if (mc[q] == -INFINITY) {
@@ -563,11 +611,52 @@ void attn_wide_kernel(const AttnKernelArgs a)
         bool changed = false;
         // element e = 2 pr + (0/1) of the exponential stream is S(u)[q = pr & 1][r = 2 (pr >> 1) + (0/1)]
         auto exp_piece = [](int e) constexpr { int t = MAXC; while (!(e < 32 * (t - MAXC + 1) / EXC)) ++t; return t; };
+        unsigned seen = seen0, w_even = 0u;                  // FOLD: the weights' bit patterns or-ed together
         auto pack_pair = [&](int pr) __attribute__((always_inline)) {
             const int q = pr & 1, r = (pr >> 1) * 2;
             unsigned w = pack_bf16_rne(pe[2 * pr], pe[2 * pr + 1]);
             asm volatile("" : "+v"(w));                      // P(u) is only consumed a step later: keep its
             pk_cur[q][r >> 3][(r & 7) >> 1] = w;             // computation here, beside the matrix-core work
+            if constexpr (FOLD) {
+                if (pr & 1) asm volatile("v_or3_b32 %0, %0, %1, %2" : "+v"(seen) : "v"(w_even), "v"(w));
+                else w_even = w;
+            }
+        };
+        // FOLD, once per unit after its last weight is packed.  Some weight reached 2 (bit 14 of a bf16 pattern:
+        // exponent field >= 128; an overflowed weight is +inf and shows the same bit), or the unit opens a row tile:
+        // move the reference of every row to the maximum of this unit plus the margin - never down, except when
+        // opening a tile - and redo what was computed with the old one: this unit's weights and the next unit's
+        // scores here, the accumulated sums at the end of the step (`changed`).
+        auto check_reference = [&]() __attribute__((always_inline)) {
+            if (__builtin_expect(FIRST || __builtin_amdgcn_ballot_w64((seen & 0x40004000u) != 0u) != 0, FIRST)) {
+                const bool opening = FIRST || ref_unset;     // nothing but zeros accumulated so far
+#pragma unroll
+                for (int q = 0; q < QB; ++q) {
+                    float rm = vmax(s_cur[q][0], s_cur[q][1]);
+#pragma unroll
+                    for (int r = 2; r < 16; r += 2) rm = vmax3(rm, s_cur[q][r], s_cur[q][r + 1]);
+                    rm = half_swap_max(rm);                  // both lane halves hold keys of the same query row
+                    float delta = rm + kFoldMargin;
+                    if (opening) delta = rm == -INFINITY ? 0.f : delta;  // a wholly masked unit leaves the reference alone
+                    else delta = delta > 0.f ? delta : 0.f;
+                    if (q == 0) {                            // masks are the same for every row
+                        ref_unset = opening && __builtin_amdgcn_ballot_w64(rm != -INFINITY) == 0;
+                        seen0 = ref_unset ? 0x4000u : 0u;
+                    }
+                    mc[q] += delta;
+                    MREF[(wave * QB + q) * 64 + lane] = make_float4(-mc[q], -mc[q], -mc[q], -mc[q]);
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        s_cur[q][r] -= delta;
+                        s_nxt[q][r] -= delta;                // (written by matrix instructions many pieces ago)
+                    }
+#pragma unroll
+                    for (int r = 0; r < 16; r += 2)
+                        pk_cur[q][r >> 3][(r & 7) >> 1] = pack_bf16_rne(fast_exp2(s_cur[q][r]), fast_exp2(s_cur[q][r + 1]));
+                    corr[q] = fast_exp2(-delta);
+                }
+                changed = !opening;                          // (zeros need no rescaling, and 2^-delta may overflow there)
+            }
         };
         // everything of the step that is not an MFMA, dealt out over the NP pieces
         auto piece = [&](int t) __attribute__((always_inline)) {
@@ -575,7 +664,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 if (t <= NDMA_K) dma_one(dk, kg, dma_koff, t - 1);
                 else dma_one(dv, vg, dma_voff, t - 1 - NDMA_K);
             }
-            if (t < MAXC) {
+            if constexpr (MAXC > 0) if (t < MAXC) {
                 // row maxima of S(u) decide, without a divergent branch, whether the maxima in use are raised
 #pragma unroll
                 for (int r = 16 * t / MAXC; r < 16 * (t + 1) / MAXC; r += 2)
@@ -597,11 +686,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
                         }
                     }
                 }
-            } else {
+            }
+            if (t >= MAXC) {
 #pragma unroll
                 for (int e = 32 * (t - MAXC) / EXC; e < 32 * (t - MAXC + 1) / EXC; ++e) {
                     const int pr = e >> 1, q = pr & 1, r = (pr >> 1) * 2 + (e & 1);
-                    pe[e] = fast_exp2(fmaf(s_cur[q][r], c[q], -mc[q]));
+                    if constexpr (FOLD) pe[e] = fast_exp2(s_cur[q][r]);
+                    else pe[e] = fast_exp2(fmaf(s_cur[q][r], c[q], -mc[q]));
                 }
             }
             // pairs completed in the previous piece are packed now: a transcendental result cannot be
@@ -609,6 +700,14 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int pr = 0; pr < 16; ++pr)
                 if (exp_piece(2 * pr + 1) == t - kPackLag) pack_pair(pr);
+            if constexpr (FOLD) {
+                if (t == CHK) check_reference();
+                // S(u) has been consumed: its registers take -m for S(u+2), two 16-byte reads per piece
+                if (t >= PRE && t < PRE + 2 * QB) {
+                    refill(s_cur[(t - PRE) / 2], (t - PRE) / 2, 2 * ((t - PRE) & 1));
+                    refill(s_cur[(t - PRE) / 2], (t - PRE) / 2, 2 * ((t - PRE) & 1) + 1);
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);               // nothing moves between pieces
         };
         // ---- S(u+1): the first V fragments are fetched meanwhile
@@ -617,8 +716,12 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
                 const int f = j / MPF;                       // fragment of this k-step; it is free after its last use
-                if (j == 0) qk_first<FP8>(s_nxt[q], k_op(kfr[0], 0), qf[q][0]);
-                else qk_next<FP8>(s_nxt[q], k_op(kfr[f % RD], j), qf[q][j]);
+                if constexpr (FOLD) {
+                    qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);   // onto -m, put there a step ago
+                } else {
+                    if (j == 0) qk_first<FP8>(s_nxt[q], k_op(kfr[0], 0), qf[q][0]);
+                    else qk_next<FP8>(s_nxt[q], k_op(kfr[f % RD], j), qf[q][j]);
+                }
                 if (q == QB - 1 && j % MPF == MPF - 1 && f + RD < KF) kfr[f % RD] = k_frag(kb, ksub, f + RD);
                 if (q == 0 && j >= KS - RD) vfr[j - (KS - RD)] = v_frag(vb, vsub, j - (KS - RD));
                 piece(j * QB + q);
@@ -656,15 +759,23 @@ void attn_wide_kernel(const AttnKernelArgs a)
         if (CANFIN && fin) {                                 // uniform: the row tile is complete
             write_out(cur);
             clear_acc_mfma();
-        } else if (__builtin_expect(changed, 0)) {           // rare: everything accumulated so far changes units
+        }
+        else if (__builtin_expect(changed, 0)) {           // rare: everything accumulated so far changes units
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
+                // (sixteen registers at a time, each block back in accumulation registers before the next is read:
+                // left alone, the compiler holds all 160 products in vector registers at once)
+                asm volatile("" : "+a"(acc_l[q]));
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc_l[q][r] *= corr[q];
+                asm volatile("" : "+a"(acc_l[q]));
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < DC; ++i) {
+                    asm volatile("" : "+a"(acc[q][i]));
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[q][i][r] *= corr[q];
+                    asm volatile("" : "+a"(acc[q][i]));
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -697,18 +808,21 @@ void attn_wide_kernel(const AttnKernelArgs a)
         const int ktile = KIND == 0 ? sp + 2 : KIND - 1, vtile = last ? 0 : sp + 1;
         step(2 * sp + 1, s1, s0, pk0, pk1, kbuf(I_<1 - PAR>{}), 0, vbuf(I_<PAR>{}), 0, F_{}, T_{}, T_{},
              kbuf(I_<PAR>{}), tile_at(KIND == 0 || BLOCK ? cur : nxt, ktile).k,
-             vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur, maskable);
+             vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur, maskable, F_{});
         if (!BLOCK && KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
             mc_done[0] = mc[0];
             mc_done[1] = mc[1];
-            mc[0] = mc[1] = -INFINITY;                       // the second step starts the next tile's softmax
-            thr[0] = thr[1] = -INFINITY;
-            c[0] = c_next[0];
-            c[1] = c_next[1];
+            if constexpr (!FOLD) {
+                mc[0] = mc[1] = -INFINITY;                   // the second step starts the next tile's softmax
+                thr[0] = thr[1] = -INFINITY;
+                c[0] = c_next[0];
+                c[1] = c_next[1];
+            }                                                // (FOLD: the second step is a tile's first and resets the reference)
         }
         step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
-             kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur, maskable);
+             kbuf(I_<PAR>{}), cur.k, vbuf(I_<1 - PAR>{}), cur.v, std::integral_constant<bool, last>{}, last, cur, maskable,
+             std::integral_constant<bool, last>{});
         // The barrier that ends a stage waits for the stage's tile loads.  Memory operations complete in
         // order, so the requests issued after those loads - the next tile's Q rows, the finished tile's
         // output rows - can stay in flight: wait until only that many are outstanding.
@@ -733,17 +847,24 @@ void attn_wide_kernel(const AttnKernelArgs a)
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            if (ks == 0) qk_first<FP8>(s0[q], k_op(k_frag(K0, 0, 0), 0), qf[q][0]);
+            if (ks == 0) qk_first<FP8>(s0[q], k_op(k_frag(K0, 0, 0), 0), qf[q][0]);      // (FOLD: from zero, the reference is 0)
             else qk_next<FP8>(s0[q], k_op(k_frag(K0, 0, ks / MPF), ks), qf[q][ks]);
         }
 #pragma unroll
     for (int q = 0; q < QB; ++q)
 #pragma unroll
         for (int t = 0; t < 8; ++t) pk1[q][t >> 2][t & 3] = 0u;
+    if constexpr (FOLD) {                                    // S(1) accumulates onto minus the reference, which is 0
+#pragma unroll
+        for (int q = 0; q < QB; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s1[q][r] = 0.f;
+        asm volatile("" : "+v"(s1[0]), "+v"(s1[1]));
+    }
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur, T_{});
+    step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur, T_{}, T_{});
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
 
     // ---- passes: stages 0 .. nt_even-1 = steps 1 .. 2 nt_even; the product with P(u) happens in step u+1,
@@ -793,8 +914,12 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
         if (a.d != 128) return hipErrorInvalidValue;      // 64-byte fp8 rows are not worth a variant
         return launch(attn_wide_kernel<128, true, false>, grid, block, stream, k);
     }
-    if (a.d == 128) return launch(attn_wide_kernel<128, false, false>, grid, block, stream, k);
-    return launch(attn_wide_kernel<64, false, false>, grid, block, stream, k);
+    // bf16 without per-head scales, long key ranges: the form with the softmax scale folded into Q
+    const bool fold = a.q_scale == nullptr && a.k_scale == nullptr && a.N >= kFoldMinKeys;
+    if (a.d == 128) return fold ? launch(attn_wide_kernel<128, false, false, true>, grid, block, stream, k)
+                                : launch(attn_wide_kernel<128, false, false>, grid, block, stream, k);
+    return fold ? launch(attn_wide_kernel<64, false, false, true>, grid, block, stream, k)
+                : launch(attn_wide_kernel<64, false, false>, grid, block, stream, k);
 }
 
 // The drafter's call on the wide kernel: worth it when a kv head has a few hundred query rows (GQA groups
@@ -838,9 +963,12 @@ hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
     const size_t rows = (size_t)a.B * a.H * a.Nq;
     k.part_ml = k.part_o ? k.part_o + rows * (size_t)splits * a.d : nullptr;
     const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles * splits)), block(kAttnThreads);
+    const bool fold = a.q_scale == nullptr && a.k_scale == nullptr && a.N >= kFoldMinKeys;
     const hipError_t e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true>, grid, block, stream, k)
-                       : a.d == 128     ? launch(attn_wide_kernel<128, false, true>, grid, block, stream, k)
-                                        : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k);
+                       : a.d == 128 ? (fold ? launch(attn_wide_kernel<128, false, true, true>, grid, block, stream, k)
+                                            : launch(attn_wide_kernel<128, false, true>, grid, block, stream, k))
+                                    : (fold ? launch(attn_wide_kernel<64, false, true, true>, grid, block, stream, k)
+                                            : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k));
     return e != hipSuccess ? e : finish_attention(a, splits, stream);
 }
 
