@@ -48,13 +48,18 @@ typedef enum {
     DD_ERR_MODE = -4,       /* unknown remask mode */
     DD_ERR_WORKSPACE = -5,  /* workspace NULL / too small / misaligned */
     DD_ERR_ALIGN = -6,      /* a pointer or row pitch is not 16-byte aligned */
-    DD_ERR_LAUNCH = -7      /* the HIP runtime refused a launch */
+    DD_ERR_LAUNCH = -7,     /* the HIP runtime refused a launch */
+    DD_STATUS_INT_RANGE_LO = -0x7fffffff - 1, DD_STATUS_INT_RANGE_HI = 0x7fffffff
 } dd_status;
+
+/* (The *_INT_RANGE_* enumerators of the enumerations in this header only give them the value range of int, so that
+ * an integer a C caller passes for them - valid or not - is a value the library may legally inspect and refuse.) */
 
 typedef enum {
     DD_F32 = 0,        /* IEEE binary32 */
     DD_BF16 = 1,       /* upper 16 bits of binary32 */
-    DD_FP8_E4M3 = 2    /* OCP e4m3 (bias 7, max 448, no infinities); Q and K only */
+    DD_FP8_E4M3 = 2,   /* OCP e4m3 (bias 7, max 448, no infinities); Q and K only */
+    DD_DTYPE_INT_RANGE_LO = -0x7fffffff - 1, DD_DTYPE_INT_RANGE_HI = 0x7fffffff
 } dd_dtype;
 
 typedef enum {
@@ -66,7 +71,8 @@ typedef enum {
     /* Budgeted forms of the two rules above (not rules of the paper, which only thresholds or draws):
      * per sequence, the k = floor(threshold) worst eligible positions are remasked. */
     DD_KL_TOPK = 5,      /* the k eligible positions with the largest KL_i   */
-    DD_CONF_TOPK = 6     /* the k eligible positions with the smallest c_V,i */
+    DD_CONF_TOPK = 6,    /* the k eligible positions with the smallest c_V,i */
+    DD_MODE_INT_RANGE_LO = -0x7fffffff - 1, DD_MODE_INT_RANGE_HI = 0x7fffffff
 } dd_mode;
 
 /* Human-readable text for a dd_status (static storage; never NULL). */
@@ -276,7 +282,8 @@ int dd_verify_remask_static(const void *logits_d, const void *logits_v, const ui
 
 typedef enum {
     DD_UNMASK_THRESH = 0,  /* every masked position whose drafter confidence exceeds the threshold */
-    DD_UNMASK_TOPK = 1     /* a fixed number per step: the k = floor(threshold) most confident masked positions */
+    DD_UNMASK_TOPK = 1,    /* a fixed number per step: the k = floor(threshold) most confident masked positions */
+    DD_UNMASK_MODE_INT_RANGE_LO = -0x7fffffff - 1, DD_UNMASK_MODE_INT_RANGE_HI = 0x7fffffff
 } dd_unmask_mode;
 
 /*

@@ -304,12 +304,14 @@ size_t dd_verify_remask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtyp
     return dd::verify_workspace_bytes(B * G, V, logit_dtype == DD_BF16 ? 2 : 4);
 }
 
-int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask,
-                     dd_mode mode, float threshold, uint64_t seed,
-                     uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
-                     int B, int G, int V, dd_dtype logit_dtype,
-                     void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+// everything dd_verify_remask checks before it launches, except the workspace; DD_OK with *empty set for a no-op
+static int check_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask, int mode, float threshold,
+                               const uint8_t *out_mask, const int32_t *out_tokens, const float *out_scores,
+                               int B, int G, int V, int logit_dtype, bool *empty)
 {
+    *empty = false;
     if (mode < DD_TRUST || mode > DD_CONF_TOPK) return DD_ERR_MODE;
     if ((mode == DD_KL_TOPK || mode == DD_CONF_TOPK) && !(threshold >= 0.0f && threshold <= 3.0e38f)) return DD_ERR_SHAPE;
     if (logit_dtype != DD_F32 && logit_dtype != DD_BF16) return DD_ERR_DTYPE;
@@ -317,7 +319,10 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
     if ((double)B * G >= 2147483648.0) return DD_ERR_SHAPE;
     const int eb = logit_dtype == DD_BF16 ? 2 : 4;
     if (((long)V * eb) % 16 != 0) return DD_ERR_ALIGN;
-    if (B == 0 || G == 0) return DD_OK;
+    if (B == 0 || G == 0) {
+        *empty = true;
+        return DD_OK;
+    }
     const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB || mode == DD_KL_TOPK);
     if (!logits_v || !mask || !out_mask || !out_tokens || !out_scores) return DD_ERR_NULL;
     if (kl && !logits_d) return DD_ERR_NULL;
@@ -332,12 +337,44 @@ int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *
         if (overlap && (per_sequence || m0 != o0)) return DD_ERR_SHAPE;
     }
     if (misaligned16(logits_v) || (kl && misaligned16(logits_d))) return DD_ERR_ALIGN;
-    const int rc = check_workspace(workspace, workspace_bytes, dd::verify_workspace_bytes(B * G, V, eb));
+    return DD_OK;
+}
+
+static int verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask, int mode, float threshold,
+                         uint64_t seed, uint8_t *out_mask, int32_t *out_tokens, float *out_scores, int B, int G, int V,
+                         int logit_dtype, void *workspace, size_t workspace_bytes, void *stream, bool static_scratch)
+{
+    bool empty = false;
+    int rc = check_verify_remask(logits_d, logits_v, mask, mode, threshold, out_mask, out_tokens, out_scores, B, G, V,
+                                 logit_dtype, &empty);
+    if (rc != DD_OK || empty) return rc;
+    const int eb = logit_dtype == DD_BF16 ? 2 : 4;
+    const size_t need = dd::verify_workspace_bytes(B * G, V, eb);
+    if (static_scratch) {
+        if (need > kStaticScratchBytes) return DD_ERR_WORKSPACE;  // more partial states than the static array holds
+        workspace = nullptr;
+        workspace_bytes = need;
+        if (need > 0 && (rc = scratch_of_current_device(&workspace)) != DD_OK) return rc;
+    }
+    rc = check_workspace(workspace, workspace_bytes, need);
     if (rc != DD_OK) return rc;
-    const hipError_t e = dd::launch_verify(kl ? logits_d : nullptr, logits_v, mask, (int)mode, threshold, seed,
+    const bool kl = (mode == DD_KL_THRESH || mode == DD_KL_PROB || mode == DD_KL_TOPK);
+    const hipError_t e = dd::launch_verify(kl ? logits_d : nullptr, logits_v, mask, mode, threshold, seed,
                                            out_mask, out_tokens, out_scores, B, G, V, logit_dtype == DD_BF16,
                                            workspace, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+extern "C" {
+
+int dd_verify_remask(const void *logits_d, const void *logits_v, const uint8_t *mask,
+                     dd_mode mode, float threshold, uint64_t seed,
+                     uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
+                     int B, int G, int V, dd_dtype logit_dtype,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return verify_remask(logits_d, logits_v, mask, (int)mode, threshold, seed, out_mask, out_tokens, out_scores, B, G, V,
+                         (int)logit_dtype, workspace, workspace_bytes, stream, false);
 }
 
 int dd_verify_remask_static(const void *logits_d, const void *logits_v, const uint8_t *mask,
@@ -345,17 +382,10 @@ int dd_verify_remask_static(const void *logits_d, const void *logits_v, const ui
                             uint8_t *out_mask, int32_t *out_tokens, float *out_scores,
                             int B, int G, int V, dd_dtype logit_dtype, void *stream)
 {
-    const size_t need = dd_verify_remask_workspace_bytes(B, G, V, logit_dtype);
-    if (need > kStaticScratchBytes) return DD_ERR_WORKSPACE;      // more partial states than the static array holds
-    void *ws = nullptr;
-    if (need > 0) {
-        const int rc = scratch_of_current_device(&ws);
-        if (rc != DD_OK) return rc;
-    }
     // every partial state the finishing kernel reads is written by the streaming kernel of the same call:
-    // nothing in the array has to be cleared between calls
-    return dd_verify_remask(logits_d, logits_v, mask, mode, threshold, seed, out_mask, out_tokens, out_scores,
-                            B, G, V, logit_dtype, ws, need, stream);
+    // nothing in the static array has to be cleared between calls
+    return verify_remask(logits_d, logits_v, mask, (int)mode, threshold, seed, out_mask, out_tokens, out_scores, B, G, V,
+                         (int)logit_dtype, nullptr, 0, stream, true);
 }
 
 size_t dd_unmask_workspace_bytes(int B, int G, int V, dd_dtype logit_dtype)
