@@ -49,6 +49,8 @@ def lib():
         _lib.ora_block_attention_cached.restype = C.c_int
         _lib.ora_block_attention_cached.argtypes = [vp, vp, vp, dp, C.c_int, C.c_int, vp, vp] + [C.c_int] * 7 + \
             [vp, vp, vp, C.c_int]
+        _lib.ora_attention_vs.restype = C.c_int
+        _lib.ora_attention_vs.argtypes = [vp, vp, vp, dp] + [C.c_int] * 8 + [vp, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int]
         _lib.ora_verify_scores.restype = C.c_int
         _lib.ora_verify_scores.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, vp, C.c_int, dp, dp, ip]
         _lib.ora_philox4x32_10.restype = None
@@ -106,9 +108,10 @@ def decode_bf16(bits: int) -> float:
     return lib().ora_decode_bf16(int(bits))
 
 
-def bidir_attention(Q, K, V, qk_dtype: int, v_dtype: int, q_scale=None, k_scale=None, rows=None) -> np.ndarray:
+def bidir_attention(Q, K, V, qk_dtype: int, v_dtype: int, q_scale=None, k_scale=None, rows=None, v_scale=None) -> np.ndarray:
     """Full bidirectional attention.  Q [B,H,N,d], K,V [B,Hkv,N,d] in storage form.
-    rows=None -> O [B,H,N,d] fp64;  rows=[(b,h,i),...] -> O [len(rows), d]."""
+    rows=None -> O [B,H,N,d] fp64;  rows=[(b,h,i),...] -> O [len(rows), d].
+    v_scale [B*Hkv] (optional): multiplier of the decoded values of V (fp8 V is stored like fp8 K)."""
     Q = _chk(Q, qk_dtype, "Q"); K = _chk(K, qk_dtype, "K"); V = _chk(V, v_dtype, "V")
     B, H, N, d = Q.shape
     Hkv = K.shape[1]
@@ -117,6 +120,14 @@ def bidir_attention(Q, K, V, qk_dtype: int, v_dtype: int, q_scale=None, k_scale=
     ks = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32).reshape(B * Hkv)
     r = _rows3(rows)
     O = np.empty((B, H, N, d) if r is None else (len(r), d), dtype=np.float64)
+    if v_scale is not None:
+        vs = np.ascontiguousarray(v_scale, dtype=np.float32).reshape(B * Hkv)
+        rc = lib().ora_attention_vs(_ptr(Q), _ptr(K), _ptr(V), O.ctypes.data_as(C.POINTER(C.c_double)),
+                                    B, H, Hkv, N, N, d, qk_dtype, v_dtype, _ptr(qs), _ptr(ks), _ptr(vs),
+                                    None, None, 0, 0, _ptr(r), 0 if r is None else len(r))
+        if rc != 0:
+            raise ValueError("oracle bidir_attention: bad argument")
+        return O
     rc = lib().ora_bidir_attention(_ptr(Q), _ptr(K), _ptr(V), O.ctypes.data_as(C.POINTER(C.c_double)),
                                    B, H, Hkv, N, d, qk_dtype, v_dtype, _ptr(qs), _ptr(ks),
                                    _ptr(r), 0 if r is None else len(r))
@@ -126,7 +137,7 @@ def bidir_attention(Q, K, V, qk_dtype: int, v_dtype: int, q_scale=None, k_scale=
 
 
 def block_attention_cached(Qblk, Kc, Vc, block_start: int, qk_dtype: int, v_dtype: int, Kblk=None, Vblk=None,
-                           q_scale=None, k_scale=None, rows=None) -> np.ndarray:
+                           q_scale=None, k_scale=None, rows=None, v_scale=None) -> np.ndarray:
     """Active-block queries over cached K/V.  Qblk [B,H,bl,d]; Kc,Vc [B,Hkv,N,d];
     optional Kblk,Vblk [B,Hkv,bl,d] replace cache rows [block_start, block_start+bl)."""
     Qblk = _chk(Qblk, qk_dtype, "Qblk"); Kc = _chk(Kc, qk_dtype, "Kc"); Vc = _chk(Vc, v_dtype, "Vc")
@@ -140,6 +151,16 @@ def block_attention_cached(Qblk, Kc, Vc, block_start: int, qk_dtype: int, v_dtyp
     ks = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32).reshape(B * Hkv)
     r = _rows3(rows)
     O = np.empty((B, H, bl, d) if r is None else (len(r), d), dtype=np.float64)
+    if v_scale is not None:
+        if not (0 <= block_start and block_start + bl <= N):
+            raise ValueError("oracle block_attention_cached: bad argument")
+        vs = np.ascontiguousarray(v_scale, dtype=np.float32).reshape(B * Hkv)
+        rc = lib().ora_attention_vs(_ptr(Qblk), _ptr(Kc), _ptr(Vc), O.ctypes.data_as(C.POINTER(C.c_double)),
+                                    B, H, Hkv, bl, N, d, qk_dtype, v_dtype, _ptr(qs), _ptr(ks), _ptr(vs),
+                                    _ptr(Kblk), _ptr(Vblk), block_start, bl, _ptr(r), 0 if r is None else len(r))
+        if rc != 0:
+            raise ValueError("oracle block_attention_cached: bad argument")
+        return O
     rc = lib().ora_block_attention_cached(_ptr(Qblk), _ptr(Kc), _ptr(Vc), O.ctypes.data_as(C.POINTER(C.c_double)),
                                           block_start, bl, _ptr(Kblk), _ptr(Vblk), B, H, Hkv, N, d,
                                           qk_dtype, v_dtype, _ptr(qs), _ptr(ks), _ptr(r), 0 if r is None else len(r))

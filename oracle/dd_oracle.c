@@ -113,20 +113,21 @@ static void attend_one_row(const double *q, const double *Kd, const double *Vd, 
  * block_start <= j < block_start + block_len, else from the (cache) tensors K, V. */
 static void gather_kv(double *Kd, double *Vd, const void *K, const void *V, const void *Kblk, const void *Vblk,
                       int b, int h, int H, int Hkv, int N, int d, int qk_dtype, int v_dtype,
-                      const float *k_scale, int block_start, int block_len)
+                      const float *k_scale, const float *v_scale, int block_start, int block_len)
 {
     int kvh = (int)(((long)h * Hkv) / H);
     double ks = k_scale ? (double)k_scale[(size_t)b * Hkv + kvh] : 1.0;
+    double vs = v_scale ? (double)v_scale[(size_t)b * Hkv + kvh] : 1.0;   /* real value = scale x decoded value */
     for (int j = 0; j < N; ++j) {
         int in_block = Kblk && j >= block_start && j < block_start + block_len;
         if (in_block) {
             size_t off = (((size_t)b * Hkv + kvh) * block_len + (size_t)(j - block_start)) * d;
             decode_run(Kd + (size_t)j * d, Kblk, off, d, qk_dtype, ks);
-            decode_run(Vd + (size_t)j * d, Vblk, off, d, v_dtype, 1.0);
+            decode_run(Vd + (size_t)j * d, Vblk, off, d, v_dtype, vs);
         } else {
             size_t off = (((size_t)b * Hkv + kvh) * N + (size_t)j) * d;
             decode_run(Kd + (size_t)j * d, K, off, d, qk_dtype, ks);
-            decode_run(Vd + (size_t)j * d, V, off, d, v_dtype, 1.0);
+            decode_run(Vd + (size_t)j * d, V, off, d, v_dtype, vs);
         }
     }
 }
@@ -137,11 +138,29 @@ static void gather_kv(double *Kd, double *Vd, const void *K, const void *V, cons
  * rows != NULL : rows is [nrows][3] = (b,h,i); O is [nrows][d].
  * returns 0, or -1 on a bad argument.
  */
+int ora_attention_vs(const void *Q, const void *K, const void *V, double *O,
+                     int B, int H, int Hkv, int Nq, int N, int d, int qk_dtype, int v_dtype,
+                     const float *q_scale, const float *k_scale, const float *v_scale,
+                     const void *Kblk, const void *Vblk, int block_start, int block_len,
+                     const int32_t *rows, int nrows);
+
 int ora_attention(const void *Q, const void *K, const void *V, double *O,
                   int B, int H, int Hkv, int Nq, int N, int d, int qk_dtype, int v_dtype,
                   const float *q_scale, const float *k_scale,
                   const void *Kblk, const void *Vblk, int block_start, int block_len,
                   const int32_t *rows, int nrows)
+{
+    return ora_attention_vs(Q, K, V, O, B, H, Hkv, Nq, N, d, qk_dtype, v_dtype, q_scale, k_scale, NULL,
+                            Kblk, Vblk, block_start, block_len, rows, nrows);
+}
+
+/* The same with a per-(batch, kv head) multiplier of the decoded values of V as well (v_scale [B*Hkv] or NULL):
+ * the second precision workload stores V in e4m3 like K, one fp32 scale per head. */
+int ora_attention_vs(const void *Q, const void *K, const void *V, double *O,
+                     int B, int H, int Hkv, int Nq, int N, int d, int qk_dtype, int v_dtype,
+                     const float *q_scale, const float *k_scale, const float *v_scale,
+                     const void *Kblk, const void *Vblk, int block_start, int block_len,
+                     const int32_t *rows, int nrows)
 {
     if (!Q || !K || !V || !O || B < 0 || H <= 0 || Hkv <= 0 || H % Hkv || Nq < 0 || N <= 0 || d <= 0)
         return -1;
@@ -163,7 +182,7 @@ int ora_attention(const void *Q, const void *K, const void *V, double *O,
             double *Vd = malloc(sizeof(double) * (size_t)N * d);
             double *sc = malloc(sizeof(double) * (size_t)N);
             double *q = malloc(sizeof(double) * (size_t)d);
-            gather_kv(Kd, Vd, K, V, Kblk, Vblk, b, h, H, Hkv, N, d, qk_dtype, v_dtype, k_scale, block_start, block_len);
+            gather_kv(Kd, Vd, K, V, Kblk, Vblk, b, h, H, Hkv, N, d, qk_dtype, v_dtype, k_scale, v_scale, block_start, block_len);
             double qs = q_scale ? (double)q_scale[(size_t)b * H + h] : 1.0;
             decode_run(q, Q, (((size_t)b * H + h) * Nq + (size_t)i) * d, d, qk_dtype, qs);
             attend_one_row(q, Kd, Vd, N, d, sc, O + (size_t)r * d);
@@ -182,7 +201,7 @@ int ora_attention(const void *Q, const void *K, const void *V, double *O,
             double *Vd = malloc(sizeof(double) * (size_t)N * d);
             double *sc = malloc(sizeof(double) * (size_t)N);
             double *q = malloc(sizeof(double) * (size_t)d);
-            gather_kv(Kd, Vd, K, V, Kblk, Vblk, b, h, H, Hkv, N, d, qk_dtype, v_dtype, k_scale, block_start, block_len);
+            gather_kv(Kd, Vd, K, V, Kblk, Vblk, b, h, H, Hkv, N, d, qk_dtype, v_dtype, k_scale, v_scale, block_start, block_len);
             double qs = q_scale ? (double)q_scale[(size_t)b * H + h] : 1.0;
             int i1 = (ch + 1) * chunk < Nq ? (ch + 1) * chunk : Nq;
             for (int i = ch * chunk; i < i1; ++i) {

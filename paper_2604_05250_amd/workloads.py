@@ -172,15 +172,15 @@ def attention_inputs(cfg: StepConfig, seed: int = 0) -> dict:
     """Q [B,H,N,d], K,V [B,Hkv,N,d] for the verifier's full attention."""
     Q, qs = _head_tensor(seed, _T_Q, cfg.B, cfg.H, cfg.N, cfg.d, cfg.qk_dtype, cfg.qk_prescale)
     K, ks = _head_tensor(seed, _T_K, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.qk_dtype, cfg.qk_prescale)
-    V, _ = _head_tensor(seed, _T_V, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.v_dtype, cfg.qk_prescale)
-    return {"Q": Q, "K": K, "V": V, "q_scale": qs, "k_scale": ks}
+    V, vs = _head_tensor(seed, _T_V, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.v_dtype, cfg.qk_prescale)
+    return {"Q": Q, "K": K, "V": V, "q_scale": qs, "k_scale": ks, "v_scale": vs}
 
 
 def cache_inputs(cfg: StepConfig, seed: int = 0) -> dict:
     """Stale drafter cache Kc, Vc [B,Hkv,N,d] (independent of the current K, V)."""
     Kc, ks = _head_tensor(seed, _T_KC, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.qk_dtype, cfg.qk_prescale)
-    Vc, _ = _head_tensor(seed, _T_VC, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.v_dtype, cfg.qk_prescale)
-    return {"Kc": Kc, "Vc": Vc, "k_scale": ks}
+    Vc, vs = _head_tensor(seed, _T_VC, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.v_dtype, cfg.qk_prescale)
+    return {"Kc": Kc, "Vc": Vc, "k_scale": ks, "v_scale": vs}
 
 
 def block_start(cfg: StepConfig, step: int) -> int:
@@ -188,9 +188,10 @@ def block_start(cfg: StepConfig, step: int) -> int:
     return cfg.prompt + (step % (cfg.G // cfg.bl)) * cfg.bl
 
 
-def block_inputs(cfg: StepConfig, seed: int = 0, step: int = 0, k_scale: Optional[np.ndarray] = None) -> dict:
+def block_inputs(cfg: StepConfig, seed: int = 0, step: int = 0, k_scale: Optional[np.ndarray] = None,
+                 v_scale: Optional[np.ndarray] = None) -> dict:
     """Fresh active-block tensors for draft step `step`: Qblk [B,H,bl,d], Kblk,Vblk [B,Hkv,bl,d].
-    With fp8 K the block rows are quantised with the *cache's* per-head scale (`k_scale`),
+    With fp8 K (V) the block rows are quantised with the *cache's* per-head scale (`k_scale`, `v_scale`),
     since one scale per (b, kv head) covers cached and fresh rows alike."""
     Qb, qs = _head_tensor(seed, _T_QBLK, cfg.B, cfg.H, cfg.bl, cfg.d, cfg.qk_dtype, cfg.qk_prescale, salt=step + 1)
     if cfg.qk_dtype == FP8_E4M3:
@@ -200,7 +201,13 @@ def block_inputs(cfg: StepConfig, seed: int = 0, step: int = 0, k_scale: Optiona
         Kb = f32_to_e4m3_bits(Kf / k_scale[:, :, None, None].astype(np.float32))
     else:
         Kb, _ = _head_tensor(seed, _T_KBLK, cfg.B, cfg.Hkv, cfg.bl, cfg.d, cfg.qk_dtype, cfg.qk_prescale, salt=step + 1)
-    Vb, _ = _head_tensor(seed, _T_VBLK, cfg.B, cfg.Hkv, cfg.bl, cfg.d, cfg.v_dtype, cfg.qk_prescale, salt=step + 1)
+    if cfg.v_dtype == FP8_E4M3:
+        if v_scale is None:
+            raise ValueError("fp8 block V needs the cache's v_scale")
+        Vf, _ = _head_tensor(seed, _T_VBLK, cfg.B, cfg.Hkv, cfg.bl, cfg.d, F32, cfg.qk_prescale, salt=step + 1)
+        Vb = f32_to_e4m3_bits(Vf / v_scale[:, :, None, None].astype(np.float32))
+    else:
+        Vb, _ = _head_tensor(seed, _T_VBLK, cfg.B, cfg.Hkv, cfg.bl, cfg.d, cfg.v_dtype, cfg.qk_prescale, salt=step + 1)
     return {"Qblk": Qb, "Kblk": Kb, "Vblk": Vb, "q_scale": qs, "block_start": block_start(cfg, step)}
 
 

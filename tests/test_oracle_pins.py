@@ -691,3 +691,39 @@ def test_workload_shapes_and_determinism():
     assert blk["Kblk"].shape == (2, 2, 16, 64) and blk["block_start"] == 48
     m3 = wl.verify_inputs(wl.custom_config(B=4, G=500, V=8, decoded_frac=0.3), 0)["mask"]
     assert 0.6 < m3.mean() < 0.8                          # ~70 % still masked
+
+
+# ------------------------------------------------------------------ fp8 V (second precision workload)
+def test_fp8_v_with_a_scale_is_attention_on_the_decoded_values():
+    # V in e4m3 with one power-of-two scale per (batch, kv head): scale x decoded value is exact in fp32, so the
+    # call must give, bit for bit, what the fp32-V path gives on those values; Q/K stay bf16
+    cfg = wl.custom_config(B=2, H=4, Hkv=2, N=37, d=64, prompt=0, G=37, v_dtype=FP8_E4M3)
+    inp = wl.attention_inputs(cfg, seed=3)
+    assert inp["V"].dtype == np.uint8 and inp["v_scale"].shape == (2, 2)
+    vs = np.array([[0.5, 2.0], [0.125, 1.0]], np.float32)
+    got = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], BF16, FP8_E4M3, v_scale=vs)
+    table = np.array([oracle.decode_e4m3(c) for c in range(256)])
+    Vdec = (table[inp["V"]] * vs[:, :, None, None]).astype(np.float32)
+    assert np.array_equal(Vdec.astype(np.float64), table[inp["V"]] * vs[:, :, None, None].astype(np.float64))
+    Q32 = wl.bf16_bits_to_f32(inp["Q"]); K32 = wl.bf16_bits_to_f32(inp["K"])
+    want = oracle.bidir_attention(Q32, K32, Vdec, F32, F32)
+    assert np.array_equal(got, want)
+    # the scale is a multiplier of V and nothing else: doubling it doubles the output exactly, and identical keys
+    # give scale x mean(decoded V) whatever the scale is
+    got2 = oracle.bidir_attention(inp["Q"], inp["K"], inp["V"], BF16, FP8_E4M3, v_scale=2 * vs)
+    assert np.array_equal(got2, 2 * got)
+    odd = np.array([[0.3, 1.7], [0.011, 5.5]], np.float32)
+    K1 = np.broadcast_to(inp["K"][:, :, :1], inp["K"].shape).copy()
+    flat = oracle.bidir_attention(inp["Q"], K1, inp["V"], BF16, FP8_E4M3, v_scale=odd)
+    mean = (table[inp["V"]] * odd[:, :, None, None].astype(np.float64)).mean(axis=2, keepdims=True)
+    assert np.abs(flat - np.repeat(mean, 2, axis=1)).max() < 1e-12
+    # block form: same rows as the full call when the cache is current, the block's fresh rows share the cache's scale
+    bs, bl = 16, 8
+    Qb = np.ascontiguousarray(inp["Q"][:, :, bs:bs + bl])
+    blk = oracle.block_attention_cached(Qb, inp["K"], inp["V"], bs, BF16, FP8_E4M3, v_scale=vs)
+    assert np.array_equal(blk, got[:, :, bs:bs + bl])
+    Vb = np.ascontiguousarray(inp["V"][:, :, bs:bs + bl])
+    Kb = np.ascontiguousarray(inp["K"][:, :, bs:bs + bl])
+    stale_V = inp["V"].copy(); stale_V[:, :, bs:bs + bl] = 0x7E          # 448: would dominate if it were read
+    blk2 = oracle.block_attention_cached(Qb, inp["K"], stale_V, bs, BF16, FP8_E4M3, Kb, Vb, v_scale=vs)
+    assert np.array_equal(blk2, blk)
