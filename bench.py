@@ -103,6 +103,9 @@ def parse():
     ap.add_argument("--no-warm", action="store_true",
                     help="skip the additional warm-cache repetition of the steps (profiling: every launch in the "
                          "trace then belongs to the rotated, cold-cache steps)")
+    ap.add_argument("--fp8v", action="store_true",
+                    help="second precision workload: the configuration with Q, K and V all stored as e4m3 codes with "
+                         "per-head scales (dd_bidir_attention_fp8v / dd_block_attention_cached_fp8v); meant for --config 5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="time only the configuration named by --config (the default run also times the other benchmark "
@@ -130,7 +133,7 @@ def main():
         light.steps, light.warmup, light.prewarm_ms = max(5, args.steps // 4), 3, min(args.prewarm_ms, 150.0)
         light.no_graph = light.no_warm = light.no_cpu_baseline = True
         light.layers, light.calib_copy_mb, light.verify_mode = 0, 0, None
-        light.parts, light.window, light.refresh_last = "block,attention,verify", 0, False
+        light.parts, light.window, light.refresh_last, light.fp8v = "block,attention,verify", 0, False, False
         out["per_config"] = {}
         for cid in (2, 4, 5, 3):
             if cid == args.config:
@@ -155,6 +158,10 @@ def run_config(args, config_id):
 
     dev = torch.device("cuda:0")
     cfg = wl.CONFIGS[config_id]
+    fp8v = bool(getattr(args, "fp8v", False))
+    if fp8v:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name=cfg.name + "_fp8v", qk_dtype=wl.FP8_E4M3, v_dtype=wl.FP8_E4M3)
     mode, tau = cfg.modes[-1]
     if args.verify_mode is not None:                     # another rule of the same call on the same inputs
         mode = {v: k for k, v in wl.MODE_NAMES.items()}[args.verify_mode]
@@ -172,7 +179,7 @@ def run_config(args, config_id):
     att = wl.attention_inputs(cfg, args.seed)
     cache = wl.cache_inputs(cfg, args.seed)
     ver = wl.verify_inputs(cfg, args.seed)
-    blocks = [wl.block_inputs(cfg, args.seed, k, k_scale=cache["k_scale"]) for k in range(cfg.K)]
+    blocks = [wl.block_inputs(cfg, args.seed, k, k_scale=cache["k_scale"], v_scale=cache["v_scale"]) for k in range(cfg.K)]
 
     eb_qk, eb_v, eb_l = wl.elem_bytes(cfg.qk_dtype), wl.elem_bytes(cfg.v_dtype), wl.elem_bytes(cfg.logit_dtype)
     q_elems = cfg.B * cfg.H * cfg.N * cfg.d
@@ -197,10 +204,11 @@ def run_config(args, config_id):
     caches = [{"Kc": up(cache["Kc"]), "Vc": up(cache["Vc"])} for _ in range(n_caches)]
     qs, ks = up(att["q_scale"]), up(att["k_scale"])
     kcs = up(cache["k_scale"])
+    vs, vcs = up(att["v_scale"]), up(cache["v_scale"])
     mask = up(ver["mask"])
     blk_dev = [{"Q": up(b["Qblk"]), "K": up(b["Kblk"]), "V": up(b["Vblk"]), "qs": up(b["q_scale"]),
                 "bs": b["block_start"]} for b in blocks]
-    o_dtype = sets[0]["V"].dtype
+    o_dtype = torch.int16 if fp8v else sets[0]["V"].dtype
     O = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=o_dtype, device=dev)
     Oblk = torch.empty((cfg.B, cfg.H, cfg.bl, cfg.d), dtype=o_dtype, device=dev)
     out_mask = torch.empty(cfg.P, dtype=torch.uint8, device=dev)
@@ -244,7 +252,10 @@ def run_config(args, config_id):
             kc = caches[0 if one_cache else (i * cfg.K + k) % n_caches]
             kw = dict(O=Oblk, Kblk=b["K"], Vblk=b["V"], q_scale=b["qs"], k_scale=kcs, qk_dtype=cfg.qk_dtype,
                       v_dtype=cfg.v_dtype)
-            if win:
+            if fp8v:
+                dd.dd_block_attention_cached_fp8v(b["Q"], kc["Kc"], kc["Vc"], b["bs"], b["qs"], kcs, vcs, O=Oblk,
+                                                  Kblk=b["K"], Vblk=b["V"])
+            elif win:
                 w0 = min(max(0, b["bs"] + cfg.bl // 2 - win // 2), cfg.N - win)
                 dd.dd_block_attention_window(b["Q"], kc["Kc"], kc["Vc"], b["bs"], w0, win, **kw)
             elif args.refresh_last and k == cfg.K - 1:
@@ -257,7 +268,9 @@ def run_config(args, config_id):
             dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
                          out_mask=um_mask, out_tokens=um_tok, out_conf=um_conf, logit_dtype=cfg.logit_dtype)
         if marks: marks[4].record()
-        if "attention" in parts:
+        if "attention" in parts and fp8v:
+            dd.dd_bidir_attention_fp8v(s["Q"], s["K"], s["V"], qs, ks, vs, O=O)
+        elif "attention" in parts:
             dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
                                   qk_dtype=cfg.qk_dtype, v_dtype=cfg.v_dtype)
         if marks: marks[2].record()
@@ -362,7 +375,10 @@ def run_config(args, config_id):
         return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false>"
 
     # the peak the attention call is priced against: each contraction at the peak of its own operand type
-    if cfg.qk_dtype == wl.F32:
+    if fp8v:
+        attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, true>", "mfma", PEAK_BF16_TFLOPS
+        attn_peak_note = "fp8 operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
+    elif cfg.qk_dtype == wl.F32:
         attn_kernel, attn_bound, attn_peak = "attn_f32_kernel", "alu", PEAK_FP32_VALU_TFLOPS
         attn_peak_note = "fp32 inputs: vector ALUs (no fp32 MFMA path is used), 157.3 TFLOP/s"
     elif cfg.qk_dtype == wl.FP8_E4M3:
@@ -378,7 +394,7 @@ def run_config(args, config_id):
         "metric": METRIC, "value": round(attn_tflops, 3), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {wl.F32: "f32", wl.BF16: "bf16", wl.FP8_E4M3: "fp8_e4m3(QK)+bf16(V)"}[cfg.qk_dtype],
+        "dtype": "fp8_e4m3(QKV)" if fp8v else {wl.F32: "f32", wl.BF16: "bf16", wl.FP8_E4M3: "fp8_e4m3(QK)+bf16(V)"}[cfg.qk_dtype],
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
                                f"drafter block_len={cfg.bl} x K={cfg.K} steps, verify P={cfg.P} x V={cfg.V} "
@@ -462,7 +478,7 @@ def run_config(args, config_id):
         def run_attn(n):
             t0 = time.perf_counter()
             oracle.bidir_attention(att_host["Q"], att_host["K"], att_host["V"], cfg.qk_dtype, cfg.v_dtype,
-                                   att_host["q_scale"], att_host["k_scale"], rows=rows(n))
+                                   att_host["q_scale"], att_host["k_scale"], rows=rows(n), v_scale=att_host["v_scale"])
             return time.perf_counter() - t0
         n0 = 64
         t0 = run_attn(n0)

@@ -136,6 +136,29 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
                                                  dd_dtype qk_dtype, dd_dtype v_dtype);
 
 /*
+ * Second precision workload: the two attention calls with V stored like K - OCP e4m3 codes with one fp32 scale per
+ * (batch, kv head), real value = scale x decoded code - which halves the bytes of V in memory, the quantity the
+ * drafter's call is bound by.  (The paper fixes no storage precision; Sec. 4.1 runs stock models.)  Same formulas
+ * as dd_bidir_attention / dd_block_attention_cached:
+ *   Q, K, V (and Qblk, Kc, Vc, Kblk, Vblk): DD_FP8_E4M3;   O: DD_BF16;   q_scale [B*H], k_scale, v_scale [B*Hkv]:
+ *   all required; the block's fresh rows Kblk / Vblk use the cache's k_scale / v_scale.
+ * Arithmetic: every code is decoded exactly (e4m3 -> bf16) on its way into LDS, the products run on the bf16
+ * matrix cores with fp32 accumulation, the weights are rounded to bf16, v_scale multiplies the output once.
+ * dd_bidir_attention_fp8v needs no workspace; the block call's comes from its own query function.
+ * Shapes, alignment and errors as for the calls above (a missing scale: DD_ERR_NULL).
+ */
+int dd_bidir_attention_fp8v(const void *Q, const void *K, const void *V, void *O,
+                            int B, int H, int Hkv, int N, int d,
+                            const float *q_scale, const float *k_scale, const float *v_scale, void *stream);
+int dd_block_attention_cached_fp8v(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                                   int block_start, int block_len,
+                                   const void *Kblk, const void *Vblk,
+                                   int B, int H, int Hkv, int N, int d,
+                                   const float *q_scale, const float *k_scale, const float *v_scale,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+size_t dd_block_attention_cached_fp8v_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d);
+
+/*
  * The same call when the block is complete (Sec. 2.3: cached activations are reused across the denoising
  * steps of a block and refreshed at block granularity): the attention exactly as
  * dd_block_attention_cached computes it with Kblk/Vblk given, and in the same call

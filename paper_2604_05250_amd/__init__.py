@@ -52,6 +52,12 @@ def lib():
     L.dd_block_attention_cached.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, i, i, vp, vp, vp, sz, vp]
     L.dd_block_attention_cached_workspace_bytes.restype = sz
     L.dd_block_attention_cached_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
+    L.dd_bidir_attention_fp8v.restype = i
+    L.dd_bidir_attention_fp8v.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, vp, vp]
+    L.dd_block_attention_cached_fp8v.restype = i
+    L.dd_block_attention_cached_fp8v.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, vp, vp, vp, vp, sz, vp]
+    L.dd_block_attention_cached_fp8v_workspace_bytes.restype = sz
+    L.dd_block_attention_cached_fp8v_workspace_bytes.argtypes = [i, i, i, i, i, i]
     L.dd_verify_remask.restype = i
     L.dd_verify_remask.argtypes = [vp, vp, vp, i, C.c_float, C.c_uint64, vp, vp, vp, i, i, i, i, vp, sz, vp]
     L.dd_verify_remask_workspace_bytes.restype = sz
@@ -90,7 +96,8 @@ EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attentio
            "dd_verify_scores", "dd_verify_scores_workspace_bytes",
            "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
            "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows",
-           "dd_block_attention_batched", "dd_block_attention_batched_workspace_bytes")
+           "dd_block_attention_batched", "dd_block_attention_batched_workspace_bytes",
+           "dd_bidir_attention_fp8v", "dd_block_attention_cached_fp8v", "dd_block_attention_cached_fp8v_workspace_bytes")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -253,6 +260,51 @@ def dd_block_attention_cached(Qblk, Kc, Vc, block_start: int, O=None, Kblk=None,
             _dev(ws, "workspace"), wsn, _stream())
     if rc != 0:
         raise DDError(rc, name)
+    return O
+
+
+def dd_bidir_attention_fp8v(Q, K, V, q_scale, k_scale, v_scale, O=None):
+    """Verifier attention with Q, K and V all stored as e4m3 codes (uint8) and per-head fp32 scales -> O bf16
+    (as int16 bit patterns unless O is given)."""
+    torch = _torch()
+    B, H, N, d = Q.shape
+    Hkv = K.shape[1]
+    if tuple(K.shape) != (B, Hkv, N, d) or tuple(V.shape) != (B, Hkv, N, d):
+        raise ValueError("K/V shape must be [B,Hkv,N,d] matching Q")
+    for t, what in ((Q, "Q"), (K, "K"), (V, "V")):
+        if t.element_size() != 1:
+            raise TypeError(f"{what}: one byte per element (e4m3 codes) expected")
+    if O is None:
+        O = torch.empty((B, H, N, d), dtype=torch.int16, device=V.device)
+    rc = lib().dd_bidir_attention_fp8v(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), B, H, Hkv, N, d,
+                                       _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"), _dev(v_scale, "v_scale"),
+                                       _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_bidir_attention_fp8v")
+    return O
+
+
+def dd_block_attention_cached_fp8v(Qblk, Kc, Vc, block_start: int, q_scale, k_scale, v_scale, O=None, Kblk=None, Vblk=None):
+    """Drafter attention with every operand stored as e4m3 codes; shapes as for dd_block_attention_cached -> O bf16."""
+    torch = _torch()
+    B, H, bl, d = Qblk.shape
+    _, Hkv, N, _ = Kc.shape
+    if tuple(Kc.shape) != (B, Hkv, N, d) or tuple(Vc.shape) != (B, Hkv, N, d):
+        raise ValueError("Kc/Vc shape must be [B,Hkv,N,d]")
+    if Kblk is not None and (tuple(Kblk.shape) != (B, Hkv, bl, d) or tuple(Vblk.shape) != (B, Hkv, bl, d)):
+        raise ValueError("Kblk/Vblk shape must be [B,Hkv,block_len,d]")
+    for t, what in ((Qblk, "Qblk"), (Kc, "Kc"), (Vc, "Vc")):
+        if t.element_size() != 1:
+            raise TypeError(f"{what}: one byte per element (e4m3 codes) expected")
+    if O is None:
+        O = torch.empty((B, H, bl, d), dtype=torch.int16, device=Vc.device)
+    ws, wsn = _workspace(lib().dd_block_attention_cached_fp8v_workspace_bytes(bl, B, H, Hkv, N, d), Qblk.device)
+    rc = lib().dd_block_attention_cached_fp8v(_dev(Qblk, "Qblk"), _dev(Kc, "Kc"), _dev(Vc, "Vc"), _dev(O, "O"),
+                                              int(block_start), bl, _dev(Kblk, "Kblk"), _dev(Vblk, "Vblk"),
+                                              B, H, Hkv, N, d, _dev(q_scale, "q_scale"), _dev(k_scale, "k_scale"),
+                                              _dev(v_scale, "v_scale"), _dev(ws, "workspace"), wsn, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_block_attention_cached_fp8v")
     return O
 
 

@@ -17,6 +17,7 @@ struct AttnKernelArgs {
     float *part_o;             // [rows][splits][d] unnormalised partial outputs (splits > 1)
     float *part_ml;            // [rows][splits][2] (running max in log2 units, partial sum)
     const float *q_scale, *k_scale;
+    const float *v_scale;      // [B*Hkv] or nullptr: multiplier of the decoded V values (fp8 V)
     int B, H, Hkv, Nq, N;
     int kv_stride;             // rows between consecutive (batch, kv head) in K and V (N unless the call sees a window)
     int group;                 // H / Hkv

@@ -87,7 +87,9 @@ constexpr float kRescaleSlack = 8.0f;
 // BLOCK = false: verifier attention (all rows of a head attend all keys, O written directly).
 // BLOCK = true : drafter block attention (key rows of the active block may come from the fresh
 //                block tensors, the key range may be split, partial states go to the workspace).
-template <int D, bool FP8, bool BLOCK>
+// V8: V (and Vblk) are fp8 e4m3 as well, decoded exactly to bf16 on their way into LDS like K; their per-head
+//      scale multiplies the output once, at the end.
+template <int D, bool FP8, bool BLOCK, bool V8 = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKernelArgs a)
 {
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
@@ -97,6 +99,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
     constexpr int KELEM = FP8 ? 1 : 2;               // bytes per K element in memory
+    constexpr int VELEM = V8 ? 1 : 2;                // bytes per V element in memory
     static_assert(KCH >= 1 && VTASKS <= kAttnThreads, "tile does not fit the staging scheme");
 
     __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // keys of task (g, e4): tile-local index (g/4)*32 + ((g/2)&1)*16 + 8*e4 + 4*(g&1) + e,  e = 0..3
     const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
     const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.kv_stride * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
-    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)(D * 2) + vt_dchunk * 16;
+    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)(D * VELEM) + vt_dchunk * (8 * VELEM);
 
     // address of key row j's chunk for this thread; rows past the range are clamped to the last
     // valid row (their scores are masked to -inf, their values multiply a zero probability)
@@ -171,8 +174,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         j = min(j, k_end - 1);
         if (BLOCK && (unsigned)j - (unsigned)bstart < (unsigned)a.block_len)
             return static_cast<const uint8_t *>(a.Vblk) +
-                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)(D * 2) + vt_dchunk * 16;
-        return v_base + (size_t)j * (D * 2);
+                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)(D * VELEM) + vt_dchunk * (8 * VELEM);
+        return v_base + (size_t)j * (D * VELEM);
     };
     // K is staged in windows of 64 keys that are offset by half a tile against the V tiles:
     // window w = keys [64w+32, 64w+96) relative to the range start.  A ring of 128 rows then always
@@ -196,7 +199,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         const int k0 = k_begin + t * TK;
         if (tid < VTASKS) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) vreg[e] = *reinterpret_cast<const uint4 *>(v_src(k0 + vt_key0 + e));
+            for (int e = 0; e < 4; ++e) {
+                if (V8) {
+                    const uint2 r = *reinterpret_cast<const uint2 *>(v_src(k0 + vt_key0 + e));
+                    vreg[e] = make_uint4(r.x, r.y, 0, 0);    // decoded when it is stored to LDS
+                } else {
+                    vreg[e] = *reinterpret_cast<const uint4 *>(v_src(k0 + vt_key0 + e));
+                }
+            }
         }
     };
     auto store_k = [&](const uint4 (&src)[KCH], int j0, int nch) {
@@ -213,10 +223,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     auto store_v = [&](int buf) {
         if (tid < VTASKS) {
             // 4 keys x 8 dims -> 8 dims x 4 keys
-            const unsigned r0[4] = {vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w};
-            const unsigned r1[4] = {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w};
-            const unsigned r2[4] = {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w};
-            const unsigned r3[4] = {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w};
+            uint4 vr[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vr[e] = V8 ? fp8x8_to_bf16x8(make_uint2(vreg[e].x, vreg[e].y)) : vreg[e];
+            const unsigned r0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
+            const unsigned r1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
+            const unsigned r2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
+            const unsigned r3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
             uint2 *vt2 = reinterpret_cast<uint2 *>(Vt[buf]);
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
@@ -411,8 +424,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     const float l_tot = half_swap_sum(l_run);
     if (!row_ok) return;
     // accumulator register r of chunk i holds dim 32*i + 8*(r/4) + 4*hh + (r%4) of this lane's query
+    const float vs = V8 ? a.v_scale[kv_head] : 1.0f;     // the decoded V values times this are the real ones
     if (!BLOCK || a.splits == 1) {
-        const float inv = 1.0f / l_tot;
+        const float inv = vs / l_tot;
         uint16_t *o = static_cast<uint16_t *>(a.O) + orow * D;
 #pragma unroll
         for (int i = 0; i < DC; ++i)
@@ -429,7 +443,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4)
                 *reinterpret_cast<float4 *>(po + i * 32 + q4 * 8 + hh * 4) =
-                    make_float4(acc[i][4 * q4], acc[i][4 * q4 + 1], acc[i][4 * q4 + 2], acc[i][4 * q4 + 3]);
+                    make_float4(acc[i][4 * q4] * vs, acc[i][4 * q4 + 1] * vs, acc[i][4 * q4 + 2] * vs, acc[i][4 * q4 + 3] * vs);
         if (hh == 0) {
             float *ml = a.part_ml + (orow * a.splits + sp) * 2;
             ml[0] = mc;
@@ -539,7 +553,7 @@ __global__ __launch_bounds__(256) void attn_combine_refresh_kernel(const float *
 void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int key_tile)
 {
     k.Q = a.Q; k.K = a.K; k.V = a.V; k.Kblk = a.Kblk; k.Vblk = a.Vblk; k.O = a.O;
-    k.q_scale = a.q_scale; k.k_scale = a.k_scale;
+    k.q_scale = a.q_scale; k.k_scale = a.k_scale; k.v_scale = a.v_scale;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.Nq = a.Nq; k.N = a.N;
     k.kv_stride = a.kv_stride > 0 ? a.kv_stride : a.N;
     k.group = a.H / a.Hkv;
@@ -569,6 +583,14 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
+    if (a.v_dtype == 2) {
+        // fp8 V (with fp8 Q/K): this file's kernel serves every shape of the workload
+        if (!blk) return a.d == 128 ? launch(attn_mfma_kernel<128, true, false, true>, grid, block, stream, k)
+                                    : launch(attn_mfma_kernel<64, true, false, true>, grid, block, stream, k);
+        e = a.d == 128 ? launch(attn_mfma_kernel<128, true, true, true>, grid, block, stream, k)
+                       : launch(attn_mfma_kernel<64, true, true, true>, grid, block, stream, k);
+        return e != hipSuccess ? e : finish_attention(a, k.splits, stream);
+    }
     if (!blk && (!fp8 || a.d == 128)) {
         // The wide-wave kernel (256 query rows per workgroup, one wave per SIMD; bf16, or fp8 Q/K with
         // d = 128) wins once there are enough row tiles to occupy the chip; below that smaller workgroups
@@ -634,11 +656,11 @@ static hipError_t launch_combine_refresh(const AttnArgs &a, bool merge, hipStrea
     if (merge_wgs + copy_wgs == 0) return hipSuccess;
     const dim3 grid((unsigned)(merge_wgs + copy_wgs)), block(256);
     if (copy_wgs == 0) {
-        if (a.v_dtype == 1)
+        if (a.v_dtype != 0)                 // bf16 output (V bf16 or fp8)
             return launch(attn_combine_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
         return launch(attn_combine_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d);
     }
-    if (a.v_dtype == 1)
+    if (a.v_dtype != 0)                 // bf16 output (V bf16 or fp8)
         return launch(attn_combine_refresh_kernel<true>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
     return launch(attn_combine_refresh_kernel<false>, grid, block, stream, po, pml, a.O, rows, a.splits, a.d, r);
 }

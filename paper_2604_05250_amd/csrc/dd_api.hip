@@ -34,14 +34,16 @@ int scratch_of_current_device(void **out)
 inline bool misaligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 int check_attention_common(int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
-                           const float *q_scale, const float *k_scale)
+                           const float *q_scale, const float *k_scale, const float *v_scale = nullptr)
 {
     if (B < 1 || H < 1 || Hkv < 1 || N < 1) return DD_ERR_SHAPE;
     if (H % Hkv != 0) return DD_ERR_SHAPE;
     if (d != 64 && d != 128) return DD_ERR_SHAPE;
     if ((double)B * H * N * d >= 1099511627776.0) return DD_ERR_SHAPE;
+    // (fp8 V - with fp8 Q/K - only through the entry points that carry its scale)
     const bool ok = (qk_dtype == DD_F32 && v_dtype == DD_F32) || (qk_dtype == DD_BF16 && v_dtype == DD_BF16) ||
-                    (qk_dtype == DD_FP8_E4M3 && v_dtype == DD_BF16);
+                    (qk_dtype == DD_FP8_E4M3 && v_dtype == DD_BF16) ||
+                    (qk_dtype == DD_FP8_E4M3 && v_dtype == DD_FP8_E4M3 && v_scale != nullptr);
     if (!ok) return DD_ERR_DTYPE;
     if (qk_dtype == DD_FP8_E4M3 && (!q_scale || !k_scale)) return DD_ERR_NULL;
     return DD_OK;
@@ -163,13 +165,14 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
                            int B, int H, int Hkv, int N, int d, dd_dtype qk_dtype, dd_dtype v_dtype,
                            const float *q_scale, const float *k_scale,
                            void *workspace, size_t workspace_bytes, void *stream, bool refresh,
-                           int win_start = 0, int win_len = 0, const int32_t *block_starts = nullptr)
+                           int win_start = 0, int win_len = 0, const int32_t *block_starts = nullptr,
+                           const float *v_scale = nullptr)
 {
     if (!Qblk || !Kc || !Vc || !O) return DD_ERR_NULL;
     if ((Kblk == nullptr) != (Vblk == nullptr)) return DD_ERR_NULL;
     if (refresh && !Kblk) return DD_ERR_NULL;
     if (refresh && block_len > (1 << 25)) return DD_ERR_SHAPE;   // the copy indexes a block's 16-byte chunks with 32 bits
-    int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale);
+    int rc = check_attention_common(B, H, Hkv, N, d, qk_dtype, v_dtype, q_scale, k_scale, v_scale);
     if (rc != DD_OK) return rc;
     if (block_start < 0 || block_len < 1 || (long)block_start + block_len > N) return DD_ERR_SHAPE;
     const int full_N = N;
@@ -178,7 +181,8 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
         // same kernels, K/V based at the window's first row, the cache's own row count as the stride
         if (win_start < 0 || win_len < 1 || (long)win_start + win_len > N) return DD_ERR_SHAPE;
         if (block_start < win_start || (long)block_start + block_len > (long)win_start + win_len) return DD_ERR_SHAPE;
-        const size_t ebk = qk_dtype == DD_F32 ? 4 : qk_dtype == DD_BF16 ? 2 : 1, ebv = v_dtype == DD_F32 ? 4 : 2;
+        const size_t ebk = qk_dtype == DD_F32 ? 4 : qk_dtype == DD_BF16 ? 2 : 1;
+        const size_t ebv = v_dtype == DD_F32 ? 4 : v_dtype == DD_BF16 ? 2 : 1;
         Kc = static_cast<const uint8_t *>(Kc) + (size_t)win_start * d * ebk;
         Vc = static_cast<const uint8_t *>(Vc) + (size_t)win_start * d * ebv;
         block_start -= win_start;
@@ -189,7 +193,7 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
         return DD_ERR_ALIGN;
     dd::AttnArgs a{};
     a.Q = Qblk; a.K = Kc; a.V = Vc; a.Kblk = Kblk; a.Vblk = Vblk; a.O = O;
-    a.q_scale = q_scale; a.k_scale = k_scale;
+    a.q_scale = q_scale; a.k_scale = k_scale; a.v_scale = v_scale;
     a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = block_len; a.N = N; a.d = d;
     a.block_start = block_start; a.block_len = block_len;
     a.qk_dtype = qk_dtype; a.v_dtype = v_dtype;
@@ -224,6 +228,40 @@ int dd_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, 
 {
     return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, qk_dtype, v_dtype,
                            q_scale, k_scale, workspace, workspace_bytes, stream, false);
+}
+
+int dd_bidir_attention_fp8v(const void *Q, const void *K, const void *V, void *O,
+                            int B, int H, int Hkv, int N, int d,
+                            const float *q_scale, const float *k_scale, const float *v_scale, void *stream)
+{
+    if (!Q || !K || !V || !O || !v_scale) return DD_ERR_NULL;
+    const int rc = check_attention_common(B, H, Hkv, N, d, DD_FP8_E4M3, DD_FP8_E4M3, q_scale, k_scale, v_scale);
+    if (rc != DD_OK) return rc;
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O)) return DD_ERR_ALIGN;
+    dd::AttnArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.Kblk = nullptr; a.Vblk = nullptr; a.O = O;
+    a.q_scale = q_scale; a.k_scale = k_scale; a.v_scale = v_scale;
+    a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = N; a.N = N; a.d = d;
+    a.block_start = 0; a.block_len = 0;
+    a.qk_dtype = DD_FP8_E4M3; a.v_dtype = DD_FP8_E4M3;
+    a.splits = 1; a.workspace = nullptr;
+    return dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
+size_t dd_block_attention_cached_fp8v_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d)
+{
+    return dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, DD_FP8_E4M3, DD_BF16);
+}
+
+int dd_block_attention_cached_fp8v(const void *Qblk, const void *Kc, const void *Vc, void *O,
+                                   int block_start, int block_len, const void *Kblk, const void *Vblk,
+                                   int B, int H, int Hkv, int N, int d,
+                                   const float *q_scale, const float *k_scale, const float *v_scale,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!v_scale) return DD_ERR_NULL;
+    return block_attention(Qblk, Kc, Vc, O, block_start, block_len, Kblk, Vblk, B, H, Hkv, N, d, DD_FP8_E4M3,
+                           DD_FP8_E4M3, q_scale, k_scale, workspace, workspace_bytes, stream, false, 0, 0, nullptr, v_scale);
 }
 
 size_t dd_block_attention_refresh_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d,

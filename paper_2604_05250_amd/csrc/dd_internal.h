@@ -72,6 +72,7 @@ struct AttnArgs {
     void *O;             // [B, H, Nq, d]
     const float *q_scale;  // [B*H] or nullptr
     const float *k_scale;  // [B*Hkv] or nullptr
+    const float *v_scale = nullptr;  // [B*Hkv]: multiplier of the decoded V values; required when V is fp8
     int B, H, Hkv, Nq, N, d;
     int kv_stride = 0;       // rows between consecutive (batch, kv head) of K and V; 0 = N (dense).  A call on a
                              // window of the cache passes K/V at the window's first row, N = the window length
