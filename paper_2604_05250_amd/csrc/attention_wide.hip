@@ -222,10 +222,21 @@ void attn_wide_kernel(const AttnKernelArgs a)
     }
     const int rows_total = a.group * a.Nq;           // query rows per (batch, kv head); contiguous in memory
     const int nkeys = a.N;
-    // Key stream as a list of 64-row tiles.  Not BLOCK: one part, rows [0, N).  BLOCK: up to three parts.
-    const int len_a = BLOCK && a.block_len ? a.block_start : nkeys;
-    const int len_b = BLOCK ? a.block_len : 0;
-    const int len_c = BLOCK && a.block_len ? nkeys - a.block_start - a.block_len : 0;
+    // Key stream as a list of 64-row tiles.  Not BLOCK: one part, rows [0, N).  BLOCK: up to three parts - cache
+    // rows [0, lo), block-tensor rows [lo - bs, hi - bs), cache rows [hi, N), where [lo, hi) = [bs, bs + block_len)
+    // cut to the sequence and bs is the block's first row: the call's, or this batch entry's own (any value).
+    int blk_lo = 0, blk_hi = 0, blk_first = 0;       // rows [lo, hi) come from the block tensors, from their row blk_first on
+    if (BLOCK && a.block_len) {
+        const int bsel = a.block_starts ? a.block_starts[(t_cur / a.row_tiles) / a.Hkv] : a.block_start;
+        const long s0 = bsel, s1 = (long)bsel + a.block_len;
+        blk_lo = (int)(s0 < 0 ? 0 : s0 > nkeys ? nkeys : s0);
+        blk_hi = (int)(s1 < 0 ? 0 : s1 > nkeys ? nkeys : s1);
+        blk_first = (int)(blk_lo - s0);              // 0 <= blk_first <= block_len whenever the part is not empty
+        if (blk_hi <= blk_lo) blk_first = 0;
+    }
+    const int len_a = BLOCK && a.block_len ? blk_lo : nkeys;
+    const int len_b = BLOCK ? blk_hi - blk_lo : 0;
+    const int len_c = BLOCK && a.block_len ? nkeys - blk_hi : 0;
     const int nt_a = (len_a + TKW - 1) / TKW, nt_b = (len_b + TKW - 1) / TKW, nt_c = (len_c + TKW - 1) / TKW;
     const int nt_all = nt_a + nt_b + nt_c;
     const int nt_per_split = BLOCK ? (nt_all + a.splits - 1) / a.splits : nt_all;
@@ -267,29 +278,35 @@ void attn_wide_kernel(const AttnKernelArgs a)
     const int dma_krow0 = wave * KDMA_ROWS + lane / KCH;
     const unsigned dma_koff = dma_krow0 * KROWB + ((lane % KCH) ^ (dma_krow0 & 7)) * 16;
     const unsigned dma_voff = dma_row0 * ROWB + ((lane % CH) ^ ((dma_row0 & (CH / 4 - 1)) << 2)) * 16;
-    // Tile `tile` of this workgroup's pass: where its 64 rows start in memory (K and V side), and how many of
-    // its leading rows are masked (`shift`): the rows a last tile shares with its predecessor, or all 64 of
-    // a stand-in tile past the end of the pass.  All of it is scalar arithmetic.
-    struct TileAt { const uint8_t *k, *v; int shift; };
+    // Tile `tile` of this workgroup's pass: where its 64 rows start in memory (K and V side), and which of them
+    // count: rows [vlo, vhi) of the tile.  A tile is always 64 whole rows of its source (the cache, or the block
+    // tensors): the window is pushed back into the source where the nominal rows 64 T .. of the part would hang
+    // over its end, so a last tile repeats rows of its predecessor, and the tile of a part shorter than 64 rows
+    // holds rows of the neighbouring part as well - all of those are masked in the scores, as is every row of a
+    // stand-in tile past the end of the pass.  All of it is scalar arithmetic.
+    struct TileAt { const uint8_t *k, *v; int vlo, vhi; };
     auto tile_at = [&](const Tile &t, int tile) __attribute__((always_inline)) {
         // (every captured value is copied before any choice is made between them: the compiler otherwise
         // turns "choose one of several loaded values" into a load through a chosen address, which pins the
         // captured variables in scratch memory)
         const int la = len_a, lb = len_b, lc = len_c, na = nt_a, nb = nt_b, nl = nt_local, tf = t_first;
-        const int c_row0 = a.block_start + a.block_len;
+        const int c_row0 = blk_hi, b_row0 = blk_first, nk = nkeys, bl = a.block_len;
         const uint8_t *const ck = t.k, *const cv = t.v, *const bk = t.kb, *const bv = t.vb;
         const bool standin = tile >= nl;
         int T = tf + min(tile, nl - 1);                                      // position in the list
         const bool in_c = BLOCK && T >= na + nb, in_b = BLOCK && !in_c && T >= na;
         T -= in_c ? na + nb : in_b ? na : 0;                                 // position in its part
-        const int len = in_c ? lc : in_b ? lb : la;
-        const int row0 = in_c ? c_row0 : 0;
+        const int len = in_c ? lc : in_b ? lb : la;                          // rows of the part
+        const int off = in_c ? c_row0 : in_b ? b_row0 : 0;                   // its first row in its source
+        const int src_rows = in_b ? bl : nk;                                 // rows of the source (>= 64: the launcher checks)
         const uint8_t *kp = in_b ? bk : ck, *vp = in_b ? bv : cv;
-        const int start = min(T * TKW, len - TKW);                           // len >= 64: checked by the launcher
+        const int first = off + T * TKW;                                     // nominal first row of the tile
+        const int win = min(first, src_rows - TKW);                          // first row actually loaded
         TileAt r;
-        r.k = kp + (size_t)(row0 + start) * KROWB;
-        r.v = vp + (size_t)(row0 + start) * ROWB;
-        r.shift = standin ? TKW : T * TKW - start;
+        r.k = kp + (size_t)win * KROWB;
+        r.v = vp + (size_t)win * ROWB;
+        r.vlo = standin ? TKW : first - win;
+        r.vhi = standin ? TKW : off + min(T * TKW + TKW, len) - win;
         return r;
     };
     // one load (index i) of the tile whose first row is at `glob`
@@ -586,19 +603,22 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
-        // rows of unit u's tile that lie before its nominal start repeat keys of the previous tile
-        const int lim = MASKABLE ? tile_at(cur, u >> 1).shift - 32 * (u & 1) : 0;
-        if (MASKABLE && __builtin_expect(lim > 0, 0)) {      // uniform branch: those score -inf
+        // keys of unit u's tile outside the rows that count (see tile_at) score -inf
+        const TileAt cur_at = tile_at(cur, u >> 1);
+        const int lo_u = MASKABLE ? cur_at.vlo - 32 * (u & 1) : 0, hi_u = MASKABLE ? cur_at.vhi - 32 * (u & 1) : 32;
+        if (MASKABLE && __builtin_expect(lo_u > 0 || hi_u < 32, 0)) {      // uniform branch
             int k0 = 4 * hh;
             asm volatile("" : "+v"(k0));
 #pragma unroll
             for (int q = 0; q < QB; ++q)
 #pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    if (k0 + 8 * (r >> 2) + (r & 3) < lim) s_cur[q][r] = -INFINITY;
+                for (int r = 0; r < 16; ++r) {
+                    const int kk = k0 + 8 * (r >> 2) + (r & 3);
+                    if (kk < lo_u || kk >= hi_u) s_cur[q][r] = -INFINITY;
+                }
             // A key range that starts with a wholly masked unit (BLOCK: a split may begin at a part's
             // overlapping last tile) has no maximum yet: give it a finite one, so that its weights are 0, not NaN.
-            if (BLOCK && !FOLD && lim >= 32) {
+            if (BLOCK && !FOLD && (lo_u >= 32 || hi_u <= 0)) {
 #pragma unroll
                 for (int q = 0; q < QB; ++q)
                     if (mc[q] == -INFINITY) {
@@ -834,6 +854,23 @@ void attn_wide_kernel(const AttnKernelArgs a)
         else wait_loads_and_sync(I_<0>{});
     };
 
+    if (BLOCK && nt_local <= 0) {
+        // A batch entry whose tile list is shorter than the launch planned for (its block hangs over an end of the
+        // sequence) leaves the last key range empty: a state that weighs nothing in the merge, and done.
+        if (lane < 32) {
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                const int v = cur.v0 + wave * kRowsWave + q * 32 + lane;
+                if (v >= rows_total) continue;
+                const size_t slot = (cur.row_base + v) * (size_t)a.splits + split;
+                for (int c4 = 0; c4 < D / 4; ++c4)
+                    reinterpret_cast<float4 *>(a.part_o + slot * D)[c4] = make_float4(0.f, 0.f, 0.f, 0.f);
+                a.part_ml[slot * 2] = -INFINITY;
+                a.part_ml[slot * 2 + 1] = 0.f;
+            }
+        }
+        return;
+    }
     // ---- prologue of the first row tile: Q rows and K tiles 0, 1 and V tile 0 go straight to LDS
     dma_q(cur);
     dma_tile(K0, tile_at(cur, 0).k, dma_koff, I_<NDMA_K>{});
@@ -929,11 +966,8 @@ bool attn_wide_block_fits(const AttnArgs &a)
 {
     if (a.qk_dtype == 0 || a.v_dtype != 1 || (a.qk_dtype == 2 && a.d != 128)) return false;
     if ((long)(a.H / a.Hkv) * a.Nq < 192) return false;
-    const bool spliced = a.Kblk != nullptr;
-    const int la = spliced ? a.block_start : a.N, lb = spliced ? a.block_len : 0;
-    const int lc = spliced ? a.N - a.block_start - a.block_len : 0;
-    auto ok = [](int len) { return len == 0 || len >= TKW; };
-    return la + lb + lc >= TKW && ok(la) && ok(lb) && ok(lc);
+    // a tile is 64 whole rows of its source: the cache, and the block tensors when rows are spliced in from them
+    return a.N >= TKW && (a.Kblk == nullptr || a.block_len >= TKW);
 }
 
 // Key splits of that form: until there is about one workgroup per compute unit, at least two tiles each.
@@ -952,13 +986,22 @@ hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
     AttnKernelArgs k;
     fill_kernel_args(a, k, kRowsWGWide, TKW);
     if (a.Kblk == nullptr) k.block_len = 0;                // no row is taken from the block tensors
-    // the kernel splits the LIST of tiles (not the key range) evenly; drop splits that would be empty
-    const int spliced = a.Kblk != nullptr;
-    const int la = spliced ? a.block_start : a.N, lb = spliced ? a.block_len : 0, lc = spliced ? a.N - a.block_start - a.block_len : 0;
-    const int nt = (la + TKW - 1) / TKW + (lb + TKW - 1) / TKW + (lc + TKW - 1) / TKW;
-    int splits = a.splits < nt ? a.splits : nt;
-    const int per = (nt + splits - 1) / splits;
-    splits = (nt + per - 1) / per;
+    // the kernel splits the LIST of tiles (not the key range) evenly
+    int splits;
+    if (a.block_starts != nullptr) {
+        // positions known on the device only: a list has between ceil(N / 64) and two more tiles; a batch entry
+        // with a shorter list than others leaves its last split empty, which the kernel handles
+        const int nt_min = (a.N + TKW - 1) / TKW;
+        splits = a.splits < nt_min ? a.splits : nt_min;
+    } else {
+        // drop splits that would be empty
+        const int spliced = a.Kblk != nullptr;
+        const int la = spliced ? a.block_start : a.N, lb = spliced ? a.block_len : 0, lc = spliced ? a.N - a.block_start - a.block_len : 0;
+        const int nt = (la + TKW - 1) / TKW + (lb + TKW - 1) / TKW + (lc + TKW - 1) / TKW;
+        splits = a.splits < nt ? a.splits : nt;
+        const int per = (nt + splits - 1) / splits;
+        splits = (nt + per - 1) / per;
+    }
     k.splits = splits;
     const size_t rows = (size_t)a.B * a.H * a.Nq;
     k.part_ml = k.part_o ? k.part_o + rows * (size_t)splits * a.d : nullptr;

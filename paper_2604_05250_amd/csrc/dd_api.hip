@@ -204,8 +204,7 @@ static int block_attention(const void *Qblk, const void *Kc, const void *Vc, voi
         a.K_refresh = const_cast<void *>(Kc);
         a.V_refresh = const_cast<void *>(Vc);
     }
-    // (the wide kernel plans its tile list on the host from one block position: not for per-sequence positions)
-    const bool wide = dd::tune("DD_TUNE_BLOCK_WIDE", 1) != 0 && block_starts == nullptr && dd::attn_wide_block_fits(a);
+    const bool wide = dd::tune("DD_TUNE_BLOCK_WIDE", 1) != 0 && dd::attn_wide_block_fits(a);
     const int splits = wide ? dd::attn_wide_block_splits(block_len, B, H, Hkv, N)
                             : dd::attn_block_splits(block_len, B, H, Hkv, N, d);
     rc = check_workspace(workspace, workspace_bytes, dd::attn_partial_bytes(B, H, block_len, d, splits));

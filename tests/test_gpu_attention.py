@@ -357,6 +357,9 @@ WIDE_BLOCK = [
     (1, 3, 1, 300, 128, 64, 100, wl.BF16), (1, 4, 1, 321, 128, 64, 193, wl.BF16), (1, 4, 1, 385, 128, 64, 129, wl.BF16),
     (1, 4, 1, 1000, 128, 80, 700, wl.BF16), (2, 8, 2, 640, 128, 64, 256, wl.FP8_E4M3), (1, 16, 4, 2048, 128, 64, 1536, wl.FP8_E4M3),
     (1, 8, 2, 400, 64, 64, 64, wl.BF16), (1, 4, 1, 4096, 128, 128, 2000, wl.BF16),
+    # parts shorter than a tile on either side of the block (1, 63 and 5 rows), block directly at an end
+    (1, 4, 1, 512, 128, 64, 1, wl.BF16), (1, 4, 1, 512, 128, 64, 63, wl.BF16), (1, 4, 1, 512, 128, 64, 512 - 64 - 5, wl.BF16),
+    (2, 8, 2, 2500, 128, 64, 2500 - 64 - 1, wl.BF16), (1, 16, 4, 700, 128, 64, 33, wl.FP8_E4M3), (1, 4, 1, 129, 128, 64, 64, wl.BF16),
 ]
 
 

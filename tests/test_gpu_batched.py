@@ -28,8 +28,11 @@ SHAPES = [
     (5, 2, 1, 150, 64, 1, wl.BF16, {}),                                    # one query row
     (4, 4, 2, 700, 128, 32, wl.BF16, {"DD_TUNE_BLOCK_STREAM": "0"}),       # MFMA kernel
     (2, 2, 2, 4096, 128, 64, wl.BF16, {"DD_TUNE_BLOCK_STREAM": "0"}),      # MFMA kernel, key splits
-    (3, 8, 2, 1000, 128, 64, wl.FP8_E4M3, {}),                             # fp8 keys, 256 rows per kv head
-    (2, 16, 4, 2048, 128, 64, wl.BF16, {}),                                # 256 rows per kv head, bf16
+    (3, 8, 2, 1000, 128, 64, wl.FP8_E4M3, {}),                             # wide kernel: fp8 keys, 256 rows per kv head
+    (2, 16, 4, 2048, 128, 64, wl.BF16, {}),                                # wide kernel (folded-scale form), key splits
+    (5, 12, 4, 700, 128, 64, wl.BF16, {}),                                 # wide kernel: 192 rows per kv head, ragged length
+    (3, 8, 2, 1000, 128, 64, wl.FP8_E4M3, {"DD_TUNE_BLOCK_WIDE": "0"}),    # the same shapes on the MFMA kernel
+    (2, 16, 4, 2048, 128, 64, wl.BF16, {"DD_TUNE_BLOCK_WIDE": "0"}),
     (4, 4, 4, 128, 64, 16, wl.F32, {}),                                    # fp32 kernel
     (3, 2, 1, 600, 128, 48, wl.F32, {}),
 ]
@@ -47,10 +50,29 @@ def test_batched_positions(monkeypatch, B, H, Hkv, N, d, bl, qk, env):
     starts = rng.integers(0, N - bl + 1, B).astype(np.int32)
     starts[0] = 0
     starts[-1] = N - bl                                                    # first and last legal positions
+    if B >= 3:
+        starts[1] = min(7, N - bl)                                         # seven cache rows before the block: a part shorter than a tile
     got = out_to_f64(run(cfg, cache, blk, starts), vd)
     ref = oracle.block_attention_batched(blk["Qblk"], cache["Kc"], cache["Vc"], starts, qk, vd, blk["Kblk"],
                                          blk["Vblk"], blk["q_scale"], cache["k_scale"])
     assert_attention_close(got, ref, qk, f"batched {B}x{H}/{Hkv} N{N} d{d} bl{bl} dtype {qk} {env} starts {starts}")
+
+
+@pytest.mark.parametrize("qk", [wl.BF16, wl.FP8_E4M3])
+def test_wide_kernel_short_parts_and_positions_outside(qk):
+    # 256 query rows per kv head: the wide kernel.  Parts of the key stream shorter than a 64-row tile on either
+    # side of the block, blocks that hang over an end of the sequence (their tile list is shorter: with key
+    # splits, an empty last split) or lie outside it altogether
+    import torch
+    for N, B in ((1000, 8), (4096, 8), (191, 8)):
+        cfg = wl.custom_config(B=B, H=8, Hkv=2, N=N, d=128, bl=64, qk_dtype=qk, v_dtype=wl.BF16, prompt=0, G=N)
+        cache = wl.cache_inputs(cfg, seed=N)
+        blk = wl.block_inputs(cfg, N, 0, k_scale=cache["k_scale"])
+        starts = np.array([1, N - 64 - 1, -10, N - 30, -64, N, 63, -(2**31)], np.int32)
+        got = out_to_f64(run(cfg, cache, blk, starts), wl.BF16)
+        ref = oracle.block_attention_batched(blk["Qblk"], cache["Kc"], cache["Vc"], starts, qk, wl.BF16, blk["Kblk"],
+                                             blk["Vblk"], blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, qk, f"wide kernel, positions {starts.tolist()} N{N} dtype {qk}")
 
 
 def test_equal_positions_are_the_plain_call_and_outside_positions_are_safe(monkeypatch):
