@@ -317,6 +317,31 @@ def run_config(args, config_id):
                 "bidir_attention": [m[4].elapsed_time(m[2]) for m in rec],
                 "verify_remask": [m[2].elapsed_time(m[3]) for m in rec]}
 
+    # Each part alone, as a stream of back-to-back launches on rotated (cold) inputs: the average launch duration of its
+    # kernels, which is what rocprofv3 reports per kernel.  Inside a step every part follows a kernel of another
+    # kind, and the events around it also see the hand-over between the two (2-5 us, which matters for parts of 30 us).
+    def stream_us(call, n=30):
+        for j in range(5):
+            call(j)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for j in range(n):
+            call(5 + j)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+
+    saved_parts = set(parts)
+    stream = {}
+    for name in ("attention", "verify", "block"):
+        if name not in saved_parts:
+            continue
+        parts.clear()
+        parts.add(name)
+        stream[name] = stream_us(lambda j: step(j)) / (cfg.K if name == "block" else 1)
+    parts.clear()
+    parts.update(saved_parts)
+
     # the same parts with every step on ONE input set: whatever fits stays in the 256 MB last-level cache.
     # Reported beside the figures above, which rotate input sets and are the ones every rate is computed from.
     warm_rec = []
@@ -362,6 +387,9 @@ def run_config(args, config_id):
     attn_tflops = attn_flops / (t_attn * 1e-3) / 1e12
     ver_gbps = verify_bytes / (t_ver * 1e-3) / 1e9
     blk_gbps = block_bytes / (t_block / cfg.K * 1e-3) / 1e9
+    attn_stream_tflops = attn_flops / (stream["attention"] * 1e-6) / 1e12 if "attention" in stream else attn_tflops
+    ver_stream_gbps = verify_bytes / (stream["verify"] * 1e-6) / 1e9 if "verify" in stream else ver_gbps
+    blk_stream_gbps = block_bytes / (stream["block"] * 1e-6) / 1e9 if "block" in stream else blk_gbps
 
     def attn_kernel_name(c):
         """The kernel the library's size rule picks for this call (the rule itself lives in the library)."""
@@ -424,6 +452,11 @@ def run_config(args, config_id):
                      "achieved": round(attn_tflops, 3), "peak": round(attn_peak, 1), "unit": "TFLOP/s",
                      "frac": round(attn_tflops / attn_peak, 4), "peak_note": attn_peak_note,
                      "frac_of_bf16_peak": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "launch_us": round(t_attn * 1e3, 2),
+                     "timing": "HIP events around the call inside every timed step (mean); back_to_back_*: the same call "
+                               "as a stream of launches on rotated inputs, nothing else on the chip",
+                     "back_to_back_us": None if "attention" not in stream else round(stream["attention"], 2),
+                     "back_to_back_achieved": round(attn_stream_tflops, 3),
                      "traffic": profiled_traffic(config_id, "attention"),
                      "algorithmic_flops": attn_flops, "algorithmic_bytes": attn_bytes},
         "roofline_verify": {"kernel": ("verify_row_kernel" if cfg.P >= 192 else "verify_partial_kernel + verify_finalize_kernel")
@@ -431,6 +464,9 @@ def run_config(args, config_id):
                                          wl.CONF_TOPK: " + verify_topk_kernel"}.get(mode, "") + " (dd_verify_remask)",
                             "bound": "hbm", "achieved": round(ver_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": round(ver_gbps / PEAK_HBM_GBPS, 4),
+                            "launch_us": round(t_ver * 1e3, 2),
+                            "back_to_back_us": None if "verify" not in stream else round(stream["verify"], 2),
+                            "back_to_back_achieved": round(ver_stream_gbps, 1),
                             "traffic": profiled_traffic(config_id, "verify"),
                             "algorithmic_bytes": verify_bytes},
     }
@@ -439,6 +475,9 @@ def run_config(args, config_id):
                                        "attn_mfma_kernel + attn_combine_kernel, by shape)",
                              "bound": "hbm", "achieved": round(blk_gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                              "frac": round(blk_gbps / PEAK_HBM_GBPS, 4), "traffic": profiled_traffic(config_id, "block"),
+                             "launch_us": round(t_block / cfg.K * 1e3, 2),
+                             "back_to_back_us": None if "block" not in stream else round(stream["block"], 2),
+                             "back_to_back_achieved": round(blk_stream_gbps, 1),
                              "algorithmic_bytes": block_bytes, "cache_copies_rotated": n_caches,
                              "note": f"per call, K={cfg.K} calls per step, each on another copy of the cache (cold); "
                                      "block_attention_warm_GBps: every call on one copy"}
