@@ -67,7 +67,7 @@ constexpr int kRowsWave = 32 * QB;
 constexpr int kRowsWGWide = 4 * kRowsWave;
 constexpr int kPackLag = 2;              // pieces between an exponential and its conversion to bf16
 constexpr float kSlack = 8.0f;          // the maximum in use is raised when exceeded by 2^8
-constexpr int kFoldMinKeys = 2048;      // key rows from which scaling Q once per row tile pays (see FOLD below)
+constexpr int kFoldMinKeys = 1024;      // key rows from which scaling Q once per row tile pays (see FOLD below)
 constexpr float kFoldMargin = 7.0f;     // folded form: the reference is set this far above a unit's maximum (log2 units)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -105,6 +105,12 @@ __device__ __forceinline__ void qk_first(floatx16 &s, const KT kf, const QT qfra
     if constexpr (FP8) asm volatile("v_mfma_f32_32x32x16_fp8_fp8 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
 }
+// the same from an addend: the block starts from `init` (minus the softmax reference of its query rows)
+template <typename KT, typename QT>
+__device__ __forceinline__ void qk_first_from(floatx16 &s, const KT kf, const QT qfrag, const floatx16 &init)
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(s) : "v"(kf), "a"(qfrag), "v"(init));
+}
 template <bool FP8, typename KT, typename QT>
 __device__ __forceinline__ void qk_next(floatx16 &s, const KT kf, const QT qfrag)
 {
@@ -139,24 +145,23 @@ using F_ = std::false_type;
 // FP8: Q and K are fp8 e4m3 (with per-head scales folded into the exponent's factor), V and O bf16.
 // BLOCK: the drafter's form of the call (Sec. 2.3) - the rows are the active block's queries, the key stream
 // is cache rows [0, block_start), the block tensors' rows, cache rows [block_start + block_len, N) (each
-// part a whole number of 64-row tiles by the same overlap rule, so each part is empty or at least 64 rows:
-// the launcher checks), a workgroup takes one row tile and one of `splits` ranges of the tile list, and
+// part tiled by the same rule of 64-row windows with a valid range), a workgroup takes one row tile and one of `splits` ranges of the tile list, and
 // with splits > 1 writes its unnormalised state for the merge kernel instead of O.
 // FOLD (bf16 Q/K without per-head scales, key ranges of kFoldMinKeys rows or more): the factor
 // c = log2(e)/sqrt(d_k) is multiplied into the Q fragments once per row tile (rounded to bf16 again; this second
 // rounding perturbs a score by about 2^-10 of the typical score magnitude, as much as the bf16 rounding of the
-// weights does), and every score block accumulates onto minus the softmax reference of its query rows instead of
-// zero, so the matrix cores deliver S' = c q.k - m and the weight of a key is exp2(S') with no other arithmetic
-// per score.  Scaling Q costs some 1600 cycles per row tile and wave and the form saves about 100 per 64 keys:
-// at 4096 keys the call is 2.5 % faster, at 1024 keys nothing is left.  The same mechanism WITHOUT the folded
-// scale (one multiplication per score in place of the fused multiply-add and the maxima) was measured 2-3 %
-// slower than the row-maximum form below on the 1024- and 2048-key workloads, so that form stays for them.  (The registers of a score block are free between its last exponential and the
-// first product of the block after next: they are refilled with -m by four 16-byte LDS reads per row block, from a
-// per-lane slot that holds four copies of it.)  The reference only has to be NEAR the running maximum (weights and
-// sums are floating point, any common factor 2^-m cancels in O = sum(P v) / sum(P)): it is set to the maximum of a
-// row tile's first unit plus a margin, and raised when some weight reaches 2, which shows as one bit of its bf16
-// pattern - the packed weights are or-ed together as they are produced (one instruction per four scores) and
-// tested once per unit.
+// weights does), and every score block starts from minus the softmax reference m of its query rows instead of
+// from zero - the first matrix instruction of a block takes -m, held in sixteen registers per row block, as its
+// addend - so the matrix cores deliver S' = c q.k - m and the weight of a key is exp2(S') with no other
+// arithmetic per score.  The reference only has to be NEAR the running maximum (weights and sums are floating
+// point, any common factor 2^-m cancels in O = sum(P v) / sum(P)): it is set to the maximum of a row tile's
+// first unit plus a margin, and raised when some weight reaches 2, which shows as one bit of its bf16 pattern -
+// the packed weights are or-ed together as they are produced (one instruction per four scores) and tested once
+// per unit.  Scaling Q costs some 1600 cycles per row tile and wave; measured against the row-maximum form
+// below, the call is 5 % faster at 4096 keys and 3 % at 1024.  (Tried: the reference refilled into the score
+// registers by LDS reads instead of kept in registers - half the gain; the same mechanism without the folded
+// scale, one multiplication per score - slower than the row-maximum form, which therefore stays for fp8 and
+// per-head scales.)
 template <int D, bool FP8, bool BLOCK, bool FOLD = false>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_wide_kernel(const AttnKernelArgs a)
@@ -181,7 +186,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int MAXC = FOLD ? 0 : NP >= 32 ? 8 : 4;   // pieces that carry the row maxima
     constexpr int CHK = NP - 6;                      // FOLD: the piece that tests the unit's weights, after the last pack ...
     constexpr int EXC = FOLD ? CHK - kPackLag : NP - MAXC;   // pieces that carry the 32 exponentials
-    constexpr int PRE = CHK + 1;                     // ... and the first of the 2 QB pieces that refill the score registers
     constexpr int RD = 3;                            // fragment rings: fetched RD uses (2 RD MFMAs) ahead
     static_assert(NDMA_K + NDMA + 1 <= NP, "one tile load per piece");
     static_assert(FOLD || 16 % (2 * MAXC) == 0, "whole pairs of scores per maximum piece");
@@ -197,8 +201,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
     constexpr int QOW = kRowsWave * OPITCH;          // bytes per wave
     static_assert(QOW % 16 == 0, "wave regions stay 16-byte aligned");
     __shared__ uint4 QO[4 * QOW / 16];
-    // FOLD: minus the softmax reference of each query row, four copies per lane: [wave][row block][lane]
-    __shared__ float4 MREF[FOLD ? 4 * QB * 64 : 1];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -410,15 +412,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
     float mc_done[QB] = {-INFINITY, -INFINITY};      // the finished tile's maximum in use (BLOCK: part of its state)
     bool ref_unset = false;                          // FOLD: a row tile has begun with wholly masked units, no reference yet (uniform)
     unsigned seen0 = 0u;                             // ... what the or of a unit's weights starts from: the tested bit while that is so
+    floatx16 cinit[QB];                              // FOLD: what a score block starts from: -mc in all 16 registers
     if constexpr (FOLD) {
 #pragma unroll
-        for (int q = 0; q < QB; ++q) MREF[(wave * QB + q) * 64 + lane] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int q = 0; q < QB; ++q)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) cinit[q][r] = 0.f;
     }
-    // a score block's registers <- -m of its rows (this lane's slot; written and read by this wave only)
-    auto refill = [&](floatx16 &sb, int q, int quarter) __attribute__((always_inline)) {
-        const float4 v = MREF[(wave * QB + q) * 64 + lane];
-        sb[4 * quarter] = v.x; sb[4 * quarter + 1] = v.y; sb[4 * quarter + 2] = v.z; sb[4 * quarter + 3] = v.w;
-    };
     intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
 
@@ -664,11 +664,11 @@ void attn_wide_kernel(const AttnKernelArgs a)
                         seen0 = ref_unset ? 0x4000u : 0u;
                     }
                     mc[q] += delta;
-                    MREF[(wave * QB + q) * 64 + lane] = make_float4(-mc[q], -mc[q], -mc[q], -mc[q]);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         s_cur[q][r] -= delta;
                         s_nxt[q][r] -= delta;                // (written by matrix instructions many pieces ago)
+                        cinit[q][r] = -mc[q];
                     }
 #pragma unroll
                     for (int r = 0; r < 16; r += 2)
@@ -676,6 +676,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     corr[q] = fast_exp2(-delta);
                 }
                 changed = !opening;                          // (zeros need no rescaling, and 2^-delta may overflow there)
+                // written by vector instructions, read as the addend of the next S = K Q^T, which the compiler's
+                // hazard padding does not see
+                asm volatile("s_nop 7" : "+v"(cinit[0]), "+v"(cinit[1]));
             }
         };
         // everything of the step that is not an MFMA, dealt out over the NP pieces
@@ -722,11 +725,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 if (exp_piece(2 * pr + 1) == t - kPackLag) pack_pair(pr);
             if constexpr (FOLD) {
                 if (t == CHK) check_reference();
-                // S(u) has been consumed: its registers take -m for S(u+2), two 16-byte reads per piece
-                if (t >= PRE && t < PRE + 2 * QB) {
-                    refill(s_cur[(t - PRE) / 2], (t - PRE) / 2, 2 * ((t - PRE) & 1));
-                    refill(s_cur[(t - PRE) / 2], (t - PRE) / 2, 2 * ((t - PRE) & 1) + 1);
-                }
             }
             __builtin_amdgcn_sched_barrier(0);               // nothing moves between pieces
         };
@@ -737,7 +735,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
             for (int q = 0; q < QB; ++q) {
                 const int f = j / MPF;                       // fragment of this k-step; it is free after its last use
                 if constexpr (FOLD) {
-                    qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);   // onto -m, put there a step ago
+                    if (j == 0) qk_first_from(s_nxt[q], kfr[0], qf[q][0], cinit[q]);   // starts from minus the reference
+                    else qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);
                 } else {
                     if (j == 0) qk_first<FP8>(s_nxt[q], k_op(kfr[0], 0), qf[q][0]);
                     else qk_next<FP8>(s_nxt[q], k_op(kfr[f % RD], j), qf[q][j]);
@@ -891,13 +890,6 @@ void attn_wide_kernel(const AttnKernelArgs a)
     for (int q = 0; q < QB; ++q)
 #pragma unroll
         for (int t = 0; t < 8; ++t) pk1[q][t >> 2][t & 3] = 0u;
-    if constexpr (FOLD) {                                    // S(1) accumulates onto minus the reference, which is 0
-#pragma unroll
-        for (int q = 0; q < QB; ++q)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) s1[q][r] = 0.f;
-        asm volatile("" : "+v"(s1[0]), "+v"(s1[1]));
-    }
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
