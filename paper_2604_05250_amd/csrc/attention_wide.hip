@@ -710,7 +710,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     }
                 }
             }
-            if (t >= MAXC) {
+            if (t >= MAXC && t < MAXC + EXC) {               // (FOLD: the last pieces carry no exponentials)
 #pragma unroll
                 for (int e = 32 * (t - MAXC) / EXC; e < 32 * (t - MAXC + 1) / EXC; ++e) {
                     const int pr = e >> 1, q = pr & 1, r = (pr >> 1) * 2 + (e & 1);
