@@ -320,13 +320,20 @@ def run_config(args, config_id):
     # Each part alone, as a stream of back-to-back launches on rotated (cold) inputs: the average launch duration of its
     # kernels, which is what rocprofv3 reports per kernel.  Inside a step every part follows a kernel of another
     # kind, and the events around it also see the hand-over between the two (2-5 us, which matters for parts of 30 us).
+    # (A change of load pattern is followed by some tens of milliseconds of lower clocks - the attention kernel's first
+    # launches of such a stream take a fifth longer than its later ones - so each stream first runs untimed for 80 ms.)
     def stream_us(call, n=30):
-        for j in range(5):
-            call(j)
+        j0 = 0
+        t_s = time.perf_counter()
+        while (time.perf_counter() - t_s) * 1e3 < 80.0:
+            for _ in range(5):
+                call(j0)
+                j0 += 1
+            torch.cuda.synchronize()
         e0, e1 = ev(), ev()
         e0.record()
         for j in range(n):
-            call(5 + j)
+            call(j0 + j)
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n * 1e3
@@ -397,7 +404,8 @@ def run_config(args, config_id):
         wide_tiles = c.B * c.Hkv * -(-group * c.N // 256)
         fp8 = c.qk_dtype == wl.FP8_E4M3
         if wide_tiles >= 192 and c.N >= 512 and (not fp8 or c.d == 128):
-            return f"attn_wide_kernel<{c.d}, {'true' if fp8 else 'false'}>"
+            fold = not fp8 and c.N >= 1024          # bf16 without per-head scales: the folded-scale form
+            return f"attn_wide_kernel<{c.d}, {'true' if fp8 else 'false'}, false, {'true' if fold else 'false'}>"
         if not fp8 and c.B * c.Hkv * -(-group * c.N // 128) < 256:
             return f"attn_stream_kernel<{c.d}>"
         return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false>"

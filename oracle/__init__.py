@@ -18,7 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dd_oracle.c")
 _LIB = os.path.join(_HERE, "libdd_oracle.so")
 
-F32, BF16, FP8_E4M3 = 0, 1, 2
+F32, BF16, FP8_E4M3, F64 = 0, 1, 2, 3
+MX_E4M3, MX_E2M1 = 0, 1      # element kinds of block-scaled tensors
 TRUST, KL_THRESH, CONF_THRESH, KL_PROB, CONF_PROB, KL_TOPK, CONF_TOPK = 0, 1, 2, 3, 4, 5, 6
 UNMASK_THRESH, UNMASK_TOPK = 0, 1
 
@@ -44,6 +45,12 @@ def lib():
         _lib.ora_decode_e4m3.argtypes = [C.c_uint8]
         _lib.ora_decode_bf16.restype = C.c_double
         _lib.ora_decode_bf16.argtypes = [C.c_uint16]
+        _lib.ora_decode_e8m0.restype = C.c_double
+        _lib.ora_decode_e8m0.argtypes = [C.c_uint8]
+        _lib.ora_decode_e2m1.restype = C.c_double
+        _lib.ora_decode_e2m1.argtypes = [C.c_uint8]
+        _lib.ora_decode_mx.restype = C.c_int
+        _lib.ora_decode_mx.argtypes = [vp, vp, dp, C.c_size_t, C.c_int, C.c_int]
         _lib.ora_bidir_attention.restype = C.c_int
         _lib.ora_bidir_attention.argtypes = [vp, vp, vp, dp] + [C.c_int] * 7 + [vp, vp, vp, C.c_int]
         _lib.ora_block_attention_cached.restype = C.c_int
@@ -80,7 +87,7 @@ def num_threads() -> int:
         return os.cpu_count() or 1
 
 
-_NP_OF = {F32: np.float32, BF16: np.uint16, FP8_E4M3: np.uint8}
+_NP_OF = {F32: np.float32, BF16: np.uint16, FP8_E4M3: np.uint8, F64: np.float64}
 
 
 def _chk(a: np.ndarray, dtype: int, name: str) -> np.ndarray:
@@ -106,6 +113,36 @@ def decode_e4m3(code: int) -> float:
 
 def decode_bf16(bits: int) -> float:
     return lib().ora_decode_bf16(int(bits))
+
+
+def decode_e8m0(code: int) -> float:
+    return lib().ora_decode_e8m0(int(code))
+
+
+def decode_e2m1(code: int) -> float:
+    return lib().ora_decode_e2m1(int(code))
+
+
+def decode_mx(elems: np.ndarray, scales: np.ndarray, kind: int) -> np.ndarray:
+    """Block-scaled tensor [..., d] -> fp64.  elems: uint8 [..., d] (MX_E4M3) or [..., d/2] (MX_E2M1, two elements
+    per byte, the even one in the low four bits); scales: uint8 [..., d/32] E8M0 codes, one per 32 elements."""
+    elems = np.ascontiguousarray(elems, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.uint8)
+    d = scales.shape[-1] * 32
+    assert elems.shape[:-1] == scales.shape[:-1] and elems.shape[-1] == (d if kind == MX_E4M3 else d // 2)
+    rows = int(np.prod(scales.shape[:-1], dtype=np.int64))
+    out = np.empty(scales.shape[:-1] + (d,), dtype=np.float64)
+    rc = lib().ora_decode_mx(_ptr(elems), _ptr(scales), out.ctypes.data_as(C.POINTER(C.c_double)), rows, d, kind)
+    if rc != 0:
+        raise ValueError("ora_decode_mx: bad argument")
+    return out
+
+
+def bidir_attention_mx(Q, Qs, K, Ks, V, Vs, rows=None) -> np.ndarray:
+    """Full bidirectional attention on block-scaled inputs: Q, K with e4m3 elements, V with e2m1 elements, each with
+    E8M0 scales per 32 elements of the head dimension: the tensors are decoded (decode_mx) and attended as fp64."""
+    return bidir_attention(decode_mx(Q, Qs, MX_E4M3), decode_mx(K, Ks, MX_E4M3), decode_mx(V, Vs, MX_E2M1),
+                           F64, F64, rows=rows)
 
 
 def bidir_attention(Q, K, V, qk_dtype: int, v_dtype: int, q_scale=None, k_scale=None, rows=None, v_scale=None) -> np.ndarray:

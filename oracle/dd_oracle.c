@@ -25,13 +25,21 @@
  * Everything is two-pass and untiled: scores are materialised per query row, the
  * maximum is subtracted, exponentials are summed.  Storage types are decoded
  * exactly into double (fp32 and bf16 are subsets of double; fp8 is OCP e4m3).
+ *
+ * The paper states no storage precision (Sec. 4.1 runs stock models); the reduced-
+ * precision workloads are input formats only.  Block-scaled ("MX") tensors follow
+ * the OCP Microscaling Formats specification v1.0: 32 consecutive elements along
+ * the head dimension share one power-of-two scale (E8M0); they are decoded to
+ * double by ora_decode_mx and then go through the same attention as any other
+ * input (dtype ORA_F64).
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
 
-enum { ORA_F32 = 0, ORA_BF16 = 1, ORA_FP8_E4M3 = 2 };
+enum { ORA_F32 = 0, ORA_BF16 = 1, ORA_FP8_E4M3 = 2, ORA_F64 = 3 };
+enum { ORA_MX_E4M3 = 0, ORA_MX_E2M1 = 1 };
 enum { ORA_TRUST = 0, ORA_KL_THRESH = 1, ORA_CONF_THRESH = 2, ORA_KL_PROB = 3, ORA_CONF_PROB = 4,
        ORA_KL_TOPK = 5, ORA_CONF_TOPK = 6 };
 
@@ -61,11 +69,47 @@ double ora_decode_bf16(uint16_t bits)
     return (double)f;
 }
 
+/* E8M0 scale of a block-scaled format: 8 exponent bits, bias 127, no sign, no mantissa:
+ * 2^(code - 127); code 255 is NaN. */
+double ora_decode_e8m0(uint8_t code)
+{
+    if (code == 255)
+        return NAN;
+    return ldexp(1.0, (int)code - 127);
+}
+
+/* 4-bit float: sign, 2 exponent bits (bias 1), 1 mantissa bit; no NaN, no infinity.
+ * exponent 0 is subnormal (m/2 * 2^0): the values are +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}. */
+double ora_decode_e2m1(uint8_t code)
+{
+    int s = (code >> 3) & 1, e = (code >> 1) & 3, m = code & 1;
+    double v = e == 0 ? (double)m / 2.0 : ldexp(1.0 + (double)m / 2.0, e - 1);
+    return s ? -v : v;
+}
+
+/* Block-scaled tensor -> double.  `rows` rows of d elements; element c of a row belongs to block c / 32,
+ * whose scale is scales[row * (d / 32) + c / 32]; value = element x scale.  kind ORA_MX_E4M3: one byte per
+ * element; ORA_MX_E2M1: two elements per byte, the even element in the low four bits.  d % 32 == 0. */
+int ora_decode_mx(const uint8_t *elems, const uint8_t *scales, double *dst, size_t rows, int d, int kind)
+{
+    if (!elems || !scales || !dst || d <= 0 || d % 32 || (kind != ORA_MX_E4M3 && kind != ORA_MX_E2M1))
+        return -1;
+    for (size_t r = 0; r < rows; ++r)
+        for (int c = 0; c < d; ++c) {
+            size_t i = r * (size_t)d + (size_t)c;
+            double x = kind == ORA_MX_E4M3 ? ora_decode_e4m3(elems[i])
+                                           : ora_decode_e2m1((uint8_t)((elems[i / 2] >> (4 * (i & 1))) & 15));
+            dst[i] = x * ora_decode_e8m0(scales[r * (size_t)(d / 32) + (size_t)(c / 32)]);
+        }
+    return 0;
+}
+
 static double load_elem(const void *base, size_t idx, int dtype)
 {
     switch (dtype) {
     case ORA_F32: return (double)((const float *)base)[idx];
     case ORA_BF16: return ora_decode_bf16(((const uint16_t *)base)[idx]);
+    case ORA_F64: return ((const double *)base)[idx];
     default: return ora_decode_e4m3(((const uint8_t *)base)[idx]);
     }
 }

@@ -875,8 +875,12 @@ void attn_wide_kernel(const AttnKernelArgs a)
     dma_tile(K0, tile_at(cur, 0).k, dma_koff, I_<NDMA_K>{});
     dma_tile(V0, tile_at(cur, 0).v, dma_voff, I_<NDMA>{});
     dma_tile(K1, tile_at(cur, 1).k, dma_koff, I_<NDMA_K>{});
-    wait_loads_and_sync(I_<0>{});
+    // the Q rows (first in line, and this wave's own) are turned into fragments while the tiles still arrive
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(waitcnt_vm(2 * NDMA_K + NDMA));
+    asm volatile("" ::: "memory");
     install_q(cur);
+    wait_loads_and_sync(I_<0>{});
     c[0] = c_next[0];
     c[1] = c_next[1];
 #pragma unroll

@@ -76,6 +76,43 @@ def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
     return code | sign
 
 
+def f32_to_e2m1_bits(x: np.ndarray) -> np.ndarray:
+    """Round fp32 to the 4-bit float e2m1 (values +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}), nearest with ties to the even
+    code, saturating at +-6; returns the 4-bit codes (sign in bit 3), one per byte.  Input must be finite."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    sign = ((x.view(np.uint32) >> np.uint32(28)) & np.uint32(8)).astype(np.uint8)
+    a = np.minimum(np.abs(x), np.float32(6.0))
+    grid = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float32)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 1, 7)          # grid[hi-1] <= a <= grid[hi] (or a == 0)
+    lo = hi - 1
+    dl, dh = a - grid[lo], grid[hi] - a
+    code = np.where(dl < dh, lo, np.where(dh < dl, hi, np.where(lo % 2 == 0, lo, hi)))
+    return code.astype(np.uint8) | sign
+
+
+def mx_quantize(x: np.ndarray, kind: str):
+    """Block-scaled (OCP Microscaling v1.0) storage of a tensor [..., d], d % 32 == 0: every 32 consecutive elements
+    share a power-of-two scale 2^(floor(log2(amax)) - emax) with emax = 8 (e4m3 elements) or 2 (e2m1), stored as the
+    E8M0 code exponent + 127 (clamped to 0..254; an all-zero block takes 127); elements = value / scale rounded to
+    the element type, saturating.  Returns (elements, scales): elements uint8 [..., d] for "e4m3", [..., d/2] for
+    "e2m1" (two per byte, the even element in the low four bits); scales uint8 [..., d/32]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    d = x.shape[-1]
+    assert d % 32 == 0 and kind in ("e4m3", "e2m1")
+    xb = x.reshape(x.shape[:-1] + (d // 32, 32))
+    amax = np.max(np.abs(xb), axis=-1)
+    _, e1 = np.frexp(amax)                                            # amax = m * 2^e1, m in [0.5, 1)
+    shared = np.where(amax > 0, e1.astype(np.int32) - 1 - (8 if kind == "e4m3" else 2), 0)
+    shared = np.clip(shared, -127, 127)
+    scaled = np.ldexp(xb, -shared[..., None]).astype(np.float32)      # exact: a power of two
+    if kind == "e4m3":
+        elems = f32_to_e4m3_bits(scaled).reshape(x.shape)
+    else:
+        c = f32_to_e2m1_bits(scaled).reshape(x.shape[:-1] + (d // 2, 2))
+        elems = (c[..., 0] | (c[..., 1] << np.uint8(4))).astype(np.uint8)
+    return elems, (shared + 127).astype(np.uint8)
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations
 # --------------------------------------------------------------------------
@@ -174,6 +211,17 @@ def attention_inputs(cfg: StepConfig, seed: int = 0) -> dict:
     K, ks = _head_tensor(seed, _T_K, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.qk_dtype, cfg.qk_prescale)
     V, vs = _head_tensor(seed, _T_V, cfg.B, cfg.Hkv, cfg.N, cfg.d, cfg.v_dtype, cfg.qk_prescale)
     return {"Q": Q, "K": K, "V": V, "q_scale": qs, "k_scale": ks, "v_scale": vs}
+
+
+def mx_attention_inputs(cfg: StepConfig, seed: int = 0) -> dict:
+    """The verifier's attention inputs of `cfg` in block-scaled storage (the same fp32 draws as attention_inputs
+    would make): Q [B,H,N,d] and K [B,Hkv,N,d] with e4m3 elements, V [B,Hkv,N,d/2] with e2m1 elements, each with
+    E8M0 scales [..., d/32]."""
+    out = {}
+    for name, tid, Hn, kind in (("Q", _T_Q, cfg.H, "e4m3"), ("K", _T_K, cfg.Hkv, "e4m3"), ("V", _T_V, cfg.Hkv, "e2m1")):
+        x, _ = _head_tensor(seed, tid, cfg.B, Hn, cfg.N, cfg.d, F32, cfg.qk_prescale)
+        out[name], out[name + "s"] = mx_quantize(x, kind)
+    return out
 
 
 def cache_inputs(cfg: StepConfig, seed: int = 0) -> dict:

@@ -9,6 +9,9 @@
 
 double ora_decode_e4m3(uint8_t code);
 double ora_decode_bf16(uint16_t bits);
+double ora_decode_e8m0(uint8_t code);
+double ora_decode_e2m1(uint8_t code);
+int ora_decode_mx(const uint8_t *elems, const uint8_t *scales, double *dst, size_t rows, int d, int kind);
 int ora_bidir_attention(const void *Q, const void *K, const void *V, double *O, int B, int H, int Hkv, int N, int d,
                         int qk_dtype, int v_dtype, const float *q_scale, const float *k_scale, const int32_t *rows, int nrows);
 int ora_block_attention_cached(const void *Qblk, const void *Kc, const void *Vc, double *O, int block_start, int block_len,
@@ -103,6 +106,22 @@ int main(void)
     rc |= attention_case(2, 4, 2, 37, 64, 1, 1, 5, 32);
     rc |= attention_case(1, 3, 1, 50, 128, 2, 1, 16, 17);
     rc |= attention_case(2, 2, 1, 33, 64, 0, 0, 7, 0);
+    for (int c = 0; c < 256; ++c) { (void)ora_decode_e8m0((uint8_t)c); (void)ora_decode_e2m1((uint8_t)(c & 15)); }
+    {
+        /* block-scaled tensors, exactly sized: 3 rows of 64 elements (e4m3: 192 bytes, e2m1: 96), 6 scales; decoded
+         * values attended as fp64 (dtype 3) */
+        enum { R = 3, D = 64 };
+        uint8_t *e8 = malloc(R * D), *e4 = malloc(R * D / 2), *sc = malloc(R * D / 32);
+        double *dq = malloc(sizeof(double) * R * D), *dv = malloc(sizeof(double) * R * D), *o = malloc(sizeof(double) * R * D);
+        for (int i = 0; i < R * D; ++i) e8[i] = (uint8_t)((i * 37) % 0x7E);
+        for (int i = 0; i < R * D / 2; ++i) e4[i] = (uint8_t)(i * 29);
+        for (int i = 0; i < R * D / 32; ++i) sc[i] = (uint8_t)(120 + i);
+        rc |= ora_decode_mx(e8, sc, dq, R, D, 0);
+        rc |= ora_decode_mx(e4, sc, dv, R, D, 1);
+        if (ora_decode_mx(e8, sc, dq, R, 48, 0) == 0) rc |= 32;          /* d not a multiple of 32 */
+        rc |= ora_bidir_attention(dq, dq, dv, o, 1, 1, 1, R, D, 3, 3, NULL, NULL, NULL, 0);
+        free(e8); free(e4); free(sc); free(dq); free(dv); free(o);
+    }
     rc |= verify_case(1, 1, 8, 1);
     rc |= verify_case(3, 7, 1000, 1);
     rc |= verify_case(2, 5, 37, 0);

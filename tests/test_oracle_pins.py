@@ -727,3 +727,93 @@ def test_fp8_v_with_a_scale_is_attention_on_the_decoded_values():
     stale_V = inp["V"].copy(); stale_V[:, :, bs:bs + bl] = 0x7E          # 448: would dominate if it were read
     blk2 = oracle.block_attention_cached(Qb, inp["K"], stale_V, bs, BF16, FP8_E4M3, Kb, Vb, v_scale=vs)
     assert np.array_equal(blk2, blk)
+
+
+# ---------------------------------------------------------------- block-scaled (MX) storage
+E2M1_VALUES = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]       # the eight magnitudes the format's definition lists
+
+
+def test_mx_decode_tables_closed_forms():
+    # E8M0: 2^(code - 127), 255 = NaN; e2m1: the sixteen values of its definition
+    for c in range(255):
+        assert oracle.decode_e8m0(c) == math.ldexp(1.0, c - 127)
+    assert math.isnan(oracle.decode_e8m0(255))
+    for c in range(16):
+        want = E2M1_VALUES[c & 7] * (-1.0 if c & 8 else 1.0)
+        got = oracle.decode_e2m1(c)
+        assert got == want and math.copysign(1.0, got) == math.copysign(1.0, want)
+
+
+def test_mx_decode_block_placement_and_nibble_order():
+    # a second formulation: table lookup per element, blocks of 32 along the last axis times their scale
+    rng = np.random.default_rng(11)
+    rows, d = 7, 96
+    t8 = np.array([oracle.decode_e4m3(c) for c in range(256)])
+    t4 = np.array([E2M1_VALUES[c & 7] * (-1.0 if c & 8 else 1.0) for c in range(16)])
+    sc = rng.integers(100, 150, size=(rows, d // 32), dtype=np.uint8)
+    e8 = rng.integers(0, 256, size=(rows, d), dtype=np.uint8)
+    e8[(e8 & 0x7F) == 0x7F] = 0x11                                   # no NaN codes
+    want8 = (t8[e8].reshape(rows, d // 32, 32) * np.ldexp(1.0, sc.astype(np.int64) - 127)[..., None]).reshape(rows, d)
+    assert np.array_equal(oracle.decode_mx(e8, sc, oracle.MX_E4M3), want8)
+    c4 = rng.integers(0, 16, size=(rows, d), dtype=np.uint8)
+    packed = (c4[:, 0::2] | (c4[:, 1::2] << 4)).astype(np.uint8)      # even element in the low four bits
+    want4 = (t4[c4].reshape(rows, d // 32, 32) * np.ldexp(1.0, sc.astype(np.int64) - 127)[..., None]).reshape(rows, d)
+    assert np.array_equal(oracle.decode_mx(packed, sc, oracle.MX_E2M1), want4)
+    one = oracle.decode_mx(np.array([[0x21] + [0] * 15], np.uint8), np.array([[127]], np.uint8), oracle.MX_E2M1)
+    assert one[0, 0] == 0.5 and one[0, 1] == 1.0 and not one[0, 2:].any()
+    # a scale belongs to its own 32 elements only
+    sc2 = sc.copy(); sc2[3, 1] += 5
+    diff = oracle.decode_mx(e8, sc2, oracle.MX_E4M3) != want8
+    assert not diff[:3].any() and not diff[4:].any() and not diff[3, :32].any() and not diff[3, 64:].any()
+    assert np.array_equal(oracle.decode_mx(e8, sc2, oracle.MX_E4M3)[3, 32:64], 32.0 * want8[3, 32:64])
+
+
+def test_mx_encode_after_decode_is_the_identity():
+    # every finite element code, in a block whose largest element sits at the top binade of the element type (which
+    # is what fixes the block's scale), for several scales: the workload's quantiser returns the same codes
+    for kind, k, codes, top in (("e4m3", oracle.MX_E4M3, [c for c in range(256) if (c & 0x7F) != 0x7F], 0x78),
+                                ("e2m1", oracle.MX_E2M1, list(range(16)), 6)):
+        for scale in (100, 127, 150):
+            codes_arr = np.array(codes, np.uint8)
+            for start in range(0, len(codes), 31):
+                blk = np.full(32, top, np.uint8)
+                part = codes_arr[start:start + 31]
+                blk[:len(part)] = part
+                elems = blk[None, :] if k == oracle.MX_E4M3 else (blk[0::2] | (blk[1::2] << 4)).astype(np.uint8)[None, :]
+                sc = np.array([[scale]], np.uint8)
+                vals = oracle.decode_mx(elems, sc, k)
+                e2, s2 = wl.mx_quantize(vals.astype(np.float32), kind)
+                assert np.array_equal(vals.astype(np.float32).astype(np.float64), vals)      # exact in fp32
+                assert np.array_equal(s2, sc) and np.array_equal(e2, elems), (kind, scale, start)
+    # an all-zero block takes the neutral scale
+    e, s = wl.mx_quantize(np.zeros((1, 32), np.float32), "e4m3")
+    assert s[0, 0] == 127 and not e.any()
+
+
+def test_mx_attention_is_attention_on_the_decoded_values():
+    cfg = wl.custom_config(B=2, H=4, Hkv=2, N=41, d=64, prompt=0, G=41)
+    inp = wl.mx_attention_inputs(cfg, seed=5)
+    assert inp["Q"].shape == (2, 4, 41, 64) and inp["V"].shape == (2, 2, 41, 32) and inp["Ks"].shape == (2, 2, 41, 2)
+    got = oracle.bidir_attention_mx(inp["Q"], inp["Qs"], inp["K"], inp["Ks"], inp["V"], inp["Vs"])
+    # all scales neutral: the e4m3 elements alone are an fp8 tensor with scale 1, and the e2m1 values are fp32 values
+    ones = {k: np.full_like(inp[k], 127) for k in ("Qs", "Ks", "Vs")}
+    t4 = np.array([E2M1_VALUES[c & 7] * (-1.0 if c & 8 else 1.0) for c in range(16)], np.float32)
+    V32 = np.stack([t4[inp["V"] & 15], t4[inp["V"] >> 4]], axis=-1).reshape(2, 2, 41, 64)
+    plain = oracle.bidir_attention(inp["Q"], inp["K"], V32, FP8_E4M3, F32)
+    unit = oracle.bidir_attention_mx(inp["Q"], ones["Qs"], inp["K"], ones["Ks"], inp["V"], ones["Vs"])
+    assert np.array_equal(unit, plain)
+    # powers of two move through exactly: V's scales up by 3 -> output x 8; Q up by 2 and K down by 2 -> unchanged
+    up = oracle.bidir_attention_mx(inp["Q"], inp["Qs"], inp["K"], inp["Ks"], inp["V"], inp["Vs"] + 3)
+    assert np.array_equal(up, 8.0 * got)
+    same = oracle.bidir_attention_mx(inp["Q"], inp["Qs"] + 2, inp["K"], inp["Ks"] - 2, inp["V"], inp["Vs"])
+    assert np.array_equal(same, got)
+    # and the result is the fp64 attention of what the tensors decode to, computed by the library formulation
+    Qd = oracle.decode_mx(inp["Q"], inp["Qs"], oracle.MX_E4M3); Kd = oracle.decode_mx(inp["K"], inp["Ks"], oracle.MX_E4M3)
+    Vd = oracle.decode_mx(inp["V"], inp["Vs"], oracle.MX_E2M1)
+    Kr, Vr = np.repeat(Kd, 2, axis=1), np.repeat(Vd, 2, axis=1)
+    S = np.einsum("bhid,bhjd->bhij", Qd, Kr) / math.sqrt(64)
+    want = np.einsum("bhij,bhjd->bhid", sp.softmax(S, axis=-1), Vr)
+    assert np.abs(got - want).max() < 1e-12
+    # quantisation error of the stand-in inputs is what the formats allow (one part in 16 for e4m3, in 4 for e2m1)
+    x, _ = wl._head_tensor(5, wl._T_Q, 2, 4, 41, 64, F32, cfg.qk_prescale)
+    assert np.abs(Qd - x).max() <= np.abs(x).max() / 8
