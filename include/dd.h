@@ -159,6 +159,26 @@ int dd_block_attention_cached_fp8v(const void *Qblk, const void *Kc, const void 
 size_t dd_block_attention_cached_fp8v_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d);
 
 /*
+ * Third precision workload: the verifier's attention on block-scaled ("MX") inputs, the storage of the OCP
+ * Microscaling Formats specification v1.0: every 32 consecutive elements of the head dimension share one
+ * power-of-two scale, an E8M0 code (real scale 2^(code - 127)); real value = scale x decoded element.  (The paper
+ * fixes no storage precision; Sec. 4.1 runs stock models.)  Same formula as dd_bidir_attention (Eq. 3 over all
+ * positions, Sec. 2.2):
+ *   Q [B,H,N,d], K [B,Hkv,N,d]: e4m3 codes, one byte per element;       Qs [B,H,N,d/32], Ks [B,Hkv,N,d/32]: E8M0
+ *   V [B,Hkv,N,d/2]: e2m1 codes (sign, 2 exponent bits with bias 1, 1 mantissa bit: +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}),
+ *      two per byte, the element with the even index in the low four bits;   Vs [B,Hkv,N,d/32]: E8M0
+ *   O [B,H,N,d]: DD_BF16.   All device pointers, dense, row-major; Q, K, V, O 16-byte aligned.
+ * Arithmetic: every element is decoded, multiplied by its block's scale and held as bf16 on its way into LDS - exact
+ * whenever the scaled value is a normal bf16 number or zero, which holds for every scale code in [27, 230]; outside
+ * that range (and for the NaN codes of e4m3 and E8M0) the result is unspecified.  The products run on the bf16
+ * matrix cores with fp32 accumulation; the weights are rounded to bf16.  No workspace; work is enqueued on `stream`.
+ * Errors: DD_ERR_NULL (a missing pointer), DD_ERR_SHAPE (as dd_bidir_attention; d is 64 or 128), DD_ERR_ALIGN,
+ * DD_ERR_LAUNCH.
+ */
+int dd_bidir_attention_mx(const void *Q, const void *Qs, const void *K, const void *Ks, const void *V, const void *Vs,
+                          void *O, int B, int H, int Hkv, int N, int d, void *stream);
+
+/*
  * The same call when the block is complete (Sec. 2.3: cached activations are reused across the denoising
  * steps of a block and refreshed at block granularity): the attention exactly as
  * dd_block_attention_cached computes it with Kblk/Vblk given, and in the same call

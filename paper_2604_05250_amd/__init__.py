@@ -54,6 +54,8 @@ def lib():
     L.dd_block_attention_cached_workspace_bytes.argtypes = [i, i, i, i, i, i, i, i]
     L.dd_bidir_attention_fp8v.restype = i
     L.dd_bidir_attention_fp8v.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, vp, vp, vp]
+    L.dd_bidir_attention_mx.restype = i
+    L.dd_bidir_attention_mx.argtypes = [vp, vp, vp, vp, vp, vp, vp, i, i, i, i, i, vp]
     L.dd_block_attention_cached_fp8v.restype = i
     L.dd_block_attention_cached_fp8v.argtypes = [vp, vp, vp, vp, i, i, vp, vp, i, i, i, i, i, vp, vp, vp, vp, sz, vp]
     L.dd_block_attention_cached_fp8v_workspace_bytes.restype = sz
@@ -97,7 +99,8 @@ EXPORTS = ("dd_strerror", "dd_version", "dd_bidir_attention", "dd_bidir_attentio
            "dd_block_attention_refresh", "dd_block_attention_refresh_workspace_bytes",
            "dd_block_attention_window", "dd_block_attention_window_workspace_bytes", "dd_cache_insert_rows",
            "dd_block_attention_batched", "dd_block_attention_batched_workspace_bytes",
-           "dd_bidir_attention_fp8v", "dd_block_attention_cached_fp8v", "dd_block_attention_cached_fp8v_workspace_bytes")
+           "dd_bidir_attention_fp8v", "dd_block_attention_cached_fp8v", "dd_block_attention_cached_fp8v_workspace_bytes",
+           "dd_bidir_attention_mx")
 
 
 # ---------------------------------------------------------------- marshalling helpers
@@ -281,6 +284,28 @@ def dd_bidir_attention_fp8v(Q, K, V, q_scale, k_scale, v_scale, O=None):
                                        _stream())
     if rc != 0:
         raise DDError(rc, "dd_bidir_attention_fp8v")
+    return O
+
+
+def dd_bidir_attention_mx(Q, Qs, K, Ks, V, Vs, O=None):
+    """Verifier attention on block-scaled inputs: Q [B,H,N,d], K [B,Hkv,N,d] e4m3 codes, V [B,Hkv,N,d/2] packed e2m1
+    codes, each with E8M0 scales [..., d/32] (all uint8) -> O bf16 (as int16 bit patterns unless O is given)."""
+    torch = _torch()
+    B, H, N, d = Q.shape
+    Hkv = K.shape[1]
+    if tuple(K.shape) != (B, Hkv, N, d) or tuple(V.shape) != (B, Hkv, N, d // 2):
+        raise ValueError("K must be [B,Hkv,N,d] and V [B,Hkv,N,d/2] matching Q")
+    if tuple(Qs.shape) != (B, H, N, d // 32) or tuple(Ks.shape) != (B, Hkv, N, d // 32) or tuple(Vs.shape) != (B, Hkv, N, d // 32):
+        raise ValueError("scales must be [..., d/32] matching their tensors")
+    for t, what in ((Q, "Q"), (K, "K"), (V, "V"), (Qs, "Qs"), (Ks, "Ks"), (Vs, "Vs")):
+        if t.element_size() != 1:
+            raise TypeError(f"{what}: one byte per entry expected")
+    if O is None:
+        O = torch.empty((B, H, N, d), dtype=torch.int16, device=V.device)
+    rc = lib().dd_bidir_attention_mx(_dev(Q, "Q"), _dev(Qs, "Qs"), _dev(K, "K"), _dev(Ks, "Ks"), _dev(V, "V"),
+                                     _dev(Vs, "Vs"), _dev(O, "O"), B, H, Hkv, N, d, _stream())
+    if rc != 0:
+        raise DDError(rc, "dd_bidir_attention_mx")
     return O
 
 

@@ -18,6 +18,7 @@ struct AttnKernelArgs {
     float *part_ml;            // [rows][splits][2] (running max in log2 units, partial sum)
     const float *q_scale, *k_scale;
     const float *v_scale;      // [B*Hkv] or nullptr: multiplier of the decoded V values (fp8 V)
+    const uint8_t *q_mx, *k_mx, *v_mx;   // block-scaled inputs: E8M0 scales [rows][d / 32] of Q, K, V; nullptr otherwise
     int B, H, Hkv, Nq, N;
     int kv_stride;             // rows between consecutive (batch, kv head) in K and V (N unless the call sees a window)
     int group;                 // H / Hkv

@@ -65,6 +65,35 @@ __device__ __forceinline__ uint4 fp8x8_to_bf16x8(uint2 w)
                       pack_bf16_trunc(c.x, c.y), pack_bf16_trunc(d.x, d.y));
 }
 
+// Block-scaled ("MX") storage, OCP Microscaling Formats v1.0: 32 consecutive elements of the head dimension share
+// one E8M0 scale 2^(code - 127).  Decoding is exact in bf16 as long as the result is a normal bf16 number (or zero).
+__device__ __forceinline__ float e8m0_to_f32(unsigned code)
+{
+    return __uint_as_float(code ? code << 23 : 0x00400000u);     // code 0 = 2^-127, a subnormal fp32
+}
+// eight bf16 (in four registers) times a power of two
+__device__ __forceinline__ uint4 bf16x8_times(uint4 w, float s)
+{
+    const unsigned u[4] = {w.x, w.y, w.z, w.w};
+    unsigned r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        r[i] = pack_bf16_trunc(__uint_as_float(u[i] << 16) * s, __uint_as_float(u[i] & 0xFFFF0000u) * s);
+    return make_uint4(r[0], r[1], r[2], r[3]);
+}
+// eight e2m1 codes (sign, two exponent bits with bias 1, one mantissa bit; four bits each, element 0 lowest) -> bf16
+__device__ __forceinline__ uint4 fp4x8_to_bf16x8(unsigned w)
+{
+    unsigned h[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned c = (w >> (4 * i)) & 15u, e = (c >> 1) & 3u, m = c & 1u;
+        const unsigned mag = e ? ((126u + e) << 7) | (m << 6) : (m ? 0x3F00u : 0u);   // (1 + m/2) 2^(e-1); 0.5 m
+        h[i] = mag | ((c & 8u) << 12);
+    }
+    return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+}
+
 // exchange between lane l and lane l^32 (one v_permlane32_swap), then combine
 __device__ __forceinline__ float half_swap_max(float x)
 {
@@ -89,9 +118,13 @@ constexpr float kRescaleSlack = 8.0f;
 //                block tensors, the key range may be split, partial states go to the workspace).
 // V8: V (and Vblk) are fp8 e4m3 as well, decoded exactly to bf16 on their way into LDS like K; their per-head
 //      scale multiplies the output once, at the end.
-template <int D, bool FP8, bool BLOCK, bool V8 = false>
+// MX: block-scaled inputs (verifier form only): Q and K with e4m3 elements, V with e2m1 elements (two per byte), each
+//      with one E8M0 scale per 32 elements of the head dimension (a.q_mx, a.k_mx, a.v_mx: [rows][D / 32] bytes).
+//      Every element is decoded, times its block's scale, to bf16 (exact) where the other forms decode fp8.
+template <int D, bool FP8, bool BLOCK, bool V8 = false, bool MX = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKernelArgs a)
 {
+    static_assert(!MX || (FP8 && !BLOCK && !V8), "block-scaled inputs: e4m3 Q/K, e2m1 V, verifier form");
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
     constexpr int KCH = TK * CH / kAttnThreads;      // K chunks staged per thread
     constexpr int KROWS = kAttnThreads / CH;         // K rows covered by one pass of the workgroup
@@ -99,7 +132,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
     constexpr int KELEM = FP8 ? 1 : 2;               // bytes per K element in memory
-    constexpr int VELEM = V8 ? 1 : 2;                // bytes per V element in memory
+    constexpr int VB8 = MX ? 4 : V8 ? 8 : 16;        // bytes of eight V elements in memory
+    constexpr int VROWB = D / 8 * VB8;               // bytes of a V row
     static_assert(KCH >= 1 && VTASKS <= kAttnThreads, "tile does not fit the staging scheme");
 
     __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
@@ -139,6 +173,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         uint4 w;
         if (FP8) w = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(a.Q) + off));
         else w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.Q) + off);
+        if (MX) w = bf16x8_times(w, e8m0_to_f32(a.q_mx[orow * (D / 32) + ks / 2]));   // dims 16 ks + 8 hh ..: block ks / 2
         qf[ks] = __builtin_bit_cast(bf16x8, w);
     }
     float c = a.scale_log2;                          // scores are exponentiated as 2^(s*c)
@@ -159,7 +194,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     // keys of task (g, e4): tile-local index (g/4)*32 + ((g/2)&1)*16 + 8*e4 + 4*(g&1) + e,  e = 0..3
     const int vt_key0 = (vt_g >> 2) * 32 + ((vt_g >> 1) & 1) * 16 + 8 * vt_e4 + 4 * (vt_g & 1);
     const uint8_t *const k_base = static_cast<const uint8_t *>(a.K) + kv_head * a.kv_stride * (size_t)(D * KELEM) + k_ch * (8 * KELEM);
-    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)(D * VELEM) + vt_dchunk * (8 * VELEM);
+    const uint8_t *const v_base = static_cast<const uint8_t *>(a.V) + kv_head * a.kv_stride * (size_t)VROWB + vt_dchunk * VB8;
 
     // address of key row j's chunk for this thread; rows past the range are clamped to the last
     // valid row (their scores are masked to -inf, their values multiply a zero probability)
@@ -174,8 +209,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         j = min(j, k_end - 1);
         if (BLOCK && (unsigned)j - (unsigned)bstart < (unsigned)a.block_len)
             return static_cast<const uint8_t *>(a.Vblk) +
-                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)(D * VELEM) + vt_dchunk * (8 * VELEM);
-        return v_base + (size_t)j * (D * VELEM);
+                   (kv_head * a.block_len + (size_t)(j - bstart)) * (size_t)VROWB + vt_dchunk * VB8;
+        return v_base + (size_t)j * VROWB;
     };
     // K is staged in windows of 64 keys that are offset by half a tile against the V tiles:
     // window w = keys [64w+32, 64w+96) relative to the range start.  A ring of 128 rows then always
@@ -189,6 +224,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
                 if (FP8) {
                     const uint2 r = *reinterpret_cast<const uint2 *>(p);
                     dst[i] = make_uint4(r.x, r.y, 0, 0);
+                    if (MX)                            // the chunk's block scale travels with it (dims 8 k_ch ..: block k_ch / 4)
+                        dst[i].z = a.k_mx[(kv_head * a.kv_stride + (size_t)min(k_begin + j0 + k_row0 + i * KROWS, k_end - 1)) * (D / 32) + k_ch / 4];
                 } else {
                     dst[i] = *reinterpret_cast<const uint4 *>(p);
                 }
@@ -200,7 +237,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         if (tid < VTASKS) {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (V8) {
+                if (MX) {
+                    const int j = min(k0 + vt_key0 + e, k_end - 1);
+                    vreg[e] = make_uint4(*reinterpret_cast<const unsigned *>(v_src(j)),
+                                         a.v_mx[(kv_head * a.kv_stride + (size_t)j) * (D / 32) + vt_dchunk / 4], 0, 0);
+                } else if (V8) {
                     const uint2 r = *reinterpret_cast<const uint2 *>(v_src(k0 + vt_key0 + e));
                     vreg[e] = make_uint4(r.x, r.y, 0, 0);    // decoded when it is stored to LDS
                 } else {
@@ -215,7 +256,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             if (i < nch) {
                 const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
                 uint4 w = src[i];
+                const unsigned code = w.z;
                 if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
+                if (MX) w = bf16x8_times(w, e8m0_to_f32(code));
                 Ks[row * CH + (k_ch ^ (row & 7))] = w;
             }
         }
@@ -225,7 +268,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             // 4 keys x 8 dims -> 8 dims x 4 keys
             uint4 vr[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) vr[e] = V8 ? fp8x8_to_bf16x8(make_uint2(vreg[e].x, vreg[e].y)) : vreg[e];
+            for (int e = 0; e < 4; ++e)
+                vr[e] = MX ? bf16x8_times(fp4x8_to_bf16x8(vreg[e].x), e8m0_to_f32(vreg[e].y))
+                      : V8 ? fp8x8_to_bf16x8(make_uint2(vreg[e].x, vreg[e].y)) : vreg[e];
             const unsigned r0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
             const unsigned r1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
             const unsigned r2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
@@ -554,6 +599,7 @@ void fill_kernel_args(const AttnArgs &a, AttnKernelArgs &k, int rows_per_wg, int
 {
     k.Q = a.Q; k.K = a.K; k.V = a.V; k.Kblk = a.Kblk; k.Vblk = a.Vblk; k.O = a.O;
     k.q_scale = a.q_scale; k.k_scale = a.k_scale; k.v_scale = a.v_scale;
+    k.q_mx = a.q_mx; k.k_mx = a.k_mx; k.v_mx = a.v_mx;
     k.B = a.B; k.H = a.H; k.Hkv = a.Hkv; k.Nq = a.Nq; k.N = a.N;
     k.kv_stride = a.kv_stride > 0 ? a.kv_stride : a.N;
     k.group = a.H / a.Hkv;
@@ -583,6 +629,12 @@ hipError_t launch_attention_mfma(const AttnArgs &a, hipStream_t stream)
     const dim3 grid((unsigned)blocks), block(kAttnThreads);
     if (a.Kblk == nullptr) k.block_len = 0;                                // no row is taken from block tensors
     hipError_t e;
+    if (a.q_mx != nullptr) {
+        // block-scaled inputs, verifier form
+        if (blk || a.k_mx == nullptr || a.v_mx == nullptr) return hipErrorInvalidValue;
+        return a.d == 128 ? launch(attn_mfma_kernel<128, true, false, false, true>, grid, block, stream, k)
+                          : launch(attn_mfma_kernel<64, true, false, false, true>, grid, block, stream, k);
+    }
     if (a.v_dtype == 2) {
         // fp8 V (with fp8 Q/K): this file's kernel serves every shape of the workload
         if (!blk) return a.d == 128 ? launch(attn_mfma_kernel<128, true, false, true>, grid, block, stream, k)

@@ -247,6 +247,25 @@ int dd_bidir_attention_fp8v(const void *Q, const void *K, const void *V, void *O
     return dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
 }
 
+int dd_bidir_attention_mx(const void *Q, const void *Qs, const void *K, const void *Ks, const void *V, const void *Vs,
+                          void *O, int B, int H, int Hkv, int N, int d, void *stream)
+{
+    if (!Q || !Qs || !K || !Ks || !V || !Vs || !O) return DD_ERR_NULL;
+    const float one = 1.0f;                    // (the per-head scales of the plain fp8 form are not part of this one)
+    const int rc = check_attention_common(B, H, Hkv, N, d, DD_FP8_E4M3, DD_BF16, &one, &one);
+    if (rc != DD_OK) return rc;
+    if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O)) return DD_ERR_ALIGN;
+    dd::AttnArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.Kblk = nullptr; a.Vblk = nullptr; a.O = O;
+    a.q_scale = nullptr; a.k_scale = nullptr;
+    a.q_mx = static_cast<const uint8_t *>(Qs); a.k_mx = static_cast<const uint8_t *>(Ks); a.v_mx = static_cast<const uint8_t *>(Vs);
+    a.B = B; a.H = H; a.Hkv = Hkv; a.Nq = N; a.N = N; a.d = d;
+    a.block_start = 0; a.block_len = 0;
+    a.qk_dtype = DD_FP8_E4M3; a.v_dtype = DD_BF16;     // (storage of V: packed e2m1; its decoded form is bf16)
+    a.splits = 1; a.workspace = nullptr;
+    return dd::launch_attention_mfma(a, static_cast<hipStream_t>(stream)) == hipSuccess ? DD_OK : DD_ERR_LAUNCH;
+}
+
 size_t dd_block_attention_cached_fp8v_workspace_bytes(int block_len, int B, int H, int Hkv, int N, int d)
 {
     return dd_block_attention_cached_workspace_bytes(block_len, B, H, Hkv, N, d, DD_FP8_E4M3, DD_BF16);

@@ -73,6 +73,9 @@ struct AttnArgs {
     const float *q_scale;  // [B*H] or nullptr
     const float *k_scale;  // [B*Hkv] or nullptr
     const float *v_scale = nullptr;  // [B*Hkv]: multiplier of the decoded V values; required when V is fp8
+    // block-scaled inputs (all three or none): E8M0 scale bytes, one per 32 elements of the head dimension, of Q
+    // [B*H*Nq][d/32], K and V [B*Hkv*N][d/32]; Q and K then hold e4m3 codes, V packed e2m1 codes (d/2 bytes per row)
+    const uint8_t *q_mx = nullptr, *k_mx = nullptr, *v_mx = nullptr;
     int B, H, Hkv, Nq, N, d;
     int kv_stride = 0;       // rows between consecutive (batch, kv head) of K and V; 0 = N (dense).  A call on a
                              // window of the cache passes K/V at the window's first row, N = the window length

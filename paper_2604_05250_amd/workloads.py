@@ -220,7 +220,11 @@ def mx_attention_inputs(cfg: StepConfig, seed: int = 0) -> dict:
     out = {}
     for name, tid, Hn, kind in (("Q", _T_Q, cfg.H, "e4m3"), ("K", _T_K, cfg.Hkv, "e4m3"), ("V", _T_V, cfg.Hkv, "e2m1")):
         x, _ = _head_tensor(seed, tid, cfg.B, Hn, cfg.N, cfg.d, F32, cfg.qk_prescale)
-        out[name], out[name + "s"] = mx_quantize(x, kind)
+        x = x.reshape(cfg.B * Hn, cfg.N, cfg.d)
+        with ThreadPoolExecutor(_threads()) as ex:
+            parts = list(ex.map(lambda i: mx_quantize(x[i], kind), range(cfg.B * Hn)))
+        out[name] = np.stack([p[0] for p in parts]).reshape(cfg.B, Hn, cfg.N, -1)
+        out[name + "s"] = np.stack([p[1] for p in parts]).reshape(cfg.B, Hn, cfg.N, cfg.d // 32)
     return out
 
 

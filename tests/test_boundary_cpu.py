@@ -90,6 +90,17 @@ def test_attention_argument_validation():
     assert L.dd_block_attention_window_workspace_bytes(64, 0, 1, 32, 32, 8192, 128, dd.BF16, dd.BF16) == 0
 
 
+def test_block_scaled_attention_argument_validation():
+    L = dd.lib()
+
+    def call(Q=FAKE, Qs=FAKE, K=FAKE, Ks=FAKE, V=FAKE, Vs=FAKE, O=FAKE, B=1, H=4, Hkv=2, N=64, d=128):
+        return L.dd_bidir_attention_mx(Q, Qs, K, Ks, V, Vs, O, B, H, Hkv, N, d, None)
+    for name in ("Q", "Qs", "K", "Ks", "V", "Vs", "O"):
+        assert call(**{name: None}) == -1
+    assert call(B=0) == -2 and call(N=0) == -2 and call(H=3) == -2 and call(d=96) == -2 and call(d=32) == -2
+    assert call(Q=FAKE + 4) == -6 and call(V=FAKE + 8) == -6 and call(O=FAKE + 2) == -6
+
+
 def test_cache_insert_argument_validation():
     L = dd.lib()
 
