@@ -106,6 +106,10 @@ def parse():
     ap.add_argument("--fp8v", action="store_true",
                     help="second precision workload: the configuration with Q, K and V all stored as e4m3 codes with "
                          "per-head scales (dd_bidir_attention_fp8v / dd_block_attention_cached_fp8v); meant for --config 5")
+    ap.add_argument("--mx", action="store_true",
+                    help="third precision workload: the verifier's attention on block-scaled inputs (e4m3 Q/K, e2m1 V, E8M0 "
+                         "scales per 32 elements: dd_bidir_attention_mx) drawn from the same fp32 values; the drafter's "
+                         "calls and the verification run as in the chosen config; meant for --config 5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="time only the configuration named by --config (the default run also times the other benchmark "
@@ -134,6 +138,7 @@ def main():
         light.no_graph = light.no_warm = light.no_cpu_baseline = True
         light.layers, light.calib_copy_mb, light.verify_mode = 0, 0, None
         light.parts, light.window, light.refresh_last, light.fp8v = "block,attention,verify", 0, False, False
+        light.mx = False
         out["per_config"] = {}
         for cid in (2, 4, 5, 3):
             if cid == args.config:
@@ -162,6 +167,10 @@ def run_config(args, config_id):
     if fp8v:
         import dataclasses
         cfg = dataclasses.replace(cfg, name=cfg.name + "_fp8v", qk_dtype=wl.FP8_E4M3, v_dtype=wl.FP8_E4M3)
+    mx = bool(getattr(args, "mx", False))
+    if mx and fp8v:
+        print("bench.py: --mx and --fp8v are different workloads", file=sys.stderr)
+        sys.exit(2)
     mode, tau = cfg.modes[-1]
     if args.verify_mode is not None:                     # another rule of the same call on the same inputs
         mode = {v: k for k, v in wl.MODE_NAMES.items()}[args.verify_mode]
@@ -177,6 +186,7 @@ def run_config(args, config_id):
 
     # ---- seeded inputs, generated on the host (the oracle reads the same arrays), resident in HBM before timing
     att = wl.attention_inputs(cfg, args.seed)
+    att_mx = wl.mx_attention_inputs(cfg, args.seed) if mx else None
     cache = wl.cache_inputs(cfg, args.seed)
     ver = wl.verify_inputs(cfg, args.seed)
     blocks = [wl.block_inputs(cfg, args.seed, k, k_scale=cache["k_scale"], v_scale=cache["v_scale"]) for k in range(cfg.K)]
@@ -185,6 +195,8 @@ def run_config(args, config_id):
     q_elems = cfg.B * cfg.H * cfg.N * cfg.d
     kv_elems = cfg.B * cfg.Hkv * cfg.N * cfg.d
     attn_bytes = q_elems * eb_qk + kv_elems * eb_qk + kv_elems * eb_v + q_elems * eb_v          # Q + K + V + O once
+    if mx:                                               # e4m3 Q, K; packed e2m1 V; one scale byte per 32 elements; bf16 O
+        attn_bytes = q_elems + kv_elems + kv_elems // 2 + (q_elems + 2 * kv_elems) // 32 + q_elems * 2
     verify_bytes = (2 if kl_mode else 1) * cfg.P * cfg.V * eb_l                               # logits read once
     blk_rows = cfg.B * cfg.H * cfg.bl * cfg.d
     block_bytes = kv_elems * (eb_qk + eb_v) + blk_rows * (eb_qk + eb_v)                       # cache + Qblk + O
@@ -197,8 +209,10 @@ def run_config(args, config_id):
 
     sets = []
     for _ in range(n_sets):
+        src = att_mx if mx else att
         sets.append({
-            "Q": up(att["Q"]), "K": up(att["K"]), "V": up(att["V"]),
+            "Q": up(src["Q"]), "K": up(src["K"]), "V": up(src["V"]),
+            "mx": tuple(up(att_mx[k]) for k in ("Qs", "Ks", "Vs")) if mx else None,
             "ld": up(ver["logits_d"]) if (kl_mode or "scores" in args.parts.split(",")) else None, "lv": up(ver["logits_v"]),
         })
     caches = [{"Kc": up(cache["Kc"]), "Vc": up(cache["Vc"])} for _ in range(n_caches)]
@@ -208,8 +222,8 @@ def run_config(args, config_id):
     mask = up(ver["mask"])
     blk_dev = [{"Q": up(b["Qblk"]), "K": up(b["Kblk"]), "V": up(b["Vblk"]), "qs": up(b["q_scale"]),
                 "bs": b["block_start"]} for b in blocks]
-    o_dtype = torch.int16 if fp8v else sets[0]["V"].dtype
-    O = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=o_dtype, device=dev)
+    o_dtype = torch.int16 if fp8v else caches[0]["Vc"].dtype
+    O = torch.empty((cfg.B, cfg.H, cfg.N, cfg.d), dtype=torch.int16 if mx else o_dtype, device=dev)
     Oblk = torch.empty((cfg.B, cfg.H, cfg.bl, cfg.d), dtype=o_dtype, device=dev)
     out_mask = torch.empty(cfg.P, dtype=torch.uint8, device=dev)
     out_tok = torch.empty(cfg.P, dtype=torch.int32, device=dev)
@@ -268,7 +282,9 @@ def run_config(args, config_id):
             dd.dd_unmask(u["ld"], u["mask"], dd.UNMASK_THRESH, args.unmask_threshold, cfg.B, cfg.bl, x_tokens=um_x,
                          out_mask=um_mask, out_tokens=um_tok, out_conf=um_conf, logit_dtype=cfg.logit_dtype)
         if marks: marks[4].record()
-        if "attention" in parts and fp8v:
+        if "attention" in parts and mx:
+            dd.dd_bidir_attention_mx(s["Q"], s["mx"][0], s["K"], s["mx"][1], s["V"], s["mx"][2], O=O)
+        elif "attention" in parts and fp8v:
             dd.dd_bidir_attention_fp8v(s["Q"], s["K"], s["V"], qs, ks, vs, O=O)
         elif "attention" in parts:
             dd.dd_bidir_attention(s["Q"], s["K"], s["V"], O=O, q_scale=qs, k_scale=ks,
@@ -411,7 +427,10 @@ def run_config(args, config_id):
         return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false>"
 
     # the peak the attention call is priced against: each contraction at the peak of its own operand type
-    if fp8v:
+    if mx:
+        attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, false, true>", "mfma", PEAK_BF16_TFLOPS
+        attn_peak_note = "block-scaled operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
+    elif fp8v:
         attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, true>", "mfma", PEAK_BF16_TFLOPS
         attn_peak_note = "fp8 operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
     elif cfg.qk_dtype == wl.F32:
@@ -430,9 +449,9 @@ def run_config(args, config_id):
         "metric": METRIC, "value": round(attn_tflops, 3), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "fp8_e4m3(QKV)" if fp8v else {wl.F32: "f32", wl.BF16: "bf16", wl.FP8_E4M3: "fp8_e4m3(QK)+bf16(V)"}[cfg.qk_dtype],
+        "dtype": "mxfp8_e4m3(QK)+mxfp4_e2m1(V)" if mx else "fp8_e4m3(QKV)" if fp8v else {wl.F32: "f32", wl.BF16: "bf16", wl.FP8_E4M3: "fp8_e4m3(QK)+bf16(V)"}[cfg.qk_dtype],
         "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
+        "config": {"workload": f"{cfg.name}{'_mx' if mx else ''}: B={cfg.B} H={cfg.H} Hkv={cfg.Hkv} N={cfg.N} d={cfg.d}, "
                                f"drafter block_len={cfg.bl} x K={cfg.K} steps, verify P={cfg.P} x V={cfg.V} "
                                f"mode={wl.MODE_NAMES[mode]} tau={tau}",
                    "baseline_config_index": config_id - 1, "input_sets_rotated": n_sets, "cache_copies_rotated": n_caches,
@@ -524,6 +543,10 @@ def run_config(args, config_id):
 
         def run_attn(n):
             t0 = time.perf_counter()
+            if mx:                                   # (decodes the whole tensors first: part of what this oracle costs)
+                oracle.bidir_attention_mx(att_mx["Q"], att_mx["Qs"], att_mx["K"], att_mx["Ks"], att_mx["V"], att_mx["Vs"],
+                                          rows=rows(n))
+                return time.perf_counter() - t0
             oracle.bidir_attention(att_host["Q"], att_host["K"], att_host["V"], cfg.qk_dtype, cfg.v_dtype,
                                    att_host["q_scale"], att_host["k_scale"], rows=rows(n), v_scale=att_host["v_scale"])
             return time.perf_counter() - t0

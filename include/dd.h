@@ -167,11 +167,13 @@ size_t dd_block_attention_cached_fp8v_workspace_bytes(int block_len, int B, int 
  *   Q [B,H,N,d], K [B,Hkv,N,d]: e4m3 codes, one byte per element;       Qs [B,H,N,d/32], Ks [B,Hkv,N,d/32]: E8M0
  *   V [B,Hkv,N,d/2]: e2m1 codes (sign, 2 exponent bits with bias 1, 1 mantissa bit: +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}),
  *      two per byte, the element with the even index in the low four bits;   Vs [B,Hkv,N,d/32]: E8M0
- *   O [B,H,N,d]: DD_BF16.   All device pointers, dense, row-major; Q, K, V, O 16-byte aligned.
- * Arithmetic: every element is decoded, multiplied by its block's scale and held as bf16 on its way into LDS - exact
- * whenever the scaled value is a normal bf16 number or zero, which holds for every scale code in [27, 230]; outside
- * that range (and for the NaN codes of e4m3 and E8M0) the result is unspecified.  The products run on the bf16
- * matrix cores with fp32 accumulation; the weights are rounded to bf16.  No workspace; work is enqueued on `stream`.
+ *   O [B,H,N,d]: DD_BF16.   All device pointers, dense, row-major; Q, K, V, O 16-byte aligned, the scale arrays
+ *   4-byte aligned.
+ * Arithmetic: S = Q K^T runs on the block-scaled matrix instruction (e4m3 operands, both operands' E8M0 scales applied
+ * by the hardware, fp32 accumulation); V is decoded, multiplied by its block's scale and held as bf16 on its way into
+ * LDS - exact whenever the scaled value is a normal bf16 number or zero, which holds for every scale code in
+ * [27, 230] - and O = P V runs on the bf16 matrix cores with the weights rounded to bf16.  Scale codes outside that
+ * range and the NaN codes of e4m3 and E8M0 give unspecified results.  No workspace; work is enqueued on `stream`.
  * Errors: DD_ERR_NULL (a missing pointer), DD_ERR_SHAPE (as dd_bidir_attention; d is 64 or 128), DD_ERR_ALIGN,
  * DD_ERR_LAUNCH.
  */

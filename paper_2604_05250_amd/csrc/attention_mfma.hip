@@ -33,6 +33,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef int intx8 __attribute__((ext_vector_type(8)));
 
 constexpr int TK = 64;            // keys per LDS tile
 constexpr int kRowsPerWave = 32;
@@ -120,7 +121,14 @@ constexpr float kRescaleSlack = 8.0f;
 //      scale multiplies the output once, at the end.
 // MX: block-scaled inputs (verifier form only): Q and K with e4m3 elements, V with e2m1 elements (two per byte), each
 //      with one E8M0 scale per 32 elements of the head dimension (a.q_mx, a.k_mx, a.v_mx: [rows][D / 32] bytes).
-//      Every element is decoded, times its block's scale, to bf16 (exact) where the other forms decode fp8.
+//      S = K Q^T runs on the block-scaled matrix instruction (v_mfma_scale_f32_32x32x64_f8f6f4: 64 head dims per
+//      instruction, the E8M0 scales of both operands applied by the hardware), K staying e4m3 in LDS; V's scales run
+//      along the head dimension, not along the keys its product contracts over, so V is decoded, times its block's
+//      scale, to bf16 (exact) on its way into LDS and O += V P runs as in the other forms.
+//      Operand layout of that instruction, found by comparing it with a plain sum for random operands and scales: of
+//      a lane's 32 operand bytes (row = lane % 32) the first 16 are elements 16 hh .. 16 hh + 15 of the 64 (hh = lane /
+//      32) and belong to scale block 0, the last 16 are elements 32 + 16 hh .. and belong to block 1; the scale of
+//      (row, block b) is taken from lane row + 32 b (its selected byte).
 template <int D, bool FP8, bool BLOCK, bool V8 = false, bool MX = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKernelArgs a)
 {
@@ -136,7 +144,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     constexpr int VROWB = D / 8 * VB8;               // bytes of a V row
     static_assert(KCH >= 1 && VTASKS <= kAttnThreads, "tile does not fit the staging scheme");
 
+    constexpr int KSX = D / 64;                      // MX: block-scaled matrix instructions per 32-key unit
+    constexpr int KCR = D / 16;                      // MX: 16-byte chunks of a K row as stored (e4m3)
     __shared__ uint4 Ks[2 * TK * CH];                // ring of 128 key rows: [key % 128][chunk ^ (key & 7)]
+    __shared__ unsigned Ksc[MX ? 2 * TK : 1];        // MX: the rows' E8M0 scales, D / 32 bytes each in one word
     __shared__ uint4 Vt[2][D * (TK / 8)];            // [dim][keygroup ^ swz(dim)], 8 keys per 16 bytes
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -173,8 +184,21 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         uint4 w;
         if (FP8) w = fp8x8_to_bf16x8(*reinterpret_cast<const uint2 *>(static_cast<const uint8_t *>(a.Q) + off));
         else w = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.Q) + off);
-        if (MX) w = bf16x8_times(w, e8m0_to_f32(a.q_mx[orow * (D / 32) + ks / 2]));   // dims 16 ks + 8 hh ..: block ks / 2
         qf[ks] = __builtin_bit_cast(bf16x8, w);
+    }
+    // MX: the operand bytes as they are (see the layout above) and the row's scales, this lane's block in byte 0 (+ 2 j)
+    intx8 qx[MX ? KSX : 1];
+    unsigned qsw = 0;
+    if constexpr (MX) {
+        const uint8_t *qrow = static_cast<const uint8_t *>(a.Q) + orow * D;
+#pragma unroll
+        for (int j = 0; j < KSX; ++j) {
+            const uint4 lo = *reinterpret_cast<const uint4 *>(qrow + 64 * j + 16 * hh);
+            const uint4 hi = *reinterpret_cast<const uint4 *>(qrow + 64 * j + 32 + 16 * hh);
+            qx[j] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        }
+        qsw = (D == 128 ? *reinterpret_cast<const unsigned *>(a.q_mx + orow * 4)
+                        : (unsigned)*reinterpret_cast<const unsigned short *>(a.q_mx + orow * 2)) >> (8 * hh);
     }
     float c = a.scale_log2;                          // scores are exponentiated as 2^(s*c)
     if (a.q_scale) c *= a.q_scale[b * a.H + head];
@@ -224,8 +248,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
                 if (FP8) {
                     const uint2 r = *reinterpret_cast<const uint2 *>(p);
                     dst[i] = make_uint4(r.x, r.y, 0, 0);
-                    if (MX)                            // the chunk's block scale travels with it (dims 8 k_ch ..: block k_ch / 4)
-                        dst[i].z = a.k_mx[(kv_head * a.kv_stride + (size_t)min(k_begin + j0 + k_row0 + i * KROWS, k_end - 1)) * (D / 32) + k_ch / 4];
+                    if (MX) {                          // the row's scales travel with it
+                        const size_t rg = kv_head * a.kv_stride + (size_t)min(k_begin + j0 + k_row0 + i * KROWS, k_end - 1);
+                        dst[i].z = D == 128 ? *reinterpret_cast<const unsigned *>(a.k_mx + rg * 4)
+                                            : (unsigned)*reinterpret_cast<const unsigned short *>(a.k_mx + rg * 2);
+                    }
                 } else {
                     dst[i] = *reinterpret_cast<const uint4 *>(p);
                 }
@@ -256,10 +283,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             if (i < nch) {
                 const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
                 uint4 w = src[i];
-                const unsigned code = w.z;
-                if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
-                if (MX) w = bf16x8_times(w, e8m0_to_f32(code));
-                Ks[row * CH + (k_ch ^ (row & 7))] = w;
+                if constexpr (MX) {
+                    // e4m3 as stored: 8 bytes into [row][16-byte chunk ^ (row % KCR)]
+                    char *p = reinterpret_cast<char *>(Ks) + (row * KCR + ((k_ch >> 1) ^ (row & (KCR - 1)))) * 16 + (k_ch & 1) * 8;
+                    *reinterpret_cast<uint2 *>(p) = make_uint2(w.x, w.y);
+                    if (k_ch == 0) Ksc[row] = w.z;
+                } else {
+                    if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
+                    Ks[row * CH + (k_ch ^ (row & 7))] = w;
+                }
             }
         }
     };
@@ -310,6 +342,29 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             for (int r = 0; r < 16; ++r) cin[r] = 0.f;
         }
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), qf[ks], cin, 0, 0, 0);
+    };
+
+    // MX: the 16-byte chunk `half` (0 / 1) of this lane's operand of block-scaled instruction j for key row `krow`
+    // of the ring: elements 64 j + 32 half + 16 hh .. +15 of the row
+    auto kx_chunk = [&](int krow, int j, int half) -> uint4 {
+        return Ks[krow * KCR + ((4 * j + 2 * half + hh) ^ (krow & (KCR - 1)))];
+    };
+    auto mx_mfma = [&](const uint4 &lo, const uint4 &hi, unsigned ksw, int j, const floatx16 &cin) -> floatx16 {
+        const intx8 kx = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+        // both operands e4m3; scale byte 0 of each scale register (the words are shifted so that it is this lane's
+        // block of this instruction)
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(kx, qx[j], cin, 0, 0, 0, (int)(ksw >> (16 * j)), 0,
+                                                               (int)(qsw >> (16 * j)));
+    };
+    auto qk_unit_mx = [&](int u, floatx16 &s) {         // S^T of unit u, all of it
+        const int krow = (u & 3) * 32 + l32;
+        const unsigned ksw = Ksc[krow] >> (8 * hh);
+        floatx16 cin;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cin[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < KSX; ++j) cin = mx_mfma(kx_chunk(krow, j, 0), kx_chunk(krow, j, 1), ksw, j, cin);
+        s = cin;
     };
 
     // keys past the end of the range score -inf (only the last tile can be ragged)
@@ -385,7 +440,45 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     auto unit = [&](int u, floatx16 &s_cur, bool have_next, floatx16 &s_nxt) {
         unsigned pk[2][4];
         update_max(s_cur);
-        if (have_next) {
+        if constexpr (MX) {
+            if (have_next) {
+                // the K operands of unit u+1 and the first V fragments of unit u, then: a block-scaled instruction
+                // every 8 / KSX exponential steps, the V products after them
+                const int krow = ((u + 1) & 3) * 32 + l32;
+                uint4 kf[2 * KSX];
+#pragma unroll
+                for (int m = 0; m < 2 * KSX; ++m) kf[m] = kx_chunk(krow, m >> 1, m & 1);
+                const unsigned ksw = Ksc[krow] >> (8 * hh);
+                constexpr int PD = 3;
+                uint4 fv[2 * DC];
+#pragma unroll
+                for (int j = 0; j < PD; ++j) fv[j] = frag(u, KS + j);
+                floatx16 cin;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) cin[r] = 0.f;
+#pragma unroll
+                for (int step = 0; step < 8; ++step) {
+                    if (step % (8 / KSX) == 0) {
+                        const int j = step / (8 / KSX);
+                        cin = mx_mfma(kf[2 * j], kf[2 * j + 1], ksw, j, cin);
+                    }
+                    exp_step(step, s_cur, pk);
+                }
+                s_nxt = cin;
+#pragma unroll
+                for (int j = 0; j < 2 * DC; ++j) {
+                    const int st = j / DC, i = j % DC;
+                    if (j + PD < 2 * DC) fv[j + PD] = frag(u, KS + j + PD);
+                    const uint4 pw = make_uint4(pk[st][0], pk[st][1], pk[st][2], pk[st][3]);
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fv[j]),
+                                                                     __builtin_bit_cast(bf16x8, pw), acc[i], 0, 0, 0);
+                }
+            } else {
+#pragma unroll
+                for (int step = 0; step < 8; ++step) exp_step(step, s_cur, pk);
+                pv((u >> 1) & 1, u & 1, pk);
+            }
+        } else if (have_next) {
             constexpr int NSLOT = KS + 2 * DC;              // matrix-core slots of the unit
             constexpr int PD = 3;                           // fragments requested this many slots ahead
             uint4 fq[NSLOT];
@@ -435,8 +528,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     __syncthreads();
     floatx16 s_a, s_b;
     if (wave_active) {
+        if constexpr (MX) qk_unit_mx(0, s_a);
+        else {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qk_step(0, ks, s_a);
+            for (int ks = 0; ks < KS; ++ks) qk_step(0, ks, s_a);
+        }
     }
     __syncthreads();   // unit 0's ring slot is rewritten at the end of stage 0: every wave must have read it
     // Stage t: on entry units 2t .. 2t+2 of K and tile t of V are in LDS, s_a holds the scores of unit 2t.

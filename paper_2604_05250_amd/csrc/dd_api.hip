@@ -255,6 +255,8 @@ int dd_bidir_attention_mx(const void *Q, const void *Qs, const void *K, const vo
     const int rc = check_attention_common(B, H, Hkv, N, d, DD_FP8_E4M3, DD_BF16, &one, &one);
     if (rc != DD_OK) return rc;
     if (misaligned16(Q) || misaligned16(K) || misaligned16(V) || misaligned16(O)) return DD_ERR_ALIGN;
+    // (a row's scale bytes are read as one word)
+    if (((reinterpret_cast<uintptr_t>(Qs) | reinterpret_cast<uintptr_t>(Ks) | reinterpret_cast<uintptr_t>(Vs)) & 3u) != 0) return DD_ERR_ALIGN;
     dd::AttnArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.Kblk = nullptr; a.Vblk = nullptr; a.O = O;
     a.q_scale = nullptr; a.k_scale = nullptr;

@@ -99,6 +99,7 @@ def test_block_scaled_attention_argument_validation():
         assert call(**{name: None}) == -1
     assert call(B=0) == -2 and call(N=0) == -2 and call(H=3) == -2 and call(d=96) == -2 and call(d=32) == -2
     assert call(Q=FAKE + 4) == -6 and call(V=FAKE + 8) == -6 and call(O=FAKE + 2) == -6
+    assert call(Qs=FAKE + 1) == -6 and call(Ks=FAKE + 2) == -6 and call(Vs=FAKE + 3) == -6   # a row's scales are read as a word
 
 
 def test_cache_insert_argument_validation():
