@@ -110,6 +110,9 @@ def parse():
                     help="third precision workload: the verifier's attention on block-scaled inputs (e4m3 Q/K, e2m1 V, E8M0 "
                          "scales per 32 elements: dd_bidir_attention_mx) drawn from the same fp32 values; the drafter's "
                          "calls and the verification run as in the chosen config; meant for --config 5")
+    ap.add_argument("--no-streams", action="store_true",
+                    help="skip the back-to-back streams of single parts after the timed steps (profiler runs: the timed "
+                         "steps are then the last launches of the trace)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true",
                     help="time only the configuration named by --config (the default run also times the other benchmark "
@@ -136,6 +139,7 @@ def main():
         light = copy.copy(args)
         light.steps, light.warmup, light.prewarm_ms = max(5, args.steps // 4), 3, min(args.prewarm_ms, 150.0)
         light.no_graph = light.no_warm = light.no_cpu_baseline = True
+        light.no_streams = False
         light.layers, light.calib_copy_mb, light.verify_mode = 0, 0, None
         light.parts, light.window, light.refresh_last, light.fp8v = "block,attention,verify", 0, False, False
         light.mx = False
@@ -357,7 +361,7 @@ def run_config(args, config_id):
     saved_parts = set(parts)
     stream = {}
     for name in ("attention", "verify", "block"):
-        if name not in saved_parts:
+        if name not in saved_parts or getattr(args, "no_streams", False):
             continue
         parts.clear()
         parts.add(name)
