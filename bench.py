@@ -432,8 +432,11 @@ def run_config(args, config_id):
 
     # the peak the attention call is priced against: each contraction at the peak of its own operand type
     if mx:
-        attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, false, true>", "mfma", PEAK_BF16_TFLOPS
-        attn_peak_note = "block-scaled operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
+        attn_kernel, attn_bound = f"attn_mfma_kernel<{cfg.d}, true, false, false, true>", "mfma"
+        attn_peak = 2.0 / (1.0 / PEAK_FP8_TFLOPS + 1.0 / PEAK_BF16_TFLOPS)
+        attn_peak_note = ("half of the FLOPs (S = Q K^T) run on the block-scaled fp8 matrix instruction (5.0 PFLOP/s), half "
+                          "(O = P V, V decoded to bf16 on its way into LDS) as bf16 MFMA (2.5 PFLOP/s): time-weighted peak "
+                          "3.33 PFLOP/s")
     elif fp8v:
         attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, true>", "mfma", PEAK_BF16_TFLOPS
         attn_peak_note = "fp8 operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
