@@ -8,7 +8,12 @@ on seeded synthetic inputs already resident in HBM.  Prints ONE JSON line:
   ms_per_step  = wall time of the whole step (events around all kernels of the step)
   roofline     = the attention kernel against the dense MFMA peak of its operand types
   roofline_verify = the verification kernels against the HBM peak
+  roofline_block  = the drafter's call against the HBM peak (every call on another copy of the cache: cold)
   cpu_baseline = the fp64 CPU oracle timed on a bounded sample of the same workload
+  per_config   = the same rates for the other benchmark configurations, timed in a light form (default run only)
+Rates come from events around each call inside the timed steps; back_to_back_* repeat each part alone as a stream of
+launches; `traffic` is the HBM bytes per call recorded in profiles/ for the kernel sources in the tree (else null).
+--fp8v / --mx time the reduced-precision workloads, --no-streams / --no-per-config / --no-graph shorten profiler runs.
 """
 from __future__ import annotations
 
