@@ -56,6 +56,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
@@ -381,12 +382,19 @@ void attn_wide_kernel(const AttnKernelArgs a)
     float c[QB], c_next[QB];                         // scores are exponentiated as 2^(s*c); the next row tile's factor
     using qfrag_t = std::conditional_t<FP8, intx2, intx4>;
     qfrag_t qf[QB][KS];                              // B operands of S^T = K Q^T (8 values each), kept in accumulation VGPRs
-    floatx16 acc[QB][DC], acc_l[QB];                 // O^T (unnormalised) and the row sums (all 16 registers equal)
+    // O^T (unnormalised), and the row sums of the weights.  The sums come from a 16x16x32 matrix instruction (half the
+    // matrix-core time of the 32x32x16 one) that takes the weights' B fragment as it is.  Read as that instruction's
+    // 16 x 32 B operand, lane l (column l % 16, k = 8 (l / 16) ..) holds, for column n: k 0-7 and 16-23 = the sixteen
+    // keys of row n, k 8-15 and 24-31 = those of row n + 16.  An A operand whose row 0 is one on the first kind of k and
+    // whose row 1 is one on the second (all else zero) therefore gives C[0][n] = sum of row n, C[1][n] = sum of row
+    // n + 16: lane n < 16 holds them in registers 0 and 1, every other lane and register holds zero.
+    floatx16 acc[QB][DC];
+    floatx4 acc_l[QB];
     auto clear_acc = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_l[q][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc_l[q][r] = 0.f;
 #pragma unroll
             for (int i = 0; i < DC; ++i)
 #pragma unroll
@@ -402,7 +410,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         asm volatile("s_nop 3" : "+v"(z));                   // the zeros are in place before a matrix instruction reads them
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc_l[q]) : "v"(z));
+            asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %1, 0" : "=a"(acc_l[q]) : "v"(z));
 #pragma unroll
             for (int i = 0; i < DC; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[q][i]) : "v"(z));
         }
@@ -419,8 +427,15 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int r = 0; r < 16; ++r) cinit[q][r] = 0.f;
     }
-    intx4 ones = {0x3F803F80, 0x3F803F80, 0x3F803F80, 0x3F803F80};         // eight bf16 1.0
+    // A operand of the row-sum instruction (see acc_l): lane l holds A[l % 16][8 (l / 16) .. + 7]
+    const int lsel_on = (lane == 0 || lane == 32 || lane == 17 || lane == 49) ? 0x3F803F80 : 0;   // bf16 1.0 twice, or zero
+    intx4 ones = {lsel_on, lsel_on, lsel_on, lsel_on};
     asm volatile("" : "+v"(ones));                   // held in registers instead of being rebuilt per use
+    // the sum of this lane's row (l32) of row block q: from lane l32 % 16, register l32 / 16 (every lane must call it)
+    auto row_sum = [&](int q) __attribute__((always_inline)) {
+        const float lo = __shfl(acc_l[q][0], lane & 15), hi = __shfl(acc_l[q][1], lane & 15);
+        return (lane & 16) ? hi : lo;
+    };
 
     // operand addresses inside a tile buffer (bytes), without the unit offset
     int k_off[KF], v_off[DC];
@@ -513,6 +528,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 // merge kernel, row r of the call at [(r * splits + split)]
 #pragma unroll
                 for (int q = 0; q < QB; ++q) {
+                    const float l_row = row_sum(q);
                     const int v = t.v0 + wave * kRowsWave + q * 32 + (ln & 31);
                     if (v >= rows_total) continue;
                     const size_t slot = (t.row_base + v) * (size_t)a.splits + split;
@@ -525,7 +541,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                                 make_float4(acc[q][i][4 * q4], acc[q][i][4 * q4 + 1], acc[q][i][4 * q4 + 2], acc[q][i][4 * q4 + 3]);
                     if ((ln >> 5) == 0) {
                         a.part_ml[slot * 2] = mc_done[q];
-                        a.part_ml[slot * 2 + 1] = acc_l[q][0];
+                        a.part_ml[slot * 2 + 1] = l_row;
                     }
                 }
                 return;
@@ -534,7 +550,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         char *wbase = region + (ln & 31) * OPITCH + (ln >> 5) * 8;
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            const float inv = __builtin_amdgcn_rcpf(acc_l[q][0]);         // 1 ulp; the result is rounded to bf16
+            const float inv = __builtin_amdgcn_rcpf(row_sum(q));          // 1 ulp; the result is rounded to bf16
 #pragma unroll
             for (int i = 0; i < DC; ++i)
 #pragma unroll
@@ -767,7 +783,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
                 const uint4 pw = make_uint4(pk_prev[q][st][0], pk_prev[q][st][1], pk_prev[q][st][2], pk_prev[q][st][3]);
-                acc_l[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ones),
+                acc_l[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ones),
                                                                    __builtin_bit_cast(bf16x8, pw), acc_l[q], 0, 0, 0);
                 piece(NQK + st * (DC + 1) * QB + DC * QB + q);
             }
@@ -785,8 +801,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 // (sixteen registers at a time, each block back in accumulation registers before the next is read:
                 // left alone, the compiler holds all 160 products in vector registers at once)
                 asm volatile("" : "+a"(acc_l[q]));
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc_l[q][r] *= corr[q];
+                // (register 0 of lanes 0-15 is the sum of the lane's own row, register 1 that of the row sixteen on,
+                // whose factor lane + 16 holds; everything else is zero)
+                acc_l[q][0] *= corr[q];
+                acc_l[q][1] *= __shfl(corr[q], (lane + 16) & 63);
                 asm volatile("" : "+a"(acc_l[q]));
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
