@@ -61,6 +61,7 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef int intx8 __attribute__((ext_vector_type(8)));
 
 constexpr int TKW = 64;                 // keys per tile
 constexpr int QB = 2;                   // 32-row query blocks per wave
@@ -99,11 +100,14 @@ __device__ __forceinline__ float vmax3(float a, float b, float c)
     return r;
 }
 // S = K Q^T step with the result in architectural VGPRs and the Q fragment read from accumulation VGPRs.
-// bf16: 8 values per lane and operand (16 bytes); fp8 e4m3: 8 values in 8 bytes.  Same shape, same layout.
+// bf16: 8 values per lane and operand (16 bytes), 16 head dims per instruction.  fp8 e4m3: 32 values per lane and
+// operand (32 bytes), 64 head dims per instruction - the only fp8 matrix instruction that runs at twice the bf16
+// rate (64 cycles for four times the products; the 32x32x16 fp8 one takes the 32 cycles of its bf16 twin).  Any
+// assignment of head dims to the bytes of the operands will do as long as K and Q use the same.
 template <bool FP8, typename KT, typename QT>
 __device__ __forceinline__ void qk_first(floatx16 &s, const KT kf, const QT qfrag)
 {
-    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x16_fp8_fp8 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
+    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(kf), "a"(qfrag));
 }
 // the same from an addend: the block starts from `init` (minus the softmax reference of its query rows)
@@ -115,7 +119,7 @@ __device__ __forceinline__ void qk_first_from(floatx16 &s, const KT kf, const QT
 template <bool FP8, typename KT, typename QT>
 __device__ __forceinline__ void qk_next(floatx16 &s, const KT kf, const QT qfrag)
 {
-    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x16_fp8_fp8 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
+    if constexpr (FP8) asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(kf), "a"(qfrag));
 }
 
@@ -169,13 +173,15 @@ void attn_wide_kernel(const AttnKernelArgs a)
 {
     static_assert(!(FOLD && FP8), "the scale cannot be folded into fp8 operands");
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per V / O row
-    constexpr int KS = D / 16;                       // MFMA k-steps over the head dim
+    static_assert(!FP8 || D % 64 == 0, "an fp8 matrix instruction takes 64 head dims");
+    constexpr int KS = FP8 ? D / 64 : D / 16;        // S = K Q^T: matrix instructions per 32-key unit and row block
     constexpr int DC = D / 32;                       // 32-wide chunks of the head dim
     constexpr int ROWB = D * 2;                      // bytes per V / O row
     constexpr int KROWB = FP8 ? D : 2 * D;           // bytes per Q / K row
     constexpr int KCH = KROWB / 16;                  // 16-byte chunks per Q / K row
-    constexpr int KF = KROWB / 32;                   // 16-byte fragments per lane and Q / K row, each feeding ...
-    constexpr int MPF = KS / KF;                     // ... this many MFMAs (bf16 1, fp8 2)
+    constexpr int KF = KROWB / 32;                   // 16-byte fragments per lane and Q / K row; an instruction takes ...
+    constexpr int FPM = KF / KS;                     // ... this many of them (bf16 1, fp8 2)
+    static_assert(FPM == (FP8 ? 2 : 1), "operand widths");
     constexpr int DMA_ROWS = 1024 / ROWB;            // rows moved by one wave-wide 16-byte-per-lane load (V)
     constexpr int KDMA_ROWS = 1024 / KROWB;          // ... (Q, K)
     constexpr int NDMA = TKW / DMA_ROWS / 4;         // such loads per wave per V tile
@@ -380,8 +386,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
 
     // ---- per-lane state of the two query blocks
     float c[QB], c_next[QB];                         // scores are exponentiated as 2^(s*c); the next row tile's factor
-    using qfrag_t = std::conditional_t<FP8, intx2, intx4>;
-    qfrag_t qf[QB][KS];                              // B operands of S^T = K Q^T (8 values each), kept in accumulation VGPRs
+    using qfrag_t = std::conditional_t<FP8, intx8, intx4>;
+    qfrag_t qf[QB][KS];                              // B operands of S^T = K Q^T (one per instruction), kept in accumulation VGPRs
     // O^T (unnormalised), and the row sums of the weights.  The sums come from a 16x16x32 matrix instruction (half the
     // matrix-core time of the 32x32x16 one) that takes the weights' B fragment as it is.  Read as that instruction's
     // 16 x 32 B operand, lane l (column l % 16, k = 8 (l / 16) ..) holds, for column n: k 0-7 and 16-23 = the sixteen
@@ -456,13 +462,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
         return __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
                    reinterpret_cast<const char *>(kb) + sub * 32 * KROWB + k_off[f]));
     };
-    // the operand of MFMA j out of its fragment
-    auto k_op = [&](const intx4 &fr, int j) __attribute__((always_inline)) {
-        if constexpr (FP8) {
-            const intx2 lo = {fr.x, fr.y}, hi = {fr.z, fr.w};
-            return (j & 1) ? hi : lo;
-        }
-        else return fr;
+    // the A operand of an fp8 instruction out of its two fragments
+    auto k_pair = [](const intx4 &f0, const intx4 &f1) __attribute__((always_inline)) {
+        return intx8{f0.x, f0.y, f0.z, f0.w, f1.x, f1.y, f1.z, f1.w};
     };
     // V^T fragment jv of the unit `sub` of a tile buffer: dims 32i + l32 (i = jv % DC),
     // keys 32 sub + 16 st + 4hh + {0..3, 8..11} (st = jv / DC)
@@ -478,6 +480,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     auto install_q = [&](const Tile &t) __attribute__((always_inline)) {
         int ln = lane;
         asm volatile("" : "+v"(ln));
+        intx4 q_half = {0, 0, 0, 0};
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
 #pragma unroll
@@ -497,12 +500,16 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     }
                     qf[q][f] = ws;
                     asm volatile("" : "+a"(qf[q][f]));
-                } else {
-#pragma unroll
-                    for (int m = 0; m < MPF; ++m) {
-                        qf[q][f * MPF + m] = k_op(w, m);
-                        asm volatile("" : "+a"(qf[q][f * MPF + m]));
+                } else if constexpr (FP8) {
+                    // fragments 2 j and 2 j + 1 are the two halves of instruction j's operand
+                    if (f % 2 == 0) q_half = w;
+                    else {
+                        qf[q][f / 2] = k_pair(q_half, w);
+                        asm volatile("" : "+a"(qf[q][f / 2]));
                     }
+                } else {
+                    qf[q][f] = w;
+                    asm volatile("" : "+a"(qf[q][f]));
                 }
             }
             const int v = min(t.v0 + wave * kRowsWave + q * 32 + (ln & 31), rows_total - 1);
@@ -592,7 +599,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
     };
 
-    intx4 kfr[RD];
+    constexpr int RDK = FP8 ? KF : RD;               // K fragment ring (fp8: a unit's four fragments, taken two at a time)
+    intx4 kfr[RDK];
     bf16x8 vfr[RD];
     // Pipeline step.  In: s_cur = S(u), pk_prev = P(u-1).  Out: pk_cur = P(u), s_nxt = S(u+1).
     // kb / ksub: tile buffer and unit of K(u+1); vb / vsub: those of V(u-1).
@@ -617,7 +625,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         constexpr bool MASKABLE = BLOCK || decltype(maskable)::value;
         if (!PRIMED) {
 #pragma unroll
-            for (int j = 0; j < RD; ++j) kfr[j] = k_frag(kb, ksub, j);
+            for (int j = 0; j < RDK; ++j) kfr[j] = k_frag(kb, ksub, j);
         }
         // keys of unit u's tile outside the rows that count (see tile_at) score -inf
         const TileAt cur_at = tile_at(cur, u >> 1);
@@ -749,16 +757,26 @@ void attn_wide_kernel(const AttnKernelArgs a)
         for (int j = 0; j < KS; ++j) {
 #pragma unroll
             for (int q = 0; q < QB; ++q) {
-                const int f = j / MPF;                       // fragment of this k-step; it is free after its last use
-                if constexpr (FOLD) {
-                    if (j == 0) qk_first_from(s_nxt[q], kfr[0], qf[q][0], cinit[q]);   // starts from minus the reference
-                    else qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);
+                if constexpr (FP8) {
+                    // the unit's four fragments are all in registers; the first V fragments: two with the first
+                    // instruction, one with the second
+                    if (j == 0) qk_first<true>(s_nxt[q], k_pair(kfr[0], kfr[1]), qf[q][0]);
+                    else qk_next<true>(s_nxt[q], k_pair(kfr[2 * j], kfr[2 * j + 1]), qf[q][j]);
+                    static_assert(!FP8 || (KS == 2 && RD == 3), "V fragment schedule of the fp8 form");
+                    if (q == 0 && j == 0) { vfr[0] = v_frag(vb, vsub, 0); vfr[1] = v_frag(vb, vsub, 1); }
+                    if (q == 0 && j == 1) vfr[2] = v_frag(vb, vsub, 2);
                 } else {
-                    if (j == 0) qk_first<FP8>(s_nxt[q], k_op(kfr[0], 0), qf[q][0]);
-                    else qk_next<FP8>(s_nxt[q], k_op(kfr[f % RD], j), qf[q][j]);
+                    const int f = j;                             // fragment of this k-step; it is free after its use
+                    if constexpr (FOLD) {
+                        if (j == 0) qk_first_from(s_nxt[q], kfr[0], qf[q][0], cinit[q]);   // starts from minus the reference
+                        else qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);
+                    } else {
+                        if (j == 0) qk_first<false>(s_nxt[q], kfr[0], qf[q][0]);
+                        else qk_next<false>(s_nxt[q], kfr[f % RD], qf[q][j]);
+                    }
+                    if (q == QB - 1 && f + RD < KF) kfr[f % RD] = k_frag(kb, ksub, f + RD);
+                    if (q == 0 && j >= KS - RD) vfr[j - (KS - RD)] = v_frag(vb, vsub, j - (KS - RD));
                 }
-                if (q == QB - 1 && j % MPF == MPF - 1 && f + RD < KF) kfr[f % RD] = k_frag(kb, ksub, f + RD);
-                if (q == 0 && j >= KS - RD) vfr[j - (KS - RD)] = v_frag(vb, vsub, j - (KS - RD));
                 piece(j * QB + q);
             }
         }
@@ -775,7 +793,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
                                                                         acc[q][i], 0, 0, 0);
                     if (q == QB - 1) {
                         if (jv + RD < 2 * DC) vfr[jv % RD] = v_frag(vb, vsub, jv + RD);
-                        else if (CHAIN) kfr[jv + RD - 2 * DC] = k_frag(kb, 1, jv + RD - 2 * DC);
+                        else if (CHAIN) {
+                            kfr[jv + RD - 2 * DC] = k_frag(kb, 1, jv + RD - 2 * DC);
+                            if (FP8 && jv == 2 * DC - 1) kfr[RDK - 1] = k_frag(kb, 1, RDK - 1);   // (the fourth of four)
+                        }
                     }
                     piece(NQK + st * (DC + 1) * QB + i * QB + q);
                 }
@@ -788,6 +809,11 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 piece(NQK + st * (DC + 1) * QB + DC * QB + q);
             }
         }
+        // The score instructions are written as assembly, so the compiler takes their results for complete at
+        // once.  Where S(u+1) is never read (the drafter's last step) it would hand those registers to a V
+        // fragment, whose load can return before the instruction, still in flight, writes over it.  This use
+        // keeps them allocated until the instructions are long done.
+        asm volatile("" :: "v"(s_nxt[0]), "v"(s_nxt[1]));
 #pragma unroll
         for (int pr = 0; pr < 16; ++pr)
             if (exp_piece(2 * pr + 1) >= NP - kPackLag) pack_pair(pr);
@@ -905,8 +931,14 @@ void attn_wide_kernel(const AttnKernelArgs a)
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int q = 0; q < QB; ++q) {
-            if (ks == 0) qk_first<FP8>(s0[q], k_op(k_frag(K0, 0, 0), 0), qf[q][0]);      // (FOLD: from zero, the reference is 0)
-            else qk_next<FP8>(s0[q], k_op(k_frag(K0, 0, ks / MPF), ks), qf[q][ks]);
+            if constexpr (FP8) {
+                const intx8 kx = k_pair(k_frag(K0, 0, 2 * ks), k_frag(K0, 0, 2 * ks + 1));
+                if (ks == 0) qk_first<true>(s0[q], kx, qf[q][0]);
+                else qk_next<true>(s0[q], kx, qf[q][ks]);
+            } else {
+                if (ks == 0) qk_first<false>(s0[q], k_frag(K0, 0, 0), qf[q][0]);       // (FOLD: from zero, the reference is 0)
+                else qk_next<false>(s0[q], k_frag(K0, 0, ks), qf[q][ks]);
+            }
         }
 #pragma unroll
     for (int q = 0; q < QB; ++q)
@@ -915,6 +947,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
     asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
+    if constexpr (FP8) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));   // (an instruction of twice the passes)
     step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur, T_{}, T_{});
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
 
