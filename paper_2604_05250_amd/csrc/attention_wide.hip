@@ -64,13 +64,12 @@ typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef int intx8 __attribute__((ext_vector_type(8)));
 
 constexpr int TKW = 64;                 // keys per tile
-constexpr int QB = 2;                   // 32-row query blocks per wave
-constexpr int kRowsWave = 32 * QB;
-constexpr int kRowsWGWide = 4 * kRowsWave;
-constexpr int kPackLag = 2;              // pieces between an exponential and its conversion to bf16
-constexpr float kSlack = 8.0f;          // the maximum in use is raised when exceeded by 2^8
+constexpr int kRowsWGWide = 256;        // query rows per workgroup: four waves of two 32-row blocks each ...
+constexpr int kRowsWGNarrow = 128;      // ... or of one (the drafter's form when that spares it the key splits)
+[[maybe_unused]] constexpr int kPackLag = 2;             // pieces between an exponential and its conversion to bf16
+[[maybe_unused]] constexpr float kSlack = 8.0f;         // the maximum in use is raised when exceeded by 2^8
 constexpr int kFoldMinKeys = 1024;      // key rows from which scaling Q once per row tile pays (see FOLD below)
-constexpr float kFoldMargin = 7.0f;     // folded form: the reference is set this far above a unit's maximum (log2 units)
+[[maybe_unused]] constexpr float kFoldMargin = 7.0f;    // folded form: the reference is set this far above a unit's maximum (log2 units)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ unsigned pack_bf16_rne(float lo, float hi)
@@ -167,11 +166,21 @@ using F_ = std::false_type;
 // registers by LDS reads instead of kept in registers - half the gain; the same mechanism without the folded
 // scale, one multiplication per score - slower than the row-maximum form, which therefore stays for fp8 and
 // per-head scales.)
-template <int D, bool FP8, bool BLOCK, bool FOLD = false>
+// QB: 32-row query blocks per wave.  2 is the form described above; 1 (the drafter's call only) halves the row
+// tile to 128 rows - every K and V fragment then feeds one matrix instruction instead of two, but twice as many
+// workgroups share the call, which can spare it the key splits, their partial states and the merge launch.
+template <int D, bool FP8, bool BLOCK, bool FOLD = false, int QB = 2>
 __global__ __launch_bounds__(kAttnThreads) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void attn_wide_kernel(const AttnKernelArgs a)
 {
+    // The body exists in the device pass only.  The host pass needs the kernel's handle, not its code, and, given
+    // lambdas whose parameter types depend on a template parameter around assembly it cannot check, it was seen to
+    // drop the handle without a diagnostic: the library then fails to load with an undefined symbol.
+#if defined(__HIP_DEVICE_COMPILE__)
     static_assert(!(FOLD && FP8), "the scale cannot be folded into fp8 operands");
+    static_assert(QB == 2 || (QB == 1 && BLOCK), "one or two row blocks per wave");
+    constexpr int kRowsWave = 32 * QB, kRowsWG = 4 * kRowsWave;
+    constexpr int NE = 16 * QB;                      // scores per lane and unit
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per V / O row
     static_assert(!FP8 || D % 64 == 0, "an fp8 matrix instruction takes 64 head dims");
     constexpr int KS = FP8 ? D / 64 : D / 16;        // S = K Q^T: matrix instructions per 32-key unit and row block
@@ -265,7 +274,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
         r.bh0 = b * a.H + kvh * a.group;             // first query head of the group
         r.row_base = (size_t)r.bh0 * a.Nq;           // row of virtual row 0 in Q and O
-        r.v0 = rt * kRowsWGWide;                     // first virtual row of the tile
+        r.v0 = rt * kRowsWG;                     // first virtual row of the tile
         r.kvs = bk;                                  // index into k_scale
         return r;
     };
@@ -354,7 +363,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         int ln = lane;
         asm volatile("" : "+v"(ln));
         const int drow = ln / KCH, dpos = ln % KCH;
-        if (__builtin_expect(t.v0 + kRowsWGWide <= rows_total, 1)) {
+        if (__builtin_expect(t.v0 + kRowsWG <= rows_total, 1)) {
             // whole tile: 1 KB per load, contiguous on both sides - scalar bases 8 KB apart and immediates;
             // the chunk a lane fetches depends on the row modulo 8, hence on the parity of a 4-row load
             unsigned off[2];
@@ -421,9 +430,14 @@ void attn_wide_kernel(const AttnKernelArgs a)
             for (int i = 0; i < DC; ++i) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc[q][i]) : "v"(z));
         }
     };
-    float mc[QB] = {FOLD ? 0.f : -INFINITY, FOLD ? 0.f : -INFINITY};   // maximum (FOLD: reference) in use, log2 units, equal in both lane halves
-    float thr[QB] = {-INFINITY, -INFINITY};          // raw scores above (mc + slack) / c raise the maximum in use
-    float mc_done[QB] = {-INFINITY, -INFINITY};      // the finished tile's maximum in use (BLOCK: part of its state)
+    float mc[QB];                                    // maximum (FOLD: reference) in use, log2 units, equal in both lane halves
+    float thr[QB];                                   // raw scores above (mc + slack) / c raise the maximum in use
+    float mc_done[QB];                               // the finished tile's maximum in use (BLOCK: part of its state)
+#pragma unroll
+    for (int q = 0; q < QB; ++q) {
+        mc[q] = FOLD ? 0.f : -INFINITY;
+        thr[q] = mc_done[q] = -INFINITY;
+    }
     bool ref_unset = false;                          // FOLD: a row tile has begun with wholly masked units, no reference yet (uniform)
     unsigned seen0 = 0u;                             // ... what the or of a unit's weights starts from: the tested bit while that is so
     floatx16 cinit[QB];                              // FOLD: what a score block starts from: -mc in all 16 registers
@@ -651,13 +665,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
                     }
             }
         }
-        float corr[QB], tpart[QB], pe[32];
+        float corr[QB], tpart[QB], pe[NE];
         bool changed = false;
-        // element e = 2 pr + (0/1) of the exponential stream is S(u)[q = pr & 1][r = 2 (pr >> 1) + (0/1)]
-        auto exp_piece = [](int e) constexpr { int t = MAXC; while (!(e < 32 * (t - MAXC + 1) / EXC)) ++t; return t; };
+        // element e = 2 pr + (0/1) of the exponential stream is S(u)[q = pr % QB][r = 2 (pr / QB) + (0/1)]
+        auto exp_piece = [](int e) constexpr { int t = MAXC; while (!(e < NE * (t - MAXC + 1) / EXC)) ++t; return t; };
         unsigned seen = seen0, w_even = 0u;                  // FOLD: the weights' bit patterns or-ed together
         auto pack_pair = [&](int pr) __attribute__((always_inline)) {
-            const int q = pr & 1, r = (pr >> 1) * 2;
+            const int q = pr % QB, r = (pr / QB) * 2;
             unsigned w = pack_bf16_rne(pe[2 * pr], pe[2 * pr + 1]);
             asm volatile("" : "+v"(w));                      // P(u) is only consumed a step later: keep its
             pk_cur[q][r >> 3][(r & 7) >> 1] = w;             // computation here, beside the matrix-core work
@@ -702,7 +716,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 changed = !opening;                          // (zeros need no rescaling, and 2^-delta may overflow there)
                 // written by vector instructions, read as the addend of the next S = K Q^T, which the compiler's
                 // hazard padding does not see
-                asm volatile("s_nop 7" : "+v"(cinit[0]), "+v"(cinit[1]));
+                if constexpr (QB == 2) asm volatile("s_nop 7" : "+v"(cinit[0]), "+v"(cinit[QB - 1]));
+                else asm volatile("s_nop 7" : "+v"(cinit[0]));
             }
         };
         // everything of the step that is not an MFMA, dealt out over the NP pieces
@@ -721,7 +736,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
                 if (t == MAXC - 1) {
                     // Each lane half compares the maximum of its own keys with the threshold; whether any
                     // lane is above it is wave-uniform (always true for the first unit of a row tile).
-                    changed = (__builtin_amdgcn_ballot_w64(tpart[0] > thr[0]) | __builtin_amdgcn_ballot_w64(tpart[1] > thr[1])) != 0;
+                    changed = (__builtin_amdgcn_ballot_w64(tpart[0] > thr[0]) | __builtin_amdgcn_ballot_w64(tpart[QB - 1] > thr[QB - 1])) != 0;
                     if (__builtin_expect(changed, 0)) {      // rare: raise the maxima in use
 #pragma unroll
                         for (int q = 0; q < QB; ++q) {
@@ -736,8 +751,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
             }
             if (t >= MAXC && t < MAXC + EXC) {               // (FOLD: the last pieces carry no exponentials)
 #pragma unroll
-                for (int e = 32 * (t - MAXC) / EXC; e < 32 * (t - MAXC + 1) / EXC; ++e) {
-                    const int pr = e >> 1, q = pr & 1, r = (pr >> 1) * 2 + (e & 1);
+                for (int e = NE * (t - MAXC) / EXC; e < NE * (t - MAXC + 1) / EXC; ++e) {
+                    const int pr = e >> 1, q = pr % QB, r = (pr / QB) * 2 + (e & 1);
                     if constexpr (FOLD) pe[e] = fast_exp2(s_cur[q][r]);
                     else pe[e] = fast_exp2(fmaf(s_cur[q][r], c[q], -mc[q]));
                 }
@@ -745,7 +760,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
             // pairs completed in the previous piece are packed now: a transcendental result cannot be
             // consumed by the very next instruction without a bubble
 #pragma unroll
-            for (int pr = 0; pr < 16; ++pr)
+            for (int pr = 0; pr < NE / 2; ++pr)
                 if (exp_piece(2 * pr + 1) == t - kPackLag) pack_pair(pr);
             if constexpr (FOLD) {
                 if (t == CHK) check_reference();
@@ -813,9 +828,10 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // once.  Where S(u+1) is never read (the drafter's last step) it would hand those registers to a V
         // fragment, whose load can return before the instruction, still in flight, writes over it.  This use
         // keeps them allocated until the instructions are long done.
-        asm volatile("" :: "v"(s_nxt[0]), "v"(s_nxt[1]));
 #pragma unroll
-        for (int pr = 0; pr < 16; ++pr)
+        for (int q = 0; q < QB; ++q) asm volatile("" :: "v"(s_nxt[q]));
+#pragma unroll
+        for (int pr = 0; pr < NE / 2; ++pr)
             if (exp_piece(2 * pr + 1) >= NP - kPackLag) pack_pair(pr);
         if (CANFIN && fin) {                                 // uniform: the row tile is complete
             write_out(cur);
@@ -874,13 +890,13 @@ void attn_wide_kernel(const AttnKernelArgs a)
              vbuf(I_<1 - PAR>{}), tile_at(last && !BLOCK ? nxt : cur, vtile).v, F_{}, false, cur, maskable, F_{});
         if (!BLOCK && KIND == 1 && has_next) dma_q(nxt);               // after this stage's tile loads: see the barrier below
         if (last) {
-            mc_done[0] = mc[0];
-            mc_done[1] = mc[1];
-            if constexpr (!FOLD) {
-                mc[0] = mc[1] = -INFINITY;                   // the second step starts the next tile's softmax
-                thr[0] = thr[1] = -INFINITY;
-                c[0] = c_next[0];
-                c[1] = c_next[1];
+#pragma unroll
+            for (int q = 0; q < QB; ++q) {
+                mc_done[q] = mc[q];
+                if constexpr (!FOLD) {
+                    mc[q] = thr[q] = -INFINITY;              // the second step starts the next tile's softmax
+                    c[q] = c_next[q];
+                }
             }                                                // (FOLD: the second step is a tile's first and resets the reference)
         }
         step(last ? 0 : 2 * sp + 2, s0, s1, pk1, pk0, kbuf(I_<1 - PAR>{}), 1, vbuf(I_<PAR>{}), 1, T_{}, F_{}, F_{},
@@ -891,7 +907,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         // output rows - can stay in flight: wait until only that many are outstanding.
         constexpr int NST = kRowsWave / (64 / (ROWB / 16));  // output stores per wave
         if (!BLOCK && KIND == 1 && has_next) wait_loads_and_sync(I_<NQDMA>{});
-        else if (last && cur.v0 + kRowsWGWide <= rows_total) {
+        else if (last && cur.v0 + kRowsWG <= rows_total) {
             wait_loads_and_sync(I_<NST>{});
         }
         else wait_loads_and_sync(I_<0>{});
@@ -925,8 +941,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
     asm volatile("" ::: "memory");
     install_q(cur);
     wait_loads_and_sync(I_<0>{});
-    c[0] = c_next[0];
-    c[1] = c_next[1];
+#pragma unroll
+    for (int q = 0; q < QB; ++q) c[q] = c_next[q];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -946,8 +962,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
         for (int t = 0; t < 8; ++t) pk1[q][t >> 2][t & 3] = 0u;
     // the compiler does not know that the statements above are matrix instructions whose results
     // need 11 more wait states before a vector instruction may read them
-    asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));
-    if constexpr (FP8) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[1]));   // (an instruction of twice the passes)
+    if constexpr (QB == 2) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]), "+v"(s0[QB - 1]));
+    else asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]));
+    if constexpr (FP8) asm volatile("s_nop 15\n\ts_nop 15" : "+v"(s0[0]));                     // (an instruction of twice the passes)
     step(0, s0, s1, pk1, pk0, K0, 1, V0, 0, F_{}, F_{}, F_{}, K0, cur.k, V0, cur.v, F_{}, false, cur, T_{}, T_{});
     __syncthreads();   // K tile 0 is overwritten during stage 0: every wave must be done with it
 
@@ -973,6 +990,7 @@ void attn_wide_kernel(const AttnKernelArgs a)
         cur = nxt;
         t_cur += t_stride;
     }
+#endif  // __HIP_DEVICE_COMPILE__
 }
 
 }  // namespace
@@ -1006,32 +1024,53 @@ hipError_t launch_attention_wide(const AttnArgs &a, hipStream_t stream)
                 : launch(attn_wide_kernel<64, false, false>, grid, block, stream, k);
 }
 
-// The drafter's call on the wide kernel: worth it when a kv head has a few hundred query rows (GQA groups
-// times the block length), which makes the call compute bound.  Every part of the key stream must be empty
-// or at least one tile long.
+// The drafter's call on the wide kernel: worth it from 65 query rows per kv head (GQA groups times the block
+// length; up to 64 the bf16 call streams), which makes the call compute bound.  Every part of the key stream must
+// be empty or at least one tile long.
 bool attn_wide_block_fits(const AttnArgs &a)
 {
     if (a.qk_dtype == 0 || a.v_dtype != 1 || (a.qk_dtype == 2 && a.d != 128)) return false;
-    if ((long)(a.H / a.Hkv) * a.Nq < 192) return false;
+    if ((long)(a.H / a.Hkv) * a.Nq < tune("DD_TUNE_BLOCK_WIDE_MIN_ROWS", 65)) return false;
     // a tile is 64 whole rows of its source: the cache, and the block tensors when rows are spliced in from them
     return a.N >= TKW && (a.Kblk == nullptr || a.block_len >= TKW);
 }
 
-// Key splits of that form: until there is about one workgroup per compute unit, at least two tiles each.
-int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N)
+// Key splits of that form for `tiles` row tiles: as many as keep the workgroups at or under one per compute unit
+// (more would run in a second round, and every split adds partial-state traffic and merge work), at least two
+// key tiles each.
+static int wide_block_splits_for(long tiles, int N)
 {
-    const long tiles = (long)B * Hkv * (((long)(H / Hkv) * block_len + kRowsWGWide - 1) / kRowsWGWide);
-    long s = (256 + tiles - 1) / tiles;
+    long s = 256 / tiles;
     const long max_s = N / (2 * TKW) > 1 ? N / (2 * TKW) : 1;
     if (s > max_s) s = max_s;
     if (s > 16) s = 16;
     return (int)(s < 1 ? 1 : s);
 }
 
+// Rows per workgroup of that form: 256, or 128 where a kv head has no more rows than that, or where the smaller
+// tile alone gives every compute unit a workgroup, so that the call needs no key splits.
+int attn_wide_block_rows(int block_len, int B, int H, int Hkv, int N)
+{
+    const long forced = tune("DD_TUNE_BLOCK_WIDE_ROWS", 0);
+    if (forced == kRowsWGNarrow || forced == kRowsWGWide) return (int)forced;
+    const long rows = (long)(H / Hkv) * block_len, heads = (long)B * Hkv;
+    if (rows <= kRowsWGNarrow) return kRowsWGNarrow;
+    const long t_wide = heads * ((rows + kRowsWGWide - 1) / kRowsWGWide);
+    const long t_narrow = heads * ((rows + kRowsWGNarrow - 1) / kRowsWGNarrow);
+    return wide_block_splits_for(t_wide, N) > 1 && wide_block_splits_for(t_narrow, N) == 1 ? kRowsWGNarrow : kRowsWGWide;
+}
+
+int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N)
+{
+    const int per_wg = attn_wide_block_rows(block_len, B, H, Hkv, N);
+    return wide_block_splits_for((long)B * Hkv * (((long)(H / Hkv) * block_len + per_wg - 1) / per_wg), N);
+}
+
 hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
 {
     AttnKernelArgs k;
-    fill_kernel_args(a, k, kRowsWGWide, TKW);
+    const bool narrow = attn_wide_block_rows(a.Nq, a.B, a.H, a.Hkv, a.N) == kRowsWGNarrow;
+    fill_kernel_args(a, k, narrow ? kRowsWGNarrow : kRowsWGWide, TKW);
     if (a.Kblk == nullptr) k.block_len = 0;                // no row is taken from the block tensors
     // the kernel splits the LIST of tiles (not the key range) evenly
     int splits;
@@ -1054,11 +1093,19 @@ hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream)
     k.part_ml = k.part_o ? k.part_o + rows * (size_t)splits * a.d : nullptr;
     const dim3 grid((unsigned)((long)a.B * a.Hkv * k.row_tiles * splits)), block(kAttnThreads);
     const bool fold = a.q_scale == nullptr && a.k_scale == nullptr && a.N >= kFoldMinKeys;
-    const hipError_t e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true>, grid, block, stream, k)
-                       : a.d == 128 ? (fold ? launch(attn_wide_kernel<128, false, true, true>, grid, block, stream, k)
-                                            : launch(attn_wide_kernel<128, false, true>, grid, block, stream, k))
-                                    : (fold ? launch(attn_wide_kernel<64, false, true, true>, grid, block, stream, k)
-                                            : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k));
+    hipError_t e;
+    if (narrow)
+        e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true, false, 1>, grid, block, stream, k)
+          : a.d == 128 ? (fold ? launch(attn_wide_kernel<128, false, true, true, 1>, grid, block, stream, k)
+                               : launch(attn_wide_kernel<128, false, true, false, 1>, grid, block, stream, k))
+                       : (fold ? launch(attn_wide_kernel<64, false, true, true, 1>, grid, block, stream, k)
+                               : launch(attn_wide_kernel<64, false, true, false, 1>, grid, block, stream, k));
+    else
+        e = a.qk_dtype == 2 ? launch(attn_wide_kernel<128, true, true>, grid, block, stream, k)
+          : a.d == 128 ? (fold ? launch(attn_wide_kernel<128, false, true, true>, grid, block, stream, k)
+                               : launch(attn_wide_kernel<128, false, true>, grid, block, stream, k))
+                       : (fold ? launch(attn_wide_kernel<64, false, true, true>, grid, block, stream, k)
+                               : launch(attn_wide_kernel<64, false, true>, grid, block, stream, k));
     return e != hipSuccess ? e : finish_attention(a, splits, stream);
 }
 

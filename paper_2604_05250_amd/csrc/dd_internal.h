@@ -34,6 +34,8 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipSt
 //   DD_TUNE_BIDIR_STREAM=0/1   small bf16 verifier calls off / on the streaming kernel
 //   DD_TUNE_BLOCK_STREAM=0     drafter calls with few query rows off the streaming kernel
 //   DD_TUNE_BLOCK_WIDE=0       drafter calls with many query rows off the wide-wave kernel
+//   DD_TUNE_BLOCK_WIDE_ROWS=128/256   query rows per workgroup of such a call
+//   DD_TUNE_BLOCK_WIDE_MIN_ROWS=n     query rows per kv head from which it takes that kernel
 // Returns the variable's integer value, or `dflt` when hooks are off or the variable is unset.
 int tune(const char *name, int dflt);
 
@@ -103,6 +105,7 @@ hipError_t launch_attention_stream(const AttnArgs &a, hipStream_t stream);  // b
 // key splits it then uses (a.splits must hold them), the launch (+ merge kernel)
 bool attn_wide_block_fits(const AttnArgs &a);
 int attn_wide_block_splits(int block_len, int B, int H, int Hkv, int N);
+int attn_wide_block_rows(int block_len, int B, int H, int Hkv, int N);      // 256 or 128 query rows per workgroup
 hipError_t launch_attention_wide_block(const AttnArgs &a, hipStream_t stream);
 bool attn_stream_fits(const AttnArgs &a);
 

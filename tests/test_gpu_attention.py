@@ -316,7 +316,7 @@ BLOCK_SMALL = [
     (1, 2, 2, 100, 64, 16, 0, wl.BF16), (1, 2, 2, 100, 64, 16, 84, wl.BF16), (2, 4, 2, 333, 128, 32, 101, wl.BF16),
     (1, 8, 2, 1000, 128, 64, 936, wl.FP8_E4M3), (1, 2, 1, 150, 64, 1, 77, wl.BF16), (1, 4, 4, 128, 64, 16, 64, wl.F32),
     (2, 2, 1, 600, 128, 48, 200, wl.F32), (1, 16, 2, 2048, 128, 64, 1024, wl.BF16), (1, 1, 1, 64, 128, 64, 0, wl.BF16),
-    # 65 .. 191 query rows per kv head at a benchmark-like size (between the streaming and the wide kernel)
+    # 65 .. 191 query rows per kv head at a benchmark-like size
     (2, 8, 4, 2048, 128, 64, 1024, wl.BF16), (1, 32, 32, 2048, 128, 96, 1000, wl.BF16), (1, 4, 2, 2048, 128, 80, 1900, wl.BF16),
     (1, 8, 4, 2048, 128, 64, 1984, wl.FP8_E4M3),
 ]
@@ -347,9 +347,9 @@ def test_block_each_kernel(monkeypatch, stream, B, H, Hkv, N, d, bl, bs):
         assert_attention_close(got, ref, wl.BF16, f"block kernel stream={stream} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} fresh={fresh}")
 
 
-# A drafter call with a few hundred query rows per kv head (GQA group x block length >= 192) runs on the wide
-# kernel when every part of its key stream (cache before the block, block tensors, cache after it) is empty or at
-# least 64 rows long; DD_TUNE_BLOCK_WIDE=0 keeps it on the other kernels.
+# A drafter call with more than 64 query rows per kv head (GQA group x block length) runs on the wide kernel when
+# every part of its key stream (cache before the block, block tensors, cache after it) is empty or at least 64
+# rows long; DD_TUNE_BLOCK_WIDE=0 keeps it on the other kernels.
 WIDE_BLOCK = [
     # (B, H, Hkv, N, d, bl, block_start, qk): block at the start / end / inside, ragged parts (overlapping last
     # tiles), key splits that begin at an overlapping tile (N=321, bs=193), 192 and 320 rows per kv head, fp8, d=64
@@ -376,6 +376,33 @@ def test_block_many_rows_each_kernel(monkeypatch, wide, B, H, Hkv, N, d, bl, bs,
         ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, qk, wl.BF16, Kb, Vb,
                                             blk["q_scale"], cache["k_scale"])
         assert_attention_close(got, ref, qk, f"block wide={wide} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk} fresh={fresh}")
+
+
+# The wide kernel's drafter form has a second row tile, 128 rows per workgroup (one 32-row block per wave), taken
+# where a kv head has no more rows than that or where it spares the call its key splits (cfg5: 256 workgroups
+# instead of 128 x 2 splits).  DD_TUNE_BLOCK_WIDE_ROWS forces the tile on every shape: 66, 96, 128 and 160 rows per
+# kv head at N = 2048 among them.
+NARROW_BLOCK = WIDE_BLOCK + [
+    (2, 8, 4, 2048, 128, 64, 1024, wl.BF16), (1, 32, 32, 2048, 128, 96, 1000, wl.BF16), (1, 4, 2, 2048, 128, 80, 1900, wl.BF16),
+    (1, 8, 4, 2048, 128, 64, 1984, wl.FP8_E4M3), (1, 4, 2, 300, 64, 64, 130, wl.BF16), (3, 2, 1, 777, 128, 33, 700, wl.BF16),
+    (16, 8, 2, 1024, 128, 64, 512, wl.FP8_E4M3),            # 32 kv heads x 256 rows: the tile is chosen, not forced
+]
+
+
+@pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", NARROW_BLOCK)
+def test_block_128_row_tiles(monkeypatch, B, H, Hkv, N, d, bl, bs, qk):
+    monkeypatch.setenv("DD_TUNE_BLOCK_WIDE", "1")
+    if B < 16:
+        monkeypatch.setenv("DD_TUNE_BLOCK_WIDE_ROWS", "128")
+    cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=wl.BF16, bl=bl, prompt=0, G=N)
+    cache = wl.cache_inputs(cfg, seed=bs + N + 1)
+    blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+    for fresh in (True, False):
+        Kb, Vb = (blk["Kblk"], blk["Vblk"]) if fresh else (None, None)
+        got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, Kb, Vb, blk["q_scale"], cache["k_scale"])
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, qk, wl.BF16, Kb, Vb,
+                                            blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, qk, f"block 128-row tiles {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk} fresh={fresh}")
 
 
 @pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", BLOCK_SMALL)
