@@ -430,10 +430,10 @@ def run_config(args, config_id):
         fp8 = c.qk_dtype == wl.FP8_E4M3
         if wide_tiles >= 192 and c.N >= 512 and (not fp8 or c.d == 128):
             fold = not fp8 and c.N >= 1024          # bf16 without per-head scales: the folded-scale form
-            return f"attn_wide_kernel<{c.d}, {'true' if fp8 else 'false'}, false, {'true' if fold else 'false'}>"
+            return f"attn_wide_kernel<{c.d}, {'true' if fp8 else 'false'}, false, {'true' if fold else 'false'}, 2>"
         if not fp8 and c.B * c.Hkv * -(-group * c.N // 128) < 256:
             return f"attn_stream_kernel<{c.d}>"
-        return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false>"
+        return f"attn_mfma_kernel<{c.d}, {'true' if fp8 else 'false'}, false, false, false>"
 
     # the peak the attention call is priced against: each contraction at the peak of its own operand type
     if mx:
