@@ -35,6 +35,9 @@ SHAPES = [
     (2, 16, 4, 2048, 128, 64, wl.BF16, {"DD_TUNE_BLOCK_WIDE": "0"}),
     (4, 4, 4, 128, 64, 16, wl.F32, {}),                                    # fp32 kernel
     (3, 2, 1, 600, 128, 48, wl.F32, {}),
+    (3, 4, 2, 1000, 128, 64, wl.FP8_E4M3, {}),                             # wide kernel, 128-row tiles (128 rows per kv head)
+    (5, 6, 2, 700, 128, 40, wl.BF16, {}),                                  # ... 120 rows per kv head, blocks shorter than a key tile
+    (2, 16, 4, 2048, 128, 64, wl.BF16, {"DD_TUNE_BLOCK_WIDE_ROWS": "128"}),   # ... forced on 256 rows per kv head
 ]
 
 

@@ -62,6 +62,8 @@ SHAPES = [
     (1, 4, 1, 4096, 128, 128, 2000, wl.BF16, {}),                             # wide kernel, key splits
     (1, 4, 1, 512, 128, 64, 448, wl.BF16, {"DD_TUNE_BLOCK_WIDE": "0"}),
     (1, 8, 2, 400, 64, 64, 64, wl.BF16, {}),
+    (2, 4, 2, 640, 128, 64, 256, wl.FP8_E4M3, {}),                            # wide kernel, 128-row tiles
+    (1, 4, 2, 4096, 128, 64, 2000, wl.BF16, {}),                              # ... key splits
     (1, 4, 4, 128, 64, 16, 64, wl.F32, {}),                                   # fp32 kernel
     (2, 2, 1, 600, 128, 48, 200, wl.F32, {}),
     (1, 1, 1, 64, 128, 64, 0, wl.BF16, {}),                                   # the block is the whole sequence

@@ -36,6 +36,8 @@ SHAPES = [
     (1, 4, 1, 4096, 128, 128, 2000, 1024, 2048, wl.BF16, {}),                        # wide kernel, key splits
     (1, 4, 1, 4096, 128, 128, 2000, 1990, 150, wl.BF16, {}),                         # parts shorter than a tile
     (1, 8, 2, 400, 64, 64, 64, 0, 256, wl.BF16, {}),
+    (2, 4, 2, 640, 128, 64, 256, 128, 384, wl.FP8_E4M3, {}),                         # wide kernel, 128-row tiles
+    (1, 4, 2, 4096, 128, 64, 2000, 1990, 150, wl.BF16, {}),                          # ... parts shorter than a tile
     (1, 4, 4, 128, 64, 16, 64, 32, 64, wl.F32, {}),                                  # fp32 kernel
     (2, 2, 1, 600, 128, 48, 200, 150, 301, wl.F32, {}),
 ]
