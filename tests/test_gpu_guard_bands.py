@@ -93,6 +93,8 @@ BLOCK = [
     (1, 4, 1, 1000, 128, 80, 700, wl.BF16, {}), (1, 4, 1, 4097, 128, 128, 2000, wl.BF16, {}),
     (2, 8, 2, 641, 128, 64, 256, wl.FP8_E4M3, {}), (2, 2, 1, 600, 128, 48, 200, wl.F32, {}),
     (1, 2, 1, 150, 64, 1, 77, wl.BF16, {}),
+    # the wide kernel's 128-row tiles: a partly filled tile (2 x 40 rows), fp8 with key splits
+    (3, 4, 2, 333, 128, 40, 101, wl.BF16, {}), (1, 4, 2, 4097, 128, 64, 2000, wl.FP8_E4M3, {}),
 ]
 
 
