@@ -59,6 +59,27 @@ def test_bidir_mx_scales_block_by_block():
     assert np.abs(flat - np.repeat(mean, 2, axis=1)).max() <= 2 ** -7 * np.abs(mean).max()
 
 
+def test_bidir_mx_extreme_v_scales():
+    # V blocks whose scale codes are so small that the scaled values are no normal bf16 numbers (codes 0 and 1: the
+    # kernel's table decode hands those to its plain path) among ordinary ones, and, in other blocks, a very large one
+    # (230, i.e. 2^103: the unnormalised fp32 accumulation of some hundred such values times weights of up to 2^8
+    # still fits)
+    cfg = wl.custom_config(B=1, H=4, Hkv=2, N=160, d=128, prompt=0, G=160)
+    inp = wl.mx_attention_inputs(cfg, 11)
+    rng = np.random.default_rng(4)
+    Vs = inp["Vs"].copy()
+    tiny = rng.random(Vs.shape) < 0.2
+    Vs[tiny] = rng.integers(0, 2, size=int(tiny.sum()), dtype=np.uint8)
+    got = gpu_bidir(dict(inp, Vs=Vs))
+    ref = ora_bidir(dict(inp, Vs=Vs))
+    assert_attention_close(got, ref, FP8, "MX bidir, V scale codes 0 and 1")
+    Vs = np.where(rng.random(Vs.shape) < 0.1, np.uint8(230), inp["Vs"]).astype(np.uint8)
+    got = gpu_bidir(dict(inp, Vs=Vs))
+    ref = ora_bidir(dict(inp, Vs=Vs))
+    assert np.isfinite(got).all()
+    assert np.linalg.norm(got - ref) <= 5e-3 * np.linalg.norm(ref)
+
+
 def test_bidir_mx_cfg5_shape():
     # the block-scaled form of the throughput workload (B16, 32 query / 8 kv heads, N 2048): a stratified sample of
     # rows (one per 128-row block of every (batch, kv head)) against the oracle
