@@ -443,8 +443,11 @@ def run_config(args, config_id):
                           "(O = P V, V decoded to bf16 on its way into LDS) as bf16 MFMA (2.5 PFLOP/s): time-weighted peak "
                           "3.33 PFLOP/s")
     elif fp8v:
-        attn_kernel, attn_bound, attn_peak = f"attn_mfma_kernel<{cfg.d}, true, false, true>", "mfma", PEAK_BF16_TFLOPS
-        attn_peak_note = "fp8 operands decoded to bf16 on their way into LDS: both contractions on the bf16 MFMA, 2.5 PFLOP/s"
+        attn_kernel, attn_bound = f"attn_mfma_kernel<{cfg.d}, true, false, true, false>", "mfma"
+        attn_peak = 2.0 / (1.0 / PEAK_FP8_TFLOPS + 1.0 / PEAK_BF16_TFLOPS)
+        attn_peak_note = ("half of the FLOPs (S = Q K^T) run as fp8 MFMA on the e4m3 operands as stored (5.0 PFLOP/s), half "
+                          "(O = P V, V decoded to bf16 on its way into LDS) as bf16 MFMA (2.5 PFLOP/s): time-weighted peak "
+                          "3.33 PFLOP/s")
     elif cfg.qk_dtype == wl.F32:
         attn_kernel, attn_bound, attn_peak = "attn_f32_kernel", "alu", PEAK_FP32_VALU_TFLOPS
         attn_peak_note = "fp32 inputs: vector ALUs (no fp32 MFMA path is used), 157.3 TFLOP/s"

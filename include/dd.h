@@ -142,8 +142,10 @@ size_t dd_block_attention_cached_workspace_bytes(int block_len, int B, int H, in
  * as dd_bidir_attention / dd_block_attention_cached:
  *   Q, K, V (and Qblk, Kc, Vc, Kblk, Vblk): DD_FP8_E4M3;   O: DD_BF16;   q_scale [B*H], k_scale, v_scale [B*Hkv]:
  *   all required; the block's fresh rows Kblk / Vblk use the cache's k_scale / v_scale.
- * Arithmetic: every code is decoded exactly (e4m3 -> bf16) on its way into LDS, the products run on the bf16
- * matrix cores with fp32 accumulation, the weights are rounded to bf16, v_scale multiplies the output once.
+ * Arithmetic: the scores are products of the e4m3 codes of Q and K as stored (fp8 matrix cores, fp32 accumulation;
+ * the per-head scales multiply the exponent); V's codes are decoded exactly (e4m3 -> bf16) on their way into LDS and
+ * O = P V runs on the bf16 matrix cores with fp32 accumulation, the weights P rounded to bf16; v_scale multiplies
+ * the output once.
  * dd_bidir_attention_fp8v needs no workspace; the block call's comes from its own query function.
  * Shapes, alignment and errors as for the calls above (a missing scale: DD_ERR_NULL).
  */

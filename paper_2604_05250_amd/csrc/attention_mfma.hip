@@ -4,7 +4,8 @@
 // block attention over the cached K/V (Sec. 2.3).
 //
 // Layout of the computation (one wave = 32 query rows, one workgroup = 4 waves = 128 rows):
-//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K fragment (from LDS), B = Q (registers).
+//   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K fragment (from LDS), B = Q (registers); fp8 Q/K: the 64-deep
+//                 fp8 instruction on the e4m3 bytes as stored (see KRAW below).
 //                 The 32x32 result puts one QUERY per lane column and 16 KEYS in the lane's
 //                 registers, so the softmax row reductions are in-register plus one
 //                 exchange between the two lane halves (v_permlane32_swap).
@@ -141,7 +142,7 @@ constexpr float kRescaleSlack = 8.0f;
 // BLOCK = false: verifier attention (all rows of a head attend all keys, O written directly).
 // BLOCK = true : drafter block attention (key rows of the active block may come from the fresh
 //                block tensors, the key range may be split, partial states go to the workspace).
-// V8: V (and Vblk) are fp8 e4m3 as well, decoded exactly to bf16 on their way into LDS like K; their per-head
+// V8: V (and Vblk) are fp8 e4m3 as well, decoded exactly to bf16 on their way into LDS; their per-head
 //      scale multiplies the output once, at the end.
 // MX: block-scaled inputs (verifier form only): Q and K with e4m3 elements, V with e2m1 elements (two per byte), each
 //      with one E8M0 scale per 32 elements of the head dimension (a.q_mx, a.k_mx, a.v_mx: [rows][D / 32] bytes).
@@ -157,6 +158,12 @@ template <int D, bool FP8, bool BLOCK, bool V8 = false, bool MX = false>
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKernelArgs a)
 {
     static_assert(!MX || (FP8 && !BLOCK && !V8), "block-scaled inputs: e4m3 Q/K, e2m1 V, verifier form");
+    // KRAW: every fp8 form keeps Q and K as e4m3 bytes - K in LDS as stored, Q in registers - and computes S = K Q^T on
+    // the 64-deep fp8 matrix instruction (twice the bf16 rate, and no vector instruction decodes K); without block
+    // scales the instruction's scale operands are the neutral code 127 (2^0) and the per-head fp32 scales stay in the
+    // exponent's factor.  "MX" in the names below is historical: the code path is this one.
+    constexpr bool KRAW = FP8;
+    static_assert(!KRAW || D % 64 == 0, "an fp8 matrix instruction takes 64 head dims");
     constexpr int CH = D / 8;                        // 16-byte chunks (8 bf16) per K row
     constexpr int KCH = TK * CH / kAttnThreads;      // K chunks staged per thread
     constexpr int KROWS = kAttnThreads / CH;         // K rows covered by one pass of the workgroup
@@ -211,9 +218,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
         qf[ks] = __builtin_bit_cast(bf16x8, w);
     }
     // MX: the operand bytes as they are (see the layout above) and the row's scales, this lane's block in byte 0 (+ 2 j)
-    intx8 qx[MX ? KSX : 1];
-    unsigned qsw = 0;
-    if constexpr (MX) {
+    intx8 qx[KRAW ? KSX : 1];
+    unsigned qsw = 0x7F7F7F7Fu;                      // (neutral scales unless the input is block-scaled)
+    if constexpr (KRAW) {
         const uint8_t *qrow = static_cast<const uint8_t *>(a.Q) + orow * D;
 #pragma unroll
         for (int j = 0; j < KSX; ++j) {
@@ -221,8 +228,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             const uint4 hi = *reinterpret_cast<const uint4 *>(qrow + 64 * j + 32 + 16 * hh);
             qx[j] = intx8{(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
         }
-        qsw = (D == 128 ? *reinterpret_cast<const unsigned *>(a.q_mx + orow * 4)
-                        : (unsigned)*reinterpret_cast<const unsigned short *>(a.q_mx + orow * 2)) >> (8 * hh);
+        if constexpr (MX)
+            qsw = (D == 128 ? *reinterpret_cast<const unsigned *>(a.q_mx + orow * 4)
+                            : (unsigned)*reinterpret_cast<const unsigned short *>(a.q_mx + orow * 2)) >> (8 * hh);
     }
     float c = a.scale_log2;                          // scores are exponentiated as 2^(s*c)
     if (a.q_scale) c *= a.q_scale[b * a.H + head];
@@ -307,11 +315,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
             if (i < nch) {
                 const int row = (j0 + k_row0 + i * KROWS) & (2 * TK - 1);
                 uint4 w = src[i];
-                if constexpr (MX) {
+                if constexpr (KRAW) {
                     // e4m3 as stored: 8 bytes into [row][16-byte chunk ^ (row % KCR)]
                     char *p = reinterpret_cast<char *>(Ks) + (row * KCR + ((k_ch >> 1) ^ (row & (KCR - 1)))) * 16 + (k_ch & 1) * 8;
                     *reinterpret_cast<uint2 *>(p) = make_uint2(w.x, w.y);
-                    if (k_ch == 0) Ksc[row] = w.z;
+                    if (MX && k_ch == 0) Ksc[row] = w.z;
                 } else {
                     if (FP8) w = fp8x8_to_bf16x8(make_uint2(w.x, w.y));
                     Ks[row * CH + (k_ch ^ (row & 7))] = w;
@@ -382,7 +390,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     };
     auto qk_unit_mx = [&](int u, floatx16 &s) {         // S^T of unit u, all of it
         const int krow = (u & 3) * 32 + l32;
-        const unsigned ksw = Ksc[krow] >> (8 * hh);
+        const unsigned ksw = MX ? Ksc[krow] >> (8 * hh) : 0x7F7F7F7Fu;
         floatx16 cin;
 #pragma unroll
         for (int r = 0; r < 16; ++r) cin[r] = 0.f;
@@ -464,7 +472,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     auto unit = [&](int u, floatx16 &s_cur, bool have_next, floatx16 &s_nxt) {
         unsigned pk[2][4];
         update_max(s_cur);
-        if constexpr (MX) {
+        if constexpr (KRAW) {
             if (have_next) {
                 // the K operands of unit u+1 and the first V fragments of unit u, then: a block-scaled instruction
                 // every 8 / KSX exponential steps, the V products after them
@@ -472,7 +480,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
                 uint4 kf[2 * KSX];
 #pragma unroll
                 for (int m = 0; m < 2 * KSX; ++m) kf[m] = kx_chunk(krow, m >> 1, m & 1);
-                const unsigned ksw = Ksc[krow] >> (8 * hh);
+                const unsigned ksw = MX ? Ksc[krow] >> (8 * hh) : 0x7F7F7F7Fu;
                 constexpr int PD = 3;
                 uint4 fv[2 * DC];
 #pragma unroll
@@ -552,7 +560,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_mfma_kernel(const AttnKe
     __syncthreads();
     floatx16 s_a, s_b;
     if (wave_active) {
-        if constexpr (MX) qk_unit_mx(0, s_a);
+        if constexpr (KRAW) qk_unit_mx(0, s_a);
         else {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) qk_step(0, ks, s_a);
