@@ -593,7 +593,8 @@ void attn_wide_kernel(const AttnKernelArgs a)
             const uint2 hi = *reinterpret_cast<const uint2 *>(rbase + it * RPI * OPITCH + 8);
             return make_uint4(lo.x, lo.y, hi.x, hi.y);
         };
-        constexpr int NIT = kRowsWave / RPI, BATCH = 8;
+        constexpr int NIT = kRowsWave / RPI, BATCH = NIT < 8 ? NIT : 8;   // (32 rows of 128 bytes are four stores)
+        static_assert(NIT % BATCH == 0, "whole batches of output stores");
         if (__builtin_expect(whole, 1)) {
             // reads in batches, so that their latencies overlap instead of adding up
 #pragma unroll

@@ -386,6 +386,8 @@ NARROW_BLOCK = WIDE_BLOCK + [
     (2, 8, 4, 2048, 128, 64, 1024, wl.BF16), (1, 32, 32, 2048, 128, 96, 1000, wl.BF16), (1, 4, 2, 2048, 128, 80, 1900, wl.BF16),
     (1, 8, 4, 2048, 128, 64, 1984, wl.FP8_E4M3), (1, 4, 2, 300, 64, 64, 130, wl.BF16), (3, 2, 1, 777, 128, 33, 700, wl.BF16),
     (16, 8, 2, 1024, 128, 64, 512, wl.FP8_E4M3),            # 32 kv heads x 256 rows: the tile is chosen, not forced
+    # d = 64: a wave's 32 output rows are four stores, not eight (320 rows per kv head: two whole tiles and half a one)
+    (3, 10, 2, 221, 64, 64, 61, wl.BF16), (3, 4, 1, 115, 64, 80, 2, wl.BF16), (1, 5, 1, 512, 64, 64, 64, wl.BF16),
 ]
 
 

@@ -95,6 +95,8 @@ BLOCK = [
     (1, 2, 1, 150, 64, 1, 77, wl.BF16, {}),
     # the wide kernel's 128-row tiles: a partly filled tile (2 x 40 rows), fp8 with key splits
     (3, 4, 2, 333, 128, 40, 101, wl.BF16, {}), (1, 4, 2, 4097, 128, 64, 2000, wl.FP8_E4M3, {}),
+    # ... with 128-byte rows a wave's 32 output rows are four stores: the last wave of the call ends at the buffer's end
+    (1, 2, 1, 300, 64, 64, 100, wl.BF16, {}), (2, 5, 1, 221, 64, 64, 61, wl.BF16, {"DD_TUNE_BLOCK_WIDE_ROWS": "128"}),
 ]
 
 
