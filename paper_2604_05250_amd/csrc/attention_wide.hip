@@ -2,7 +2,8 @@
 // (Eq. 3 applied bidirectionally, Sec. 2.2) -- the O(N^2)-per-step cost of a masked diffusion model.
 //
 // Why a second kernel.  With 32 query rows per wave every matrix-core instruction needs its own 1 KB
-// operand fragment from LDS, and the 128 B/clk LDS port can only just feed four SIMDs at the MFMA rate.
+// operand fragment from LDS, twice the fragment reads (and, with two workgroups per compute unit, twice the
+// tile loads) of this form; measured on a drafter call, two such waves per SIMD are slower than the one below.
 // Here one wave owns 64 query rows (two 32-row blocks) and is alone on its SIMD (up to 512 registers);
 // one workgroup = 4 waves = 256 query rows of one (batch, kv head).  Every K fragment and every V
 // fragment read from LDS feeds two MFMAs (one per block): half the LDS bytes per FLOP.
@@ -470,8 +471,9 @@ void attn_wide_kernel(const AttnKernelArgs a)
         }
     }
     // K fragment f of the unit `sub` (0/1) of a tile buffer: key 32 sub + l32, bytes 32 f + 16 hh .. +15 of its
-    // row: bf16 dims 16 f + 8 hh .. +7 (one MFMA); fp8 dims 32 f + 16 hh .. +15 (two MFMAs, 8 dims each -
-    // any split of the head dim over k-steps and lane halves will do as long as Q uses the same)
+    // row: bf16 dims 16 f + 8 hh .. +7 (one MFMA); fp8 dims 32 f + 16 hh .. +15 (half of one MFMA's operand: fragments
+    // 2 j and 2 j + 1 make up instruction j's - any split of the head dim over instructions, operand bytes and lane
+    // halves will do as long as Q uses the same)
     auto k_frag = [&](const uint4 *kb, int sub, int f) __attribute__((always_inline)) {
         return __builtin_bit_cast(intx4, *reinterpret_cast<const uint4 *>(
                    reinterpret_cast<const char *>(kb) + sub * 32 * KROWB + k_off[f]));
