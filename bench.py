@@ -38,12 +38,17 @@ KERNEL_SOURCES = ("attention_wide.hip", "attention_mfma.hip", "attention_stream.
 
 
 def kernel_source_digest():
-    """Short hash of the kernel sources: a profile records the one it was taken with."""
+    """Short hash of the kernel sources, comments and blank space left out (a comment edit is no other kernel): a
+    profile records the one it was taken with."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2604_05250_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2604_05250_amd", "csrc", name), "r", encoding="utf-8") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)           # block comments
+        text = re.sub(r"//[^\n]*", "", text)                          # line comments (no string in these files holds "//")
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:12]
 
 
