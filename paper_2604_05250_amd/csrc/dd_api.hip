@@ -87,6 +87,8 @@ int attn_block_splits(int block_len, int B, int H, int Hkv, int N, int d)
     // there is about one workgroup per compute unit.
     const int target = 256;
     long s = (target + base - 1) / base;
+    const long forced = tune("DD_TUNE_BLOCK_SPLITS", 0);
+    if (forced >= 1) s = forced;
     const long max_s = N / 128 > 1 ? N / 128 : 1;   // at least 128 keys per split
     if (s > max_s) s = max_s;
     if (s > 16) s = 16;

@@ -34,6 +34,7 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipSt
 //   DD_TUNE_BIDIR_STREAM=0/1   small bf16 verifier calls off / on the streaming kernel
 //   DD_TUNE_BLOCK_STREAM=0     drafter calls with few query rows off the streaming kernel
 //   DD_TUNE_BLOCK_WIDE=0       drafter calls with many query rows off the wide-wave kernel
+//   DD_TUNE_BLOCK_SPLITS=n     key splits of a drafter call on the streaming / MFMA kernels (still at least 128 keys each)
 //   DD_TUNE_BLOCK_WIDE_ROWS=128/256   query rows per workgroup of such a call
 //   DD_TUNE_BLOCK_WIDE_MIN_ROWS=n     query rows per kv head from which it takes that kernel
 // Returns the variable's integer value, or `dflt` when hooks are off or the variable is unset.

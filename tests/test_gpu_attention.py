@@ -407,6 +407,26 @@ def test_block_128_row_tiles(monkeypatch, B, H, Hkv, N, d, bl, bs, qk):
         assert_attention_close(got, ref, qk, f"block 128-row tiles {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk} fresh={fresh}")
 
 
+# DD_TUNE_BLOCK_SPLITS sets the number of key splits of the streaming / MFMA kernels against the library's own rule
+# (it keeps at least 128 keys per split): odd counts, short last splits, a split that is nothing but block rows.
+@pytest.mark.parametrize("stream", ["1", "0"])
+@pytest.mark.parametrize("splits", ["2", "3", "5", "7", "16"])
+def test_block_forced_key_splits(monkeypatch, stream, splits):
+    monkeypatch.setenv("DD_TUNE_BLOCK_STREAM", stream)
+    monkeypatch.setenv("DD_TUNE_BLOCK_WIDE", "0")
+    monkeypatch.setenv("DD_TUNE_BLOCK_SPLITS", splits)
+    for (B, H, Hkv, N, d, bl, bs, qk) in ((1, 2, 2, 1000, 128, 64, 500, wl.BF16), (2, 4, 2, 777, 64, 32, 745, wl.BF16),
+                                          (1, 4, 2, 2049, 128, 48, 128, wl.FP8_E4M3), (1, 2, 1, 900, 128, 16, 0, wl.F32)):
+        vd = wl.F32 if qk == wl.F32 else wl.BF16
+        cfg = wl.custom_config(B=B, H=H, Hkv=Hkv, N=N, d=d, qk_dtype=qk, v_dtype=vd, bl=bl, prompt=0, G=N)
+        cache = wl.cache_inputs(cfg, seed=N)
+        blk = wl.block_inputs(cfg, bs, 0, k_scale=cache["k_scale"])
+        got = gpu_block(cfg, blk["Qblk"], cache["Kc"], cache["Vc"], bs, blk["Kblk"], blk["Vblk"], blk["q_scale"], cache["k_scale"])
+        ref = oracle.block_attention_cached(blk["Qblk"], cache["Kc"], cache["Vc"], bs, qk, vd, blk["Kblk"], blk["Vblk"],
+                                            blk["q_scale"], cache["k_scale"])
+        assert_attention_close(got, ref, qk, f"block, {splits} key splits, stream={stream} {B}x{H}/{Hkv} N{N} d{d} bl{bl}@{bs} dtype {qk}")
+
+
 @pytest.mark.parametrize("B,H,Hkv,N,d,bl,bs,qk", BLOCK_SMALL)
 def test_block_small_shapes(B, H, Hkv, N, d, bl, bs, qk):
     vd = wl.F32 if qk == wl.F32 else wl.BF16
